@@ -1,0 +1,142 @@
+"""ctypes loader for the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg may
+import this package.  It imports nothing from the HIP binding, and the HIP binding
+imports nothing from here.
+
+``hbp_oracle.c`` holds the compact-layout builder and the fp64 SpMV definitions;
+``hbp_literal.py`` holds the paper's literal layout for tiny inputs.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hbp_oracle.c")
+_LIB = os.path.join(_HERE, "libhbp_oracle.so")
+
+ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
+    "blk_bm": (0, np.int32), "blk_bn": (1, np.int32), "slot_ptr": (2, np.int32),
+    "blk_group_ptr": (3, np.int32), "col_blk_ptr": (4, np.int32), "stripe_ptr": (5, np.int32),
+    "stripe_blk": (6, np.int32), "group_ptr": (7, np.int32), "group_slot": (8, np.int32),
+    "row_local": (9, np.uint16), "seg_len": (10, np.uint16), "col_local": (11, np.uint16),
+    "data": (12, np.float32), "add_sign": (13, np.int32),
+}
+DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "F")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, single-threaded)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        lib.oracle_csr_spmv_f64.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+        lib.oracle_csr_spmv_f64.restype = None
+        lib.oracle_hash_key.argtypes = [ctypes.c_uint32, i32, i32]
+        lib.oracle_hash_key.restype = ctypes.c_uint32
+        lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
+        lib.oracle_sample_shift.restype = i32
+        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i64, i32]
+        lib.oracle_hbp_build.restype = vp
+        lib.oracle_hbp_free.argtypes = [vp]
+        lib.oracle_hbp_free.restype = None
+        lib.oracle_hbp_dims.argtypes = [vp, vp]
+        lib.oracle_hbp_dims.restype = None
+        lib.oracle_hbp_copy.argtypes = [vp, i32, vp]
+        lib.oracle_hbp_copy.restype = i64
+        lib.oracle_hbp_spmv.argtypes = [vp, vp, vp, vp]
+        lib.oracle_hbp_spmv.restype = None
+        lib.oracle_hbp_to_coo.argtypes = [vp, vp, vp, vp]
+        lib.oracle_hbp_to_coo.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data
+
+
+def csr_spmv_f64(ptr, col, val, x):
+    """(y_ref, s_abs): fp64 CSR SpMV by the plain definition and the per-row sum of
+    absolute products."""
+    n_rows = len(ptr) - 1
+    y = np.empty(n_rows, dtype=np.float64)
+    s = np.empty(n_rows, dtype=np.float64)
+    _load().oracle_csr_spmv_f64(_p(ptr), _p(col), _p(val), _p(x), n_rows, _p(y), _p(s))
+    return y, s
+
+
+def hash_key(n: int, a: int, R: int) -> int:
+    return int(_load().oracle_hash_key(int(n), int(a), int(R)))
+
+
+def sample_shift(ptr, col, n_rows: int, C: int) -> int:
+    return int(_load().oracle_sample_shift(_p(ptr), _p(col), int(n_rows), int(C)))
+
+
+class OracleHbp:
+    """The compact HBP layout built by the C oracle; arrays are numpy copies."""
+
+    def __init__(self, ptr, col, val, n_rows, n_cols, R=512, C=4096, W=64, hash_shift=-1,
+                 num_workers=1, fixed_q8=128):
+        lib = _load()
+        self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(n_rows), int(n_cols), int(R), int(C), int(W),
+                                       int(hash_shift), int(num_workers), int(fixed_q8))
+        if not self._h:
+            raise ValueError("oracle_hbp_build rejected the parameters")
+        dims = np.zeros(len(DIMS), dtype=np.int64)
+        lib.oracle_hbp_dims(self._h, _p(dims))
+        for k, v in zip(DIMS, dims):
+            setattr(self, k, int(v))
+        self._cache = {}
+
+    def array(self, name: str) -> np.ndarray:
+        if name not in self._cache:
+            which, dt = ARRAYS[name]
+            lib = _load()
+            nbytes = lib.oracle_hbp_copy(self._h, which, None)
+            out = np.empty(nbytes // np.dtype(dt).itemsize, dtype=dt)
+            if nbytes:
+                lib.oracle_hbp_copy(self._h, which, _p(out))
+            self._cache[name] = out
+        return self._cache[name]
+
+    def spmv(self, x):
+        """(y, partial) through the layout (Algorithm 3 walk + combine), fp64."""
+        partial = np.zeros(max(self.S, 1), dtype=np.float64)
+        y = np.zeros(self.n_rows, dtype=np.float64)
+        _load().oracle_hbp_spmv(self._h, _p(x), _p(partial), _p(y))
+        return y, partial[: self.S]
+
+    def to_coo(self):
+        rows = np.full(max(self.nnz, 1), -1, dtype=np.int64)
+        cols = np.full(max(self.nnz, 1), -1, dtype=np.int64)
+        vals = np.zeros(max(self.nnz, 1), dtype=np.float32)
+        _load().oracle_hbp_to_coo(self._h, _p(rows), _p(cols), _p(vals))
+        return rows[: self.nnz], cols[: self.nnz], vals[: self.nnz]
+
+    def close(self):
+        if self._h:
+            _load().oracle_hbp_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,272 @@
+"""Pins for the oracle's HBP layout: the hand-worked example, the HBP->COO round trip,
+brute-force recounts on tiny inputs, closed forms and special cases (W = 1, one block)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle.hbp_literal import LiteralHbp
+from workloads import make_config, random_csr, worked_example_8x8
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_8x8.json")
+
+
+def build(oracle, m, **kw):
+    return oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, **kw)
+
+
+def coo_set(rows, cols, vals):
+    bits = np.asarray(vals, dtype=np.float32).view(np.uint32).astype(np.int64)
+    return sorted(zip(np.asarray(rows).tolist(), np.asarray(cols).tolist(), bits.tolist()))
+
+
+def csr_coo(m):
+    rows = np.repeat(np.arange(m.n_rows), np.diff(m.ptr))
+    return coo_set(rows, m.col, m.val)
+
+
+# ---------------------------------------------------------------- worked example
+
+def test_worked_example_literal():
+    g = json.load(open(GOLDEN))
+    m = worked_example_8x8()
+    L = LiteralHbp(m.ptr, m.col, m.val, 8, 8, g["R"], g["C"], g["W"], g["a"])
+    lit = g["literal"]
+    for name in ("output_hash", "zero_row", "begin_ptr", "begin_nnz", "col", "data", "add_sign"):
+        assert list(getattr(L, name)) == lit[name], name
+    y, partials = L.spmv(m.x)
+    assert y.tolist() == g["y"]
+    assert partials == lit["partials"]
+
+
+def test_worked_example_compact(oracle):
+    g = json.load(open(GOLDEN))
+    m = worked_example_8x8()
+    h = build(oracle, m, R=g["R"], C=g["C"], W=g["W"], hash_shift=g["a"])
+    for name, want in g["compact"].items():
+        if name.startswith("_") or name == "partial":
+            continue
+        assert h.array(name).tolist() == want, name
+    y, partial = h.spmv(m.x)
+    assert y.tolist() == g["y"]
+    assert partial.tolist() == g["compact"]["partial"]
+
+
+# ---------------------------------------------------------------- brute force helpers
+
+def brute_segments(m, R, C):
+    """{(bn, bm): [(local row, [csr positions])]} by direct definition."""
+    blocks = {}
+    for r in range(m.n_rows):
+        per_bn = {}
+        for j in range(m.ptr[r], m.ptr[r + 1]):
+            per_bn.setdefault(int(m.col[j]) // C, []).append(j)
+        for bn, js in per_bn.items():
+            blocks.setdefault((bn, r // R), []).append((r % R, js))
+    return blocks
+
+
+CASES = [
+    # rows, cols, density, seed, R, C, W, shift
+    (40, 40, 0.2, 1, 8, 8, 4, -1),
+    (77, 53, 0.3, 2, 16, 10, 4, 0),
+    (64, 200, 0.15, 3, 64, 32, 8, 1),
+    (129, 65, 0.5, 4, 32, 16, 3, 2),
+    (30, 300, 0.4, 5, 7, 50, 64, -1),
+    (200, 30, 0.1, 6, 512, 4096, 64, -1),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_layout_against_brute_force(oracle, case):
+    nr, nc, dens, seed, R, C, W, shift = case
+    m = random_csr(nr, nc, dens, seed, empty_row_frac=0.15)
+    h = build(oracle, m, R=R, C=C, W=W, hash_shift=shift)
+    a = h.a
+    blocks = brute_segments(m, R, C)
+    order = sorted(blocks)                                     # (bn, bm): column-major
+    assert h.B == len(order) and h.nnz == m.nnz
+    assert list(zip(h.array("blk_bn").tolist(), h.array("blk_bm").tolist())) == order
+    slot_ptr, gptr_blk = h.array("slot_ptr"), h.array("blk_group_ptr")
+    row_local, seg_len = h.array("row_local"), h.array("seg_len")
+    group_ptr, group_slot = h.array("group_ptr"), h.array("group_slot")
+    col_local, data, add_sign = h.array("col_local"), h.array("data"), h.array("add_sign")
+    assert slot_ptr[0] == 0 and slot_ptr[-1] == h.S == sum(len(v) for v in blocks.values())
+    g = 0
+    for b, key in enumerate(order):
+        segs = blocks[key]
+        s0, s1 = slot_ptr[b], slot_ptr[b + 1]
+        assert s1 - s0 == len(segs)
+        # slots: ascending (hash key, local row), uniquely determined
+        want = sorted(segs, key=lambda t: (oracle.hash_key(len(t[1]), a, R), t[0]))
+        assert row_local[s0:s1].tolist() == [q for q, _ in want]
+        assert seg_len[s0:s1].tolist() == [len(js) for _, js in want]
+        assert gptr_blk[b] == g
+        for w0 in range(0, len(want), W):
+            lanes = want[w0:w0 + W]
+            assert group_slot[g] == s0 + w0
+            pos = group_ptr[g]
+            # round-by-round (column-major) fill, rows keep CSR order
+            for k in range(max(len(js) for _, js in lanes)):
+                for li, (q, js) in enumerate(lanes):
+                    if k < len(js):
+                        assert col_local[pos] == m.col[js[k]] - key[0] * C
+                        assert data[pos] == m.val[js[k]]
+                        # closed form of add_sign: elements after it in this round plus
+                        # elements before it in the next round, plus one
+                        if k + 1 == len(js):
+                            assert add_sign[pos] == -1
+                        else:
+                            after = sum(1 for _, j2 in lanes[li + 1:] if k < len(j2))
+                            before = sum(1 for _, j2 in lanes[:li] if k + 1 < len(j2))
+                            assert add_sign[pos] == after + before + 1
+                        pos += 1
+            g += 1
+            assert group_ptr[g] == pos
+    assert g == h.G and gptr_blk[-1] == g and group_slot[-1] == h.S and group_ptr[-1] == m.nnz
+    # column index of blocks and the combine index
+    cbp = h.array("col_blk_ptr")
+    for bn in range(h.NBC):
+        assert list(range(cbp[bn], cbp[bn + 1])) == [i for i, k in enumerate(order) if k[0] == bn]
+    sp, sb = h.array("stripe_ptr"), h.array("stripe_blk")
+    for bm in range(h.NBR):
+        assert sb[sp[bm]:sp[bm + 1]].tolist() == [i for i, k in enumerate(order) if k[1] == bm]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_round_trip_and_spmv(oracle, case):
+    nr, nc, dens, seed, R, C, W, shift = case
+    m = random_csr(nr, nc, dens, seed, empty_row_frac=0.15)
+    h = build(oracle, m, R=R, C=C, W=W, hash_shift=shift)
+    assert coo_set(*h.to_coo()) == csr_coo(m)                    # exact (row, col, value bits) multiset
+    y_ref, s = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    y, partial = h.spmv(m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-13 * s)
+    assert np.all(y[np.diff(m.ptr) == 0] == 0)
+
+
+@pytest.mark.parametrize("case", CASES[:4])
+def test_literal_and_compact_agree(oracle, case):
+    nr, nc, dens, seed, R, C, W, shift = case
+    m = random_csr(nr, nc, dens, seed, empty_row_frac=0.15)
+    h = build(oracle, m, R=R, C=C, W=W, hash_shift=shift)
+    L = LiteralHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R, C, W, h.a)
+    y_lit, partials = L.spmv(m.x)
+    y_ref, s = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    assert np.all(np.abs(y_lit - y_ref) <= 1e-13 * s)
+    # compact slots = literal slots with the empty rows dropped, block by block
+    row_local, slot_ptr = h.array("row_local"), h.array("slot_ptr")
+    _, partial = h.spmv(m.x)
+    for b in range(h.B):
+        bm, bn = h.array("blk_bm")[b], h.array("blk_bn")[b]
+        blk = bm * L.NBC + bn
+        lo, hi = L.slot_base[blk], L.slot_base[blk + 1]
+        kept = [L.output_hash[s] for s in range(lo, hi) if L.zero_row[s] != -1]
+        assert row_local[slot_ptr[b]:slot_ptr[b + 1]].tolist() == kept
+        for s in range(slot_ptr[b], slot_ptr[b + 1]):
+            assert abs(partial[s] - partials[bm][bn][row_local[s]]) <= 1e-12 * max(1.0, abs(partial[s]))
+    # literal array lengths the paper states: add_sign = nnz; zero_row, output_hash = rows x column blocks
+    assert len(L.add_sign) == m.nnz
+    assert len(L.zero_row) == len(L.output_hash) == m.n_rows * L.NBC
+
+
+def test_w1_blocks_are_csr_order(oracle):
+    """W = 1: a group is one row, so each block's col/data are its rows' CSR runs in slot order
+    and add_sign is 1 inside a row, -1 at its end."""
+    m = random_csr(90, 70, 0.25, 11, empty_row_frac=0.1)
+    R, C = 16, 32
+    h = build(oracle, m, R=R, C=C, W=1, hash_shift=-1)
+    blocks = brute_segments(m, R, C)
+    pos = 0
+    for b in range(h.B):
+        key = (int(h.array("blk_bn")[b]), int(h.array("blk_bm")[b]))
+        by_row = dict(blocks[key])
+        for s in range(h.array("slot_ptr")[b], h.array("slot_ptr")[b + 1]):
+            js = by_row[int(h.array("row_local")[s])]
+            assert h.array("data")[pos:pos + len(js)].tolist() == m.val[js].tolist()
+            assert h.array("add_sign")[pos:pos + len(js)].tolist() == [1] * (len(js) - 1) + [-1]
+            pos += len(js)
+    assert pos == m.nnz
+
+
+def test_single_block_equal_rows_reproduces_csr(oracle):
+    """One block, W = 1, all rows equally long: the reorder is the identity and col/data are
+    the CSR arrays verbatim."""
+    rows, n = 25, 6
+    rng = np.random.default_rng(5)
+    col = np.concatenate([np.sort(rng.choice(40, n, replace=False)) for _ in range(rows)]).astype(np.int32)
+    ptr = (np.arange(rows + 1) * n).astype(np.int32)
+    val = rng.standard_normal(rows * n).astype(np.float32)
+    h = oracle.OracleHbp(ptr, col, val, rows, 40, R=32, C=64, W=1)
+    assert h.B == 1 and h.array("row_local").tolist() == list(range(rows))
+    assert np.array_equal(h.array("col_local"), col.astype(np.uint16))
+    assert np.array_equal(h.array("data"), val)
+
+
+def test_equal_rows_any_w_is_ell(oracle):
+    """All rows equally long in one block: a full group is a column-major (ELL) tile."""
+    rows, n, W = 16, 5, 8
+    ptr = (np.arange(rows + 1) * n).astype(np.int32)
+    col = np.tile(np.arange(n), rows).astype(np.int32) * 2
+    val = np.arange(rows * n, dtype=np.float32)
+    h = oracle.OracleHbp(ptr, col, val, rows, 16, R=16, C=16, W=W)
+    want = val.reshape(2, W, n).transpose(0, 2, 1).ravel()
+    assert np.array_equal(h.array("data"), want)
+    assert set(h.array("add_sign").tolist()) == {W, -1}
+
+
+def test_schedule_split(oracle):
+    m = random_csr(300, 300, 0.05, 3)
+    for P, q8 in [(1, 128), (4, 192), (7, 255), (64, 256), (5, 0)]:
+        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8)
+        assert h.P == P and h.F == (h.B * q8) // (256 * P)
+        assert P * h.F <= h.B                                     # fixed lists are disjoint prefixes
+        # equal number of fixed blocks per worker; everything else is competitive
+
+
+def test_hash_groups_similar_rows(oracle):
+    """Diagnostic of Section 4.1: the mean per-group standard deviation of row lengths does
+    not grow when rows are put in hash order (it shrinks on varied inputs)."""
+    m = make_config(5, scale=0.002)
+    R, C, W = 512, 256, 32
+    h = build(oracle, m, R=R, C=C, W=W)
+    seg_len, row_local, slot_ptr = h.array("seg_len"), h.array("row_local"), h.array("slot_ptr")
+    after, before = [], []
+    for b in range(h.B):
+        ln = seg_len[slot_ptr[b]:slot_ptr[b + 1]].astype(np.float64)
+        if len(ln) < 2 * W:
+            continue
+        by_row = ln[np.argsort(row_local[slot_ptr[b]:slot_ptr[b + 1]], kind="stable")]
+        for g0 in range(0, len(ln) - W + 1, W):
+            after.append(ln[g0:g0 + W].std())
+            before.append(by_row[g0:g0 + W].std())
+    assert len(after) > 10 and np.mean(after) < np.mean(before)
+
+
+def test_rejects_bad_parameters(oracle):
+    m = worked_example_8x8()
+    for kw in (dict(R=0), dict(C=0), dict(W=0), dict(R=70000), dict(C=70000), dict(num_workers=0)):
+        with pytest.raises(ValueError):
+            build(oracle, m, **{**dict(R=4, C=4, W=2), **kw})
+
+
+@pytest.mark.parametrize("number,scale,R,C", [(1, 1.0, 512, 4096), (2, 0.002, 512, 4096), (3, 2**-8, 256, 1024),
+                                              (4, 2**-9, 512, 2048), (5, 0.002, 512, 4096)])
+def test_configs_small_scale(oracle, number, scale, R, C):
+    m = make_config(number, scale)
+    m.check()
+    h = build(oracle, m, R=R, C=C, W=64)
+    r, c, v = h.to_coo()
+    order = np.lexsort((c, r))
+    rows = np.repeat(np.arange(m.n_rows), np.diff(m.ptr))
+    assert np.array_equal(r[order], rows) and np.array_equal(c[order], m.col)
+    assert np.array_equal(v[order].view(np.uint32), m.val.view(np.uint32))
+    y_ref, s = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    y, _ = h.spmv(m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-12 * s)
+    # per-row segment lengths add up to the row length
+    tot = np.zeros(m.n_rows, dtype=np.int64)
+    bm = np.repeat(h.array("blk_bm"), np.diff(h.array("slot_ptr")))
+    np.add.at(tot, bm.astype(np.int64) * R + h.array("row_local"), h.array("seg_len"))
+    assert np.array_equal(tot, np.diff(m.ptr))
