@@ -1,0 +1,164 @@
+/*
+ * hbp.h - C ABI of the MI355X (gfx950) Hash-based Partition (HBP) SpMV library.
+ *
+ * The library implements the data-parallel hot path of "A Nonlinear Hash-based
+ * Optimization Method for SpMV on GPUs": the hash-driven preprocessing that turns a CSR
+ * matrix into the HBP format (Sections 3.1-3.2, Algorithm 2) and the two-step
+ * y = A x with mixed fixed/competitive block scheduling (Section 3.3, Algorithm 3,
+ * Fig. 1).  Every step runs in hand-written HIP kernels on the current device.
+ *
+ * Conventions
+ *   - Pointers marked DEVICE are device addresses on the GPU that is current when the
+ *     call is made; pointers marked HOST are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function returns HBP_OK (0) or a negative hbp_status; nothing throws or
+ *     aborts across this boundary.  hbp_status_string() names a status.
+ *   - The caller owns csr_*, x and y.  A handle owns all of its device arrays and
+ *     copies the matrix values, so the CSR arrays may be freed once hbp_build returns.
+ *
+ * Layout held by a handle ("compact" HBP; the paper's arrays in parentheses)
+ *   Blocks are R rows x C columns.  Only blocks with at least one nonzero are kept,
+ *   listed column-major (column block bn ascending, then row block bm): the order in
+ *   which Section 3.3 hands blocks of one column to one worker.  Inside a block only
+ *   rows with a nonzero in it own a slot; slots are in ascending (hash key, local row)
+ *   order.  W consecutive slots of a block are a group; a group's nonzeros are stored
+ *   round by round (round k holds the k-th nonzero of every row that still has one).
+ *     blk_bm, blk_bn      [B]      block coordinates
+ *     slot_ptr            [B+1]    first slot of each block
+ *     blk_group_ptr       [B+1]    first group of each block
+ *     col_blk_ptr         [NBC+1]  first block of each block column
+ *     stripe_ptr          [NBR+1]  per row block, range into stripe_blk
+ *     stripe_blk          [B]      blocks of one row block, bn ascending (combine index)
+ *     group_ptr           [G+1]    position of a group's first nonzero   (begin_ptr)
+ *     group_slot          [G+1]    first slot of a group
+ *     row_local   u16     [S]      slot -> row inside its block          (output_hash)
+ *     seg_len     u16     [S]      nonzeros of that row inside the block (add_sign is
+ *                                  derived from these at run time)
+ *     col_local   u16     [nnz]    column inside the block               (col)
+ *     data        f32     [nnz]    values, bit-for-bit copies            (data)
+ *   begin_nnz of a block is group_ptr[blk_group_ptr[b]]; zero_row is not stored because
+ *   empty rows own no slot.
+ */
+#ifndef HBP_H
+#define HBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hbp_handle_s *hbp_handle_t;
+
+typedef enum {
+    HBP_OK = 0,
+    HBP_ERR_INVALID_ARGUMENT = -1,   /* null pointer, non-positive size, parameter out of range */
+    HBP_ERR_BAD_CSR_PTR = -2,        /* csr_ptr[0] != 0, decreasing, or beyond nnz */
+    HBP_ERR_BAD_CSR_COL = -3,        /* column < 0, >= n_cols, or not strictly ascending in a row */
+    HBP_ERR_TOO_LARGE = -4,          /* nnz or NBR*NBC beyond the supported range */
+    HBP_ERR_OUT_OF_MEMORY = -5,
+    HBP_ERR_HIP = -6,                /* a HIP runtime call failed; see hbp_last_hip_error() */
+    HBP_ERR_INTERNAL = -7
+} hbp_status;
+
+/* flags for hbp_params_t.flags */
+#define HBP_FLAG_VALIDATE 1u /* check column order/range of the CSR input during the build */
+
+/* Build parameters.  Block sizes follow Section 3.1 (the paper derives 4096 columns from
+ * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is
+ * staged in the 160 KB LDS of a gfx950 compute unit as fp32. */
+typedef struct {
+    int32_t rows_per_block;    /* R, 1..8192; 0 = default 512                                   */
+    int32_t cols_per_block;    /* C, 1..32768; 0 = default 4096                                 */
+    int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
+    int32_t num_workers;       /* P, persistent workgroups the schedule is built for; 0 = device default */
+    int32_t fixed_fraction_q8; /* share of blocks pre-assigned to workers, in 1/256; -1 = default */
+    int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
+    int32_t claim_chunk;       /* consecutive blocks taken per competitive ticket; 0 = default  */
+    uint32_t flags;            /* HBP_FLAG_*                                                    */
+} hbp_params_t;
+
+typedef struct {
+    int64_t n_rows, n_cols, nnz;
+    int32_t rows_per_block, cols_per_block, group_width;
+    int32_t hash_shift;          /* a (sampled or given); c = 2^a                               */
+    int32_t hash_b;              /* b = d = max(1, R / 9)                                       */
+    int64_t row_blocks, col_blocks;       /* NBR, NBC                                           */
+    int64_t blocks, slots, groups;        /* B, S, G                                            */
+    int32_t num_workers;         /* P                                                           */
+    int32_t fixed_per_worker;    /* F = floor(B * fixed_fraction_q8 / (256 P))                   */
+    int32_t claim_chunk;
+    int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
+    int64_t bytes_layout;        /* device bytes of all layout arrays                           */
+    int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
+    int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
+    double build_ms;             /* wall time of hbp_build, allocation and synchronisation included */
+} hbp_info_t;
+
+/* ids for hbp_export */
+typedef enum {
+    HBP_ARRAY_BLK_BM = 0, HBP_ARRAY_BLK_BN = 1, HBP_ARRAY_SLOT_PTR = 2, HBP_ARRAY_BLK_GROUP_PTR = 3,
+    HBP_ARRAY_COL_BLK_PTR = 4, HBP_ARRAY_STRIPE_PTR = 5, HBP_ARRAY_STRIPE_BLK = 6, HBP_ARRAY_GROUP_PTR = 7,
+    HBP_ARRAY_GROUP_SLOT = 8, HBP_ARRAY_ROW_LOCAL = 9, HBP_ARRAY_SEG_LEN = 10, HBP_ARRAY_COL_LOCAL = 11,
+    HBP_ARRAY_DATA = 12,
+    HBP_ARRAY_ADD_SIGN = 13, /* int32 [nnz], derived on the device from seg_len when exported   */
+    HBP_ARRAY_PARTIAL = 14   /* float [S], per-slot partial sums left by the last hbp_spmv      */
+} hbp_array_id;
+
+/* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */
+int hbp_default_params(hbp_params_t *params /* HOST */);
+
+/* Preprocessing: CSR -> HBP (Section 3.2: sampling of the shift a, data preparation of
+ * Algorithm 2, hash reorder, format conversion; Section 3.3: fixed/competitive split).
+ *   csr_ptr DEVICE int32 [n_rows+1], csr_ptr[0] = 0, non-decreasing;
+ *   csr_col DEVICE int32 [nnz], strictly ascending inside each row, in [0, n_cols);
+ *   csr_val DEVICE float [nnz];  params HOST or NULL for defaults;  *out HOST.
+ * Runs on `stream`, synchronises it, and returns with the handle complete.  With
+ * HBP_FLAG_VALIDATE a malformed column array yields HBP_ERR_BAD_CSR_COL; without it
+ * out-of-range columns are still detected (never dereferenced), order is not checked.
+ * nnz must be below 2^31 - 64 and NBR*NBC at most 2^27.  On error *out is NULL. */
+int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+              int64_t n_rows, int64_t n_cols, const hbp_params_t *params, void *stream, hbp_handle_t *out);
+
+/* y = A x, exactly (alpha 1, beta 0; Algorithm 1 assigns).  Two-step SpMV of Fig. 1:
+ * the SpMV part (Algorithm 3 per block; workers take their fixed blocks, then claim
+ * competitive ones through an atomic ticket counter, Section 3.3) writes one partial sum
+ * per slot; the combine part adds the partial sums of each row and writes y.
+ *   x DEVICE float [n_cols], read only;  y DEVICE float [n_rows], overwritten.
+ * Asynchronous on `stream`.  A handle supports one SpMV in flight at a time: calls on the
+ * same stream serialise by themselves; calls on different streams must be ordered by the
+ * caller (they share the partial-sum buffer and the ticket counter). */
+int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream);
+
+/* Frees the handle and its device arrays (synchronises the device first). NULL is allowed. */
+int hbp_free(hbp_handle_t h);
+
+/* Sizes, parameters and byte counts of a handle.  *info HOST. */
+int hbp_get_info(hbp_handle_t h, hbp_info_t *info);
+
+/* Copies one layout array to host memory (synchronous).  With host_dst NULL only the size
+ * is reported.  *bytes_out HOST receives the array's size in bytes; capacity is the size
+ * of host_dst, HBP_ERR_INVALID_ARGUMENT if it is too small. */
+int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_t *bytes_out);
+
+/* Times `iters` back-to-back hbp_spmv calls with HIP events recorded on `stream` around
+ * each of the two kernels.  HOST outputs: average milliseconds of the SpMV-part kernel,
+ * of the combine kernel, and of a whole call (event before the first kernel to event
+ * after the second).  Synchronises the stream. */
+int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters,
+                   float *ms_part, float *ms_combine, float *ms_total);
+
+/* In-repo CSR baselines (Algorithm 1).  kind 0: one thread per row; kind 1: one wavefront
+ * per row with a cross-lane reduction.  All pointers DEVICE; y overwritten. */
+int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+                 const float *x, float *y, int64_t n_rows, void *stream);
+
+const char *hbp_status_string(int status);
+/* hipError_t of the most recent HBP_ERR_HIP on this thread, as int. */
+int hbp_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBP_H */

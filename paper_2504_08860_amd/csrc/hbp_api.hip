@@ -1,0 +1,250 @@
+// C ABI of libhbp: argument checking, handle lifetime, export and timing hooks.
+#include "hbp_internal.h"
+
+#include <chrono>
+#include <cstring>
+#include <new>
+
+namespace hbp {
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+}  // namespace hbp
+
+namespace {
+
+struct DeviceGuard {  // makes the handle's device current for the duration of a call
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int device)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != device && hipSetDevice(device) != hipSuccess) ok = false;
+    }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+void free_arrays(hbp_handle_s *h)
+{
+    void *ptrs[] = {h->blk_bm, h->blk_bn, h->slot_ptr, h->blk_group_ptr, h->col_blk_ptr, h->stripe_ptr, h->stripe_blk,
+                    h->group_ptr, h->group_slot, h->row_local, h->seg_len, h->col_local, h->data, h->partial, h->ticket};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+}  // namespace
+
+extern "C" {
+
+int hbp_default_params(hbp_params_t *p)
+{
+    if (!p) return HBP_ERR_INVALID_ARGUMENT;
+    p->rows_per_block = 512;
+    p->cols_per_block = 4096;
+    p->group_width = 64;
+    p->num_workers = 0;
+    p->fixed_fraction_q8 = -1;
+    p->hash_shift = -1;
+    p->claim_chunk = 0;
+    p->flags = HBP_FLAG_VALIDATE;
+    return HBP_OK;
+}
+
+int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, int64_t n_rows, int64_t n_cols,
+              const hbp_params_t *params, void *stream, hbp_handle_t *out)
+{
+    if (!out) return HBP_ERR_INVALID_ARGUMENT;
+    *out = nullptr;
+    if (!csr_ptr || !csr_col || !csr_val || n_rows < 1 || n_cols < 1) return HBP_ERR_INVALID_ARGUMENT;
+    if (n_rows >= (int64_t(1) << 31) - 1 || n_cols >= (int64_t(1) << 31) - 1) return HBP_ERR_TOO_LARGE;
+    hbp_params_t p;
+    hbp_default_params(&p);
+    if (params) p = *params;
+    if (p.rows_per_block == 0) p.rows_per_block = 512;
+    if (p.cols_per_block == 0) p.cols_per_block = 4096;
+    if (p.group_width == 0) p.group_width = 64;
+    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 128;
+    if (p.claim_chunk == 0) p.claim_chunk = 1;
+    if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
+        p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > (1 << 20) ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1)
+        return HBP_ERR_INVALID_ARGUMENT;
+
+    const auto t0 = std::chrono::steady_clock::now();
+    hbp_handle_s *h = new (std::nothrow) hbp_handle_s;
+    if (!h) return HBP_ERR_OUT_OF_MEMORY;
+    std::memset(h, 0, sizeof *h);
+    if (hipGetDevice(&h->device) != hipSuccess) { delete h; return HBP_ERR_HIP; }
+    h->n_rows = n_rows; h->n_cols = n_cols;
+    h->R = p.rows_per_block; h->C = p.cols_per_block; h->W = p.group_width;
+    h->NBR = (n_rows + h->R - 1) / h->R;
+    h->NBC = (n_cols + h->C - 1) / h->C;
+    h->claim_chunk = p.claim_chunk;
+    int rc = HBP_OK;
+    if (h->NBR * h->NBC > hbp::kMaxDense) rc = HBP_ERR_TOO_LARGE;
+    int32_t threads = 0, workers = 0;
+    if (rc == HBP_OK) rc = hbp::default_workers(h->device, h->C, &threads, &workers);
+    if (rc == HBP_OK) {
+        h->threads = threads;
+        h->P = p.num_workers > 0 ? p.num_workers : workers;
+        rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
+    }
+    if (rc != HBP_OK) {
+        (void)hipStreamSynchronize((hipStream_t)stream);
+        free_arrays(h);
+        delete h;
+        return rc;
+    }
+    // Section 3.3: the first P*F list entries are fixed (F per worker), the rest competitive
+    h->F = (int32_t)((h->B * (int64_t)p.fixed_fraction_q8) / (256 * (int64_t)h->P));
+    h->build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *out = h;
+    return HBP_OK;
+}
+
+int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream)
+{
+    if (!h || !x || !y) return HBP_ERR_INVALID_ARGUMENT;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return HBP_ERR_HIP;
+    int rc = hbp::launch_spmv_part(h, x, (hipStream_t)stream);
+    if (rc != HBP_OK) return rc;
+    return hbp::launch_combine(h, y, (hipStream_t)stream);
+}
+
+int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters, float *ms_part, float *ms_combine,
+                   float *ms_total)
+{
+    if (!h || !x || !y || iters < 1 || iters > 100000) return HBP_ERR_INVALID_ARGUMENT;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return HBP_ERR_HIP;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t ev[3];
+    for (auto &e : ev) HBP_HIP(hipEventCreate(&e));
+    double part = 0, comb = 0, total = 0;
+    int rc = HBP_OK;
+    for (int i = 0; i < iters && rc == HBP_OK; i++) {
+        HBP_HIP(hipEventRecord(ev[0], st));
+        rc = hbp::launch_spmv_part(h, x, st);
+        HBP_HIP(hipEventRecord(ev[1], st));
+        if (rc == HBP_OK) rc = hbp::launch_combine(h, y, st);
+        HBP_HIP(hipEventRecord(ev[2], st));
+        HBP_HIP(hipEventSynchronize(ev[2]));
+        float a = 0, b = 0, c = 0;
+        HBP_HIP(hipEventElapsedTime(&a, ev[0], ev[1]));
+        HBP_HIP(hipEventElapsedTime(&b, ev[1], ev[2]));
+        HBP_HIP(hipEventElapsedTime(&c, ev[0], ev[2]));
+        part += a; comb += b; total += c;
+    }
+    for (auto &e : ev) (void)hipEventDestroy(e);
+    if (rc != HBP_OK) return rc;
+    if (ms_part) *ms_part = (float)(part / iters);
+    if (ms_combine) *ms_combine = (float)(comb / iters);
+    if (ms_total) *ms_total = (float)(total / iters);
+    return HBP_OK;
+}
+
+int hbp_free(hbp_handle_t h)
+{
+    if (!h) return HBP_OK;
+    DeviceGuard guard(h->device);
+    (void)hipDeviceSynchronize();
+    free_arrays(h);
+    delete h;
+    return HBP_OK;
+}
+
+int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
+{
+    if (!h || !info) return HBP_ERR_INVALID_ARGUMENT;
+    std::memset(info, 0, sizeof *info);
+    info->n_rows = h->n_rows; info->n_cols = h->n_cols; info->nnz = h->nnz;
+    info->rows_per_block = h->R; info->cols_per_block = h->C; info->group_width = h->W;
+    info->hash_shift = h->a;
+    info->hash_b = h->R / 9 > 0 ? h->R / 9 : 1;
+    info->row_blocks = h->NBR; info->col_blocks = h->NBC;
+    info->blocks = h->B; info->slots = h->S; info->groups = h->G;
+    info->num_workers = h->P; info->fixed_per_worker = h->F; info->claim_chunk = h->claim_chunk;
+    info->threads_per_worker = h->threads;
+    const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
+    const int64_t grp = 4 * 2 * (h->G + 1);
+    info->bytes_layout = blk + grp + 2 * 2 * h->S + 6 * h->nnz;
+    // SpMV part: col + data per nonzero, seg_len per slot, both group arrays, the block arrays it
+    // reads (blk_bn, blk_group_ptr, col_blk_ptr), x once, one partial sum written per slot.
+    info->bytes_spmv_part = 6 * h->nnz + 2 * h->S + grp + 4 * (2 * (h->B + 1) + h->NBC + 1) + 4 * h->n_cols + 4 * h->S;
+    // combine: partial sum + row_local per slot, stripe index and slot_ptr, y written once.
+    info->bytes_combine = 6 * h->S + 4 * ((h->NBR + 1) + 2 * h->B + 1) + 4 * h->n_rows;
+    info->build_ms = h->build_ms;
+    return HBP_OK;
+}
+
+int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_t *bytes_out)
+{
+    if (!h) return HBP_ERR_INVALID_ARGUMENT;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return HBP_ERR_HIP;
+    const void *src = nullptr;
+    size_t bytes = 0;
+    switch (which) {
+    case HBP_ARRAY_BLK_BM: src = h->blk_bm; bytes = 4 * (size_t)h->B; break;
+    case HBP_ARRAY_BLK_BN: src = h->blk_bn; bytes = 4 * (size_t)h->B; break;
+    case HBP_ARRAY_SLOT_PTR: src = h->slot_ptr; bytes = 4 * (size_t)(h->B + 1); break;
+    case HBP_ARRAY_BLK_GROUP_PTR: src = h->blk_group_ptr; bytes = 4 * (size_t)(h->B + 1); break;
+    case HBP_ARRAY_COL_BLK_PTR: src = h->col_blk_ptr; bytes = 4 * (size_t)(h->NBC + 1); break;
+    case HBP_ARRAY_STRIPE_PTR: src = h->stripe_ptr; bytes = 4 * (size_t)(h->NBR + 1); break;
+    case HBP_ARRAY_STRIPE_BLK: src = h->stripe_blk; bytes = 4 * (size_t)h->B; break;
+    case HBP_ARRAY_GROUP_PTR: src = h->group_ptr; bytes = 4 * (size_t)(h->G + 1); break;
+    case HBP_ARRAY_GROUP_SLOT: src = h->group_slot; bytes = 4 * (size_t)(h->G + 1); break;
+    case HBP_ARRAY_ROW_LOCAL: src = h->row_local; bytes = 2 * (size_t)h->S; break;
+    case HBP_ARRAY_SEG_LEN: src = h->seg_len; bytes = 2 * (size_t)h->S; break;
+    case HBP_ARRAY_COL_LOCAL: src = h->col_local; bytes = 2 * (size_t)h->nnz; break;
+    case HBP_ARRAY_DATA: src = h->data; bytes = 4 * (size_t)h->nnz; break;
+    case HBP_ARRAY_ADD_SIGN: bytes = 4 * (size_t)h->nnz; break;
+    case HBP_ARRAY_PARTIAL: src = h->partial; bytes = 4 * (size_t)h->S; break;
+    default: return HBP_ERR_INVALID_ARGUMENT;
+    }
+    if (bytes_out) *bytes_out = bytes;
+    if (!host_dst) return HBP_OK;
+    if (capacity < bytes) return HBP_ERR_INVALID_ARGUMENT;
+    if (bytes == 0) return HBP_OK;
+    HBP_HIP(hipDeviceSynchronize());
+    if (which == HBP_ARRAY_ADD_SIGN) {
+        int32_t *tmp = nullptr;
+        HBP_HIP(hipMalloc((void **)&tmp, bytes));
+        int rc = hbp::derive_add_sign(h, tmp, nullptr);
+        hipError_t e = rc == HBP_OK ? hipMemcpy(host_dst, tmp, bytes, hipMemcpyDeviceToHost) : hipSuccess;
+        (void)hipFree(tmp);
+        if (rc != HBP_OK) return rc;
+        HBP_HIP(e);
+        return HBP_OK;
+    }
+    HBP_HIP(hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost));
+    return HBP_OK;
+}
+
+int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, const float *x, float *y,
+                 int64_t n_rows, void *stream)
+{
+    if ((kind != 0 && kind != 1) || !csr_ptr || !csr_col || !csr_val || !x || !y || n_rows < 1 ||
+        n_rows >= (int64_t(1) << 31) - 1)
+        return HBP_ERR_INVALID_ARGUMENT;
+    return hbp::launch_csr(kind, csr_ptr, csr_col, csr_val, x, y, n_rows, (hipStream_t)stream);
+}
+
+const char *hbp_status_string(int status)
+{
+    switch (status) {
+    case HBP_OK: return "ok";
+    case HBP_ERR_INVALID_ARGUMENT: return "invalid argument";
+    case HBP_ERR_BAD_CSR_PTR: return "csr_ptr is not a valid row pointer array";
+    case HBP_ERR_BAD_CSR_COL: return "csr_col has an out-of-range or unsorted column index";
+    case HBP_ERR_TOO_LARGE: return "matrix or block table too large";
+    case HBP_ERR_OUT_OF_MEMORY: return "out of device memory";
+    case HBP_ERR_HIP: return "HIP runtime error";
+    case HBP_ERR_INTERNAL: return "internal error";
+    default: return "unknown status";
+    }
+}
+
+int hbp_last_hip_error(void) { return hbp::g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,666 @@
+// HBP preprocessing on the GPU: CSR -> compact HBP layout (Sections 3.1-3.3 of the paper).
+//
+// The paper's Algorithm 2 walks one matrix row per thread and inserts rows into a per-block
+// hash table with atomics.  Here the same quantities are produced with coalesced passes
+// over the CSR arrays and a deterministic placement:
+//   1. row-start bits      one bit per nonzero marking the first nonzero of a row
+//   2. segment flags       a nonzero starts a segment when it starts a row or its column
+//                          block differs from its left neighbour's (Algorithm 2's inner
+//                          while loop, evaluated for all nonzeros at once)
+//   3. segment records     (first nonzero, row, column block) in CSR order via a scan
+//   4. block table         count of segments per (column block, row block); scans give each
+//                          non-empty block its slot range, group range and list position
+//   5. bucketed scatter    every segment drops (hash key, local row, segment id) into its
+//                          block's slot range through an atomic cursor
+//   6. block ordering      each block's range is ordered by (key, local row) in LDS; the
+//                          pair is unique inside a block, so the result does not depend on
+//                          the order in which step 5's atomics were served.  This is the
+//                          deterministic limit of the paper's atomic hash-table insertion.
+//   7. fill                one wavefront per group writes col/data round by round
+//                          (column-major inside the group, Section 3.2 last paragraph)
+#include "hbp_internal.h"
+
+#include <chrono>
+#include <vector>
+
+namespace hbp {
+namespace {
+
+constexpr int32_t kErrPtr = 1, kErrCol = 2;  // bits of the device-side error word
+
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Exclusive scan of one value per thread over a 256-thread workgroup; *total is the
+// workgroup sum.  sh needs 4 entries.
+__device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t *total, uint32_t *sh)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(inc, d);
+        if (lane >= d) inc += t;
+    }
+    if (lane == 63) sh[w] = inc;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        uint32_t s = sh[i];
+        if (i < w) woff += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return woff + inc - v;
+}
+
+// ------------------------------------------------------------------ device-wide exclusive scan
+
+enum { kOpIdentity = 0, kOpCeilDivW = 1, kOpNonZero = 2 };
+template <int OP>
+__device__ __forceinline__ uint32_t scan_input(uint32_t v, uint32_t W)
+{
+    if (OP == kOpCeilDivW) return (v + W - 1) / W;
+    if (OP == kOpNonZero) return v ? 1u : 0u;
+    return v;
+}
+
+constexpr int kScanTile = 2048;  // 256 threads x 8 consecutive items
+
+template <int OP>
+__global__ __launch_bounds__(256) void k_scan_reduce(const uint32_t *__restrict__ in, int64_t n, uint32_t W,
+                                                     uint32_t *__restrict__ tile_sum)
+{
+    __shared__ uint32_t sh[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * 8;
+    uint32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+        if (base + i < n) s += scan_input<OP>(in[base + i], W);
+    uint32_t total;
+    block_excl_scan_256(s, &total, sh);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+}
+
+// One workgroup scans the tile sums in place (exclusive) and writes the grand total.
+__global__ __launch_bounds__(256) void k_scan_tiles(uint32_t *__restrict__ tile_sum, int64_t n_tiles,
+                                                    uint32_t *__restrict__ total_out)
+{
+    __shared__ uint32_t sh[4];
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < n_tiles; base += 256) {
+        int64_t i = base + threadIdx.x;
+        uint32_t v = i < n_tiles ? tile_sum[i] : 0u, total;
+        uint32_t ex = block_excl_scan_256(v, &total, sh);
+        if (i < n_tiles) tile_sum[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) *total_out = carry;
+}
+
+template <int OP>
+__global__ __launch_bounds__(256) void k_scan_down(const uint32_t *__restrict__ in, int64_t n, uint32_t W,
+                                                   const uint32_t *__restrict__ tile_off, uint32_t *__restrict__ out)
+{
+    __shared__ uint32_t sh[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * 8;
+    uint32_t v[8], s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        v[i] = base + i < n ? scan_input<OP>(in[base + i], W) : 0u;
+        s += v[i];
+    }
+    uint32_t total;
+    uint32_t run = tile_off[blockIdx.x] + block_excl_scan_256(s, &total, sh);
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        if (base + i < n) out[base + i] = run;
+        run += v[i];
+    }
+}
+
+// out[0..n) = exclusive scan of OP(in), out[n] = total.  `in` and `out` may alias.
+// tile_tmp must hold ceil(n / 2048) entries.
+template <int OP>
+int exclusive_scan(const uint32_t *in, uint32_t *out, int64_t n, uint32_t W, uint32_t *tile_tmp, hipStream_t st)
+{
+    if (n <= 0) {
+        HBP_HIP(hipMemsetAsync(out, 0, sizeof(uint32_t), st));
+        return HBP_OK;
+    }
+    const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+    k_scan_reduce<OP><<<dim3((unsigned)tiles), 256, 0, st>>>(in, n, W, tile_tmp);
+    k_scan_tiles<<<1, 256, 0, st>>>(tile_tmp, tiles, out + n);
+    k_scan_down<OP><<<dim3((unsigned)tiles), 256, 0, st>>>(in, n, W, tile_tmp, out);
+    HBP_HIP(hipGetLastError());
+    return HBP_OK;
+}
+
+// ------------------------------------------------------------------ Section 3.2: hash
+
+// key(n) = min(min(n >> a, 8) * b + (((n mod 2^a) * d) >> a), R - 1) with b = d = max(1, R / 9):
+// aggregation (shift, rows beyond class 8 count as 8), dispersion (class bands of width b),
+// linear mapping (position inside the band).
+__device__ __forceinline__ uint32_t hash_key(uint32_t n, uint32_t a, uint32_t b, uint32_t R)
+{
+    uint32_t agg = n >> a;
+    agg = agg > 8u ? 8u : agg;
+    uint32_t lin = ((n & ((1u << a) - 1u)) * b) >> a;
+    uint32_t key = agg * b + lin;
+    return key > R - 1u ? R - 1u : key;
+}
+
+// Sampling of the shift a: histogram, over the segments of up to 4096 evenly spaced rows, of
+// the smallest a in 0..12 with n < 9 * 2^a.  One wavefront walks one sampled row.
+__global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
+                                                     int64_t n_rows, int64_t nnz, int32_t C, int32_t S,
+                                                     uint32_t *__restrict__ hist)
+{
+    __shared__ uint32_t sh_hist[14];
+    if (threadIdx.x < 14) sh_hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    auto tally = [&](int n) {
+        int a = 0;
+        while (a < 13 && n >= (9 << a)) a++;
+        atomicAdd(&sh_hist[a], 1u);
+    };
+    if (k < S) {
+        const int64_t r = ((int64_t)k * n_rows) / S;
+        int64_t j0 = ptr[r], j1 = ptr[r + 1];
+        if (j0 < 0 || j1 > nnz || j1 < j0) j1 = j0;  // malformed ptr is reported by the row-bit pass
+        int64_t open = -1;                            // start of the segment whose end is not yet seen
+        int bn_left = -1;                             // column block of the nonzero left of this chunk
+        for (int64_t base = j0; base < j1; base += 64) {
+            const int64_t j = base + lane;
+            const bool valid = j < j1;
+            const int bn = valid ? col[j] / C : -2;
+            int bn_prev = __shfl_up(bn, 1);
+            if (lane == 0) bn_prev = bn_left;
+            const bool start = valid && bn != bn_prev;
+            const uint64_t mask = __ballot(start);
+            if (mask) {
+                const int first = __ffsll((long long)mask) - 1;
+                if (open >= 0 && lane == 0) tally((int)(base + first - open));
+                if (start) {
+                    const uint64_t above = mask & ~((2ull << lane) - 1ull);
+                    if (above) tally(__ffsll((long long)above) - 1 - lane);
+                }
+                open = base + (63 - __clzll((long long)mask));
+            }
+            bn_left = __shfl(bn, 63);
+        }
+        if (open >= 0 && lane == 0) tally((int)(j1 - open));
+    }
+    __syncthreads();
+    if (threadIdx.x < 14 && sh_hist[threadIdx.x]) atomicAdd(&hist[threadIdx.x], sh_hist[threadIdx.x]);
+}
+
+// a = smallest shift for which at least 15/16 of the sampled segments aggregate into 0..8.
+__global__ void k_pick_shift(const uint32_t *__restrict__ hist, int32_t *__restrict__ a_out)
+{
+    if (threadIdx.x || blockIdx.x) return;
+    uint64_t total = 0, below = 0;
+    for (int i = 0; i < 14; i++) total += hist[i];
+    int a = 0;
+    if (total) {
+        a = 12;
+        for (int i = 0; i <= 12; i++) {
+            below += hist[i];
+            if (16 * below >= 15 * total) { a = i; break; }
+        }
+    }
+    *a_out = a;
+}
+
+__global__ void k_set_i32(int32_t *p, int32_t v)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
+}
+
+// ------------------------------------------------------------------ steps 1-3: segments
+
+__global__ __launch_bounds__(256) void k_row_bits(const int32_t *__restrict__ ptr, int64_t n_rows, int64_t nnz,
+                                                  uint32_t *__restrict__ row_bits, int32_t *__restrict__ err)
+{
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= n_rows) return;
+    const int64_t p0 = ptr[r], p1 = ptr[r + 1];
+    if (p0 < 0 || p1 < p0 || p1 > nnz) {
+        atomicOr(err, kErrPtr);
+        return;
+    }
+    if (p1 > p0) atomicOr(&row_bits[p0 >> 5], 1u << (p0 & 31));
+}
+
+// word_row[w] = the row that holds nonzero 64 w (largest r with ptr[r] <= 64 w); word_row[n_words] = n_rows - 1.
+__global__ __launch_bounds__(256) void k_word_rows(const int32_t *__restrict__ ptr, int64_t n_rows, int64_t n_words,
+                                                   int32_t *__restrict__ word_row)
+{
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w > n_words) return;
+    if (w == n_words) { word_row[w] = (int32_t)(n_rows - 1); return; }
+    const int64_t j = w * 64;
+    int64_t lo = 0, hi = n_rows - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (ptr[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    word_row[w] = (int32_t)lo;
+}
+
+// One wavefront per 64 consecutive nonzeros: segment-start bits and their count.
+__global__ __launch_bounds__(256) void k_seg_flags(const int32_t *__restrict__ col, const uint32_t *__restrict__ row_bits,
+                                                   int64_t nnz, int64_t n_cols, int32_t C, int64_t n_words, int validate,
+                                                   uint64_t *__restrict__ seg_bits, uint32_t *__restrict__ seg_cnt,
+                                                   int32_t *__restrict__ err)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= n_words) return;
+    const int64_t j = w * 64 + lane;
+    const bool valid = j < nnz;
+    const int32_t c = valid ? col[j] : 0;
+    int32_t c_prev = __shfl_up(c, 1);
+    if (lane == 0) c_prev = j > 0 && valid ? col[j - 1] : -1;
+    const bool row_start = valid && ((row_bits[j >> 5] >> (j & 31)) & 1u);
+    const bool in_range = c >= 0 && c < n_cols;
+    if (valid && !in_range) atomicOr(err, kErrCol);
+    if (validate && valid && !row_start && c <= c_prev) atomicOr(err, kErrCol);
+    const bool start = valid && (row_start || (c / C) != (c_prev / C));
+    const uint64_t mask = __ballot(start);
+    if (lane == 0) {
+        seg_bits[w] = mask;
+        seg_cnt[w] = (uint32_t)__popcll(mask);
+    }
+}
+
+// Segment records in CSR order, and the per-block segment counts.
+__global__ __launch_bounds__(256) void k_seg_emit(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
+                                                  const uint64_t *__restrict__ seg_bits, const uint32_t *__restrict__ word_off,
+                                                  const int32_t *__restrict__ word_row, int64_t nnz, int64_t n_cols,
+                                                  int32_t R, int32_t C, int32_t NBR, int64_t n_words,
+                                                  int32_t *__restrict__ seg_j, int32_t *__restrict__ seg_row,
+                                                  int32_t *__restrict__ seg_bn, uint32_t *__restrict__ dense_cnt)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= n_words) return;
+    const uint64_t mask = seg_bits[w];
+    if (w == n_words - 1 && lane == 0) seg_j[word_off[n_words]] = (int32_t)nnz;  // sentinel: end of the last segment
+    if (!((mask >> lane) & 1ull)) return;
+    const int64_t j = w * 64 + lane;
+    const int32_t c = col[j];
+    if (c < 0 || c >= n_cols) return;  // already reported; never index with it
+    int32_t lo = word_row[w], hi = word_row[w + 1];
+    while (lo < hi) {                  // largest row with ptr[row] <= j
+        const int32_t mid = lo + ((hi - lo + 1) >> 1);
+        if (ptr[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    const uint32_t s = word_off[w] + (uint32_t)lanes_below(mask);
+    const int32_t bn = c / C;
+    seg_j[s] = (int32_t)j;
+    seg_row[s] = lo;
+    seg_bn[s] = bn;
+    atomicAdd(&dense_cnt[(int64_t)bn * NBR + lo / R], 1u);
+}
+
+// ------------------------------------------------------------------ step 4: block table
+
+// Non-empty blocks get their coordinates and ranges; thread d also fills col_blk_ptr[d].
+__global__ __launch_bounds__(256) void k_compact_blocks(const uint32_t *__restrict__ dense_cnt, const uint32_t *__restrict__ slot_off,
+                                                        const uint32_t *__restrict__ group_off, const uint32_t *__restrict__ blk_id,
+                                                        int64_t D, int32_t NBR, int32_t NBC, int32_t *__restrict__ blk_bm,
+                                                        int32_t *__restrict__ blk_bn, int32_t *__restrict__ slot_ptr,
+                                                        int32_t *__restrict__ blk_group_ptr, int32_t *__restrict__ col_blk_ptr)
+{
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d <= NBC) col_blk_ptr[d] = (int32_t)blk_id[d * NBR];   // blk_id[D] = B closes the last column
+    if (d > D) return;
+    if (d == D) {
+        const uint32_t B = blk_id[D];
+        slot_ptr[B] = (int32_t)slot_off[D];
+        blk_group_ptr[B] = (int32_t)group_off[D];
+        return;
+    }
+    if (!dense_cnt[d]) return;
+    const uint32_t b = blk_id[d];
+    blk_bn[b] = (int32_t)(d / NBR);
+    blk_bm[b] = (int32_t)(d % NBR);
+    slot_ptr[b] = (int32_t)slot_off[d];
+    blk_group_ptr[b] = (int32_t)group_off[d];
+}
+
+// Combine index: thread bm walks its row of the block table left to right (coalesced over bm).
+__global__ __launch_bounds__(256) void k_stripe_count(const uint32_t *__restrict__ dense_cnt, int32_t NBR, int32_t NBC,
+                                                      uint32_t *__restrict__ stripe_cnt)
+{
+    const int64_t bm = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (bm >= NBR) return;
+    uint32_t n = 0;
+    for (int64_t bn = 0; bn < NBC; bn++) n += dense_cnt[bn * NBR + bm] ? 1u : 0u;
+    stripe_cnt[bm] = n;
+}
+
+__global__ __launch_bounds__(256) void k_stripe_fill(const uint32_t *__restrict__ dense_cnt, const uint32_t *__restrict__ blk_id,
+                                                     const int32_t *__restrict__ stripe_ptr, int32_t NBR, int32_t NBC,
+                                                     int32_t *__restrict__ stripe_blk)
+{
+    const int64_t bm = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (bm >= NBR) return;
+    int32_t k = stripe_ptr[bm];
+    for (int64_t bn = 0; bn < NBC; bn++) {
+        const int64_t d = bn * NBR + bm;
+        if (dense_cnt[d]) stripe_blk[k++] = (int32_t)blk_id[d];
+    }
+}
+
+// ------------------------------------------------------------------ steps 5-6: hash + placement
+
+// Bucketed scatter: (key << 16 | local row, segment id) into the block's slot range.
+__global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_j, const int32_t *__restrict__ seg_row,
+                                                const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR,
+                                                const int32_t *__restrict__ a_ptr, uint32_t *__restrict__ cursor,
+                                                uint32_t *__restrict__ bucket_key, uint32_t *__restrict__ bucket_seg)
+{
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s >= S) return;
+    const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
+    const int32_t row = seg_row[s];
+    const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u;
+    const uint32_t key = hash_key(n, (uint32_t)*a_ptr, b, R_u);
+    const uint32_t pos = atomicAdd(&cursor[(int64_t)seg_bn[s] * NBR + row / R], 1u);
+    bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
+    bucket_seg[pos] = (uint32_t)s;
+}
+
+// One workgroup per non-empty block: order its slots by (key, local row) with a bitonic
+// network in LDS, then write the slot arrays and the nonzero count of each group.
+__global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict__ bucket_key, const uint32_t *__restrict__ bucket_seg,
+                                                     const int32_t *__restrict__ seg_j, const int32_t *__restrict__ slot_ptr,
+                                                     const int32_t *__restrict__ blk_group_ptr, int32_t W,
+                                                     uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
+                                                     int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz,
+                                                     int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk)
+{
+    extern __shared__ uint64_t keys[];
+    const int b = blockIdx.x;
+    const int s0 = slot_ptr[b], m = slot_ptr[b + 1] - s0;
+    int n2 = 1;
+    while (n2 < m) n2 <<= 1;
+    for (int i = threadIdx.x; i < n2; i += 256)
+        keys[i] = i < m ? ((uint64_t)bucket_key[s0 + i] << 32) | bucket_seg[s0 + i] : ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n2; i += 256) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const uint64_t x = keys[i], y = keys[p];
+                    if ((x > y) == ((i & k) == 0)) { keys[i] = y; keys[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+    for (int i = threadIdx.x; i < m; i += 256) {
+        const uint64_t e = keys[i];
+        const uint32_t seg = (uint32_t)e;
+        const int32_t j0 = seg_j[seg], n = seg_j[seg + 1] - j0;
+        row_local[s0 + i] = (uint16_t)((e >> 32) & 0xffffu);
+        seg_len[s0 + i] = (uint16_t)n;
+        slot_j[s0 + i] = j0;
+        keys[i] = (uint64_t)n;  // only this thread touches entry i in this phase
+    }
+    __syncthreads();
+    const int g0 = blk_group_ptr[b], ng = (m + W - 1) / W;
+    for (int gi = threadIdx.x; gi < ng; gi += 256) {
+        uint32_t sum = 0;
+        const int e1 = min(m, (gi + 1) * W);
+        for (int i = gi * W; i < e1; i++) sum += (uint32_t)keys[i];
+        group_nnz[g0 + gi] = sum;
+        group_slot[g0 + gi] = s0 + gi * W;
+        group_blk[g0 + gi] = b;
+    }
+}
+
+// ------------------------------------------------------------------ step 7: fill
+
+// One wavefront per group.  Round k stores the k-th nonzero of every lane that still has
+// one, lanes in slot order; rows keep their CSR (ascending column) order.
+__global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_col, const float *__restrict__ csr_val,
+                                              const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
+                                              const int32_t *__restrict__ group_blk, const int32_t *__restrict__ blk_bn,
+                                              const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
+                                              int32_t G, int32_t C, uint16_t *__restrict__ col_local, float *__restrict__ data)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= G) return;
+    const int s0 = group_slot[g], cnt = group_slot[g + 1] - s0;
+    const int32_t col0 = blk_bn[group_blk[g]] * C;
+    const int n = lane < cnt ? seg_len[s0 + lane] : 0;
+    const int64_t j = lane < cnt ? slot_j[s0 + lane] : 0;
+    int64_t base = group_ptr[g];
+    for (int k = 0;; k++) {
+        const uint64_t live = __ballot(k < n);
+        if (!live) break;
+        if (k < n) {
+            const int64_t dst = base + lanes_below(live);
+            col_local[dst] = (uint16_t)(csr_col[j + k] - col0);
+            data[dst] = csr_val[j + k];
+        }
+        base += __popcll(live);
+    }
+}
+
+// add_sign derived from seg_len (Section 3.2: distance to the row's next nonzero = nonzeros
+// after it in this round + nonzeros before it in the next round + 1; -1 at the row's end).
+__global__ __launch_bounds__(256) void k_add_sign(const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
+                                                  const uint16_t *__restrict__ seg_len, int32_t G, int32_t *__restrict__ add_sign)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= G) return;
+    const int s0 = group_slot[g], cnt = group_slot[g + 1] - s0;
+    const int n = lane < cnt ? seg_len[s0 + lane] : 0;
+    int64_t base = group_ptr[g];
+    const uint64_t above_me = ~((2ull << lane) - 1ull);
+    for (int k = 0;; k++) {
+        const uint64_t live = __ballot(k < n);
+        if (!live) break;
+        const uint64_t next = __ballot(k + 1 < n);
+        if (k < n) {
+            const int64_t dst = base + lanes_below(live);
+            add_sign[dst] = k + 1 < n ? __popcll(live & above_me) + lanes_below(next) + 1 : -1;
+        }
+        base += __popcll(live);
+    }
+}
+
+struct DeviceBuffers {  // frees every temporary on scope exit
+    std::vector<void *> ptrs;
+    ~DeviceBuffers() { for (void *p : ptrs) (void)hipFree(p); }
+    template <typename T>
+    int alloc(T **out, int64_t count)
+    {
+        void *p = nullptr;
+        HBP_HIP(hipMalloc(&p, (size_t)(count > 0 ? count : 1) * sizeof(T)));
+        ptrs.push_back(p);
+        *out = (T *)p;
+        return HBP_OK;
+    }
+};
+
+template <typename T>
+int alloc_owned(T **out, int64_t count)
+{
+    void *p = nullptr;
+    HBP_HIP(hipMalloc(&p, (size_t)(count > 0 ? count : 1) * sizeof(T)));
+    *out = (T *)p;
+    return HBP_OK;
+}
+
+inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+#define HBP_TRY(expr) do { int rc_ = (expr); if (rc_ != HBP_OK) return rc_; } while (0)
+
+}  // namespace
+
+int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+                 const hbp_params_t &p, hipStream_t st)
+{
+    const int64_t n_rows = h->n_rows, n_cols = h->n_cols;
+    const int32_t R = h->R, C = h->C, W = h->W;
+    const int64_t NBR = h->NBR, NBC = h->NBC, D = NBR * NBC;
+
+    // nnz and csr_ptr[0] are needed on the host before anything can be sized
+    int32_t ends[2] = {0, 0};
+    HBP_HIP(hipMemcpyAsync(&ends[0], csr_ptr, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&ends[1], csr_ptr + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipStreamSynchronize(st));
+    if (ends[0] != 0 || ends[1] < 0) return HBP_ERR_BAD_CSR_PTR;
+    const int64_t nnz = ends[1];
+    if (nnz >= (int64_t(1) << 31) - 64) return HBP_ERR_TOO_LARGE;
+    h->nnz = nnz;
+
+    // arrays whose size does not depend on the matrix content
+    HBP_TRY(alloc_owned(&h->col_blk_ptr, NBC + 1));
+    HBP_TRY(alloc_owned(&h->stripe_ptr, NBR + 1));
+    HBP_TRY(alloc_owned(&h->ticket, 1));
+    HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t), st));
+    HBP_HIP(hipMemsetAsync(h->col_blk_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
+    HBP_HIP(hipMemsetAsync(h->stripe_ptr, 0, sizeof(int32_t) * (size_t)(NBR + 1), st));
+
+    if (nnz == 0) {  // empty matrix: no blocks; the combine part alone writes y = 0
+        h->B = h->S = h->G = 0;
+        h->a = p.hash_shift >= 0 ? p.hash_shift : 0;
+        HBP_TRY(alloc_owned(&h->blk_bm, 1)); HBP_TRY(alloc_owned(&h->blk_bn, 1));
+        HBP_TRY(alloc_owned(&h->slot_ptr, 1)); HBP_TRY(alloc_owned(&h->blk_group_ptr, 1));
+        HBP_TRY(alloc_owned(&h->stripe_blk, 1)); HBP_TRY(alloc_owned(&h->group_ptr, 1));
+        HBP_TRY(alloc_owned(&h->group_slot, 1)); HBP_TRY(alloc_owned(&h->row_local, 1));
+        HBP_TRY(alloc_owned(&h->seg_len, 1)); HBP_TRY(alloc_owned(&h->col_local, 1));
+        HBP_TRY(alloc_owned(&h->data, 1)); HBP_TRY(alloc_owned(&h->partial, 1));
+        HBP_HIP(hipMemsetAsync(h->slot_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->blk_group_ptr, 0, 4, st));
+        HBP_HIP(hipMemsetAsync(h->group_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->group_slot, 0, 4, st));
+        HBP_HIP(hipStreamSynchronize(st));
+        return HBP_OK;
+    }
+
+    DeviceBuffers tmp;
+    const int64_t n_words = (nnz + 63) / 64;
+    const int64_t scan_n = std::max<int64_t>(std::max<int64_t>(n_words, D), std::max<int64_t>(NBR, nnz / W + D)) + 1;
+    uint32_t *row_bits, *seg_cnt, *word_off, *dense_cnt, *slot_off, *group_off, *blk_id, *scan_tmp, *hist, *stripe_cnt;
+    uint64_t *seg_bits;
+    int32_t *word_row, *seg_j, *seg_row, *seg_bn, *d_a, *d_err;
+    HBP_TRY(tmp.alloc(&row_bits, (nnz + 31) / 32 + 1));
+    HBP_TRY(tmp.alloc(&seg_bits, n_words));
+    HBP_TRY(tmp.alloc(&seg_cnt, n_words));
+    HBP_TRY(tmp.alloc(&word_off, n_words + 1));
+    HBP_TRY(tmp.alloc(&word_row, n_words + 1));
+    HBP_TRY(tmp.alloc(&seg_j, nnz + 1));     // S <= nnz: sized by the bound, no host round trip needed
+    HBP_TRY(tmp.alloc(&seg_row, nnz));
+    HBP_TRY(tmp.alloc(&seg_bn, nnz));
+    HBP_TRY(tmp.alloc(&dense_cnt, D));
+    HBP_TRY(tmp.alloc(&slot_off, D + 1));
+    HBP_TRY(tmp.alloc(&group_off, D + 1));
+    HBP_TRY(tmp.alloc(&blk_id, D + 1));
+    HBP_TRY(tmp.alloc(&stripe_cnt, NBR));
+    HBP_TRY(tmp.alloc(&scan_tmp, scan_n / kScanTile + 2));
+    HBP_TRY(tmp.alloc(&hist, 16));
+    HBP_TRY(tmp.alloc(&d_a, 1));
+    HBP_TRY(tmp.alloc(&d_err, 1));
+    HBP_HIP(hipMemsetAsync(row_bits, 0, sizeof(uint32_t) * (size_t)((nnz + 31) / 32 + 1), st));
+    HBP_HIP(hipMemsetAsync(dense_cnt, 0, sizeof(uint32_t) * (size_t)D, st));
+    HBP_HIP(hipMemsetAsync(hist, 0, sizeof(uint32_t) * 16, st));
+    HBP_HIP(hipMemsetAsync(d_err, 0, sizeof(int32_t), st));
+
+    // Section 3.2: shift a, sampled or given
+    if (p.hash_shift >= 0) {
+        k_set_i32<<<1, 64, 0, st>>>(d_a, p.hash_shift);
+    } else {
+        const int32_t S_rows = (int32_t)std::min<int64_t>(n_rows, 4096);
+        k_sample_hist<<<blocks_for(S_rows, 4), 256, 0, st>>>(csr_ptr, csr_col, n_rows, nnz, C, S_rows, hist);
+        k_pick_shift<<<1, 64, 0, st>>>(hist, d_a);
+    }
+
+    // steps 1-3
+    k_row_bits<<<blocks_for(n_rows, 256), 256, 0, st>>>(csr_ptr, n_rows, nnz, row_bits, d_err);
+    k_word_rows<<<blocks_for(n_words + 1, 256), 256, 0, st>>>(csr_ptr, n_rows, n_words, word_row);
+    k_seg_flags<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_col, row_bits, nnz, n_cols, C, n_words,
+                                                       (p.flags & HBP_FLAG_VALIDATE) ? 1 : 0, seg_bits, seg_cnt, d_err);
+    HBP_TRY(exclusive_scan<kOpIdentity>(seg_cnt, word_off, n_words, 1, scan_tmp, st));
+    k_seg_emit<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_ptr, csr_col, seg_bits, word_off, word_row, nnz, n_cols, R, C,
+                                                      (int32_t)NBR, n_words, seg_j, seg_row, seg_bn, dense_cnt);
+    // step 4: scans over the block table
+    HBP_TRY(exclusive_scan<kOpIdentity>(dense_cnt, slot_off, D, 1, scan_tmp, st));
+    HBP_TRY(exclusive_scan<kOpCeilDivW>(dense_cnt, group_off, D, (uint32_t)W, scan_tmp, st));
+    HBP_TRY(exclusive_scan<kOpNonZero>(dense_cnt, blk_id, D, 1, scan_tmp, st));
+    k_stripe_count<<<blocks_for(NBR, 256), 256, 0, st>>>(dense_cnt, (int32_t)NBR, (int32_t)NBC, stripe_cnt);
+    HBP_TRY(exclusive_scan<kOpIdentity>(stripe_cnt, (uint32_t *)h->stripe_ptr, NBR, 1, scan_tmp, st));
+    HBP_HIP(hipGetLastError());
+
+    // the one host round trip of the build: totals (and the error word)
+    uint32_t totals[3];
+    int32_t err = 0, a = 0;
+    HBP_HIP(hipMemcpyAsync(&totals[0], slot_off + D, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&totals[1], group_off + D, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&totals[2], blk_id + D, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&err, d_err, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&a, d_a, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipStreamSynchronize(st));
+    if (err & kErrPtr) return HBP_ERR_BAD_CSR_PTR;
+    if (err & kErrCol) return HBP_ERR_BAD_CSR_COL;
+    const int64_t S = totals[0], G = totals[1], B = totals[2];
+    h->S = S; h->G = G; h->B = B; h->a = a;
+
+    HBP_TRY(alloc_owned(&h->blk_bm, B + 1)); HBP_TRY(alloc_owned(&h->blk_bn, B + 1));
+    HBP_TRY(alloc_owned(&h->slot_ptr, B + 1)); HBP_TRY(alloc_owned(&h->blk_group_ptr, B + 1));
+    HBP_TRY(alloc_owned(&h->stripe_blk, B + 1));
+    HBP_TRY(alloc_owned(&h->group_ptr, G + 1)); HBP_TRY(alloc_owned(&h->group_slot, G + 1));
+    HBP_TRY(alloc_owned(&h->row_local, S + 1)); HBP_TRY(alloc_owned(&h->seg_len, S + 1));
+    HBP_TRY(alloc_owned(&h->col_local, nnz + 1)); HBP_TRY(alloc_owned(&h->data, nnz + 1));
+    HBP_TRY(alloc_owned(&h->partial, S + 1));
+    uint32_t *bucket_key, *bucket_seg, *group_nnz;
+    int32_t *slot_j, *group_blk;
+    HBP_TRY(tmp.alloc(&bucket_key, S)); HBP_TRY(tmp.alloc(&bucket_seg, S));
+    HBP_TRY(tmp.alloc(&slot_j, S)); HBP_TRY(tmp.alloc(&group_nnz, G + 1)); HBP_TRY(tmp.alloc(&group_blk, G + 1));
+
+    k_compact_blocks<<<blocks_for(std::max<int64_t>(D, NBC) + 1, 256), 256, 0, st>>>(
+        dense_cnt, slot_off, group_off, blk_id, D, (int32_t)NBR, (int32_t)NBC, h->blk_bm, h->blk_bn, h->slot_ptr,
+        h->blk_group_ptr, h->col_blk_ptr);
+    k_stripe_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(dense_cnt, blk_id, h->stripe_ptr, (int32_t)NBR, (int32_t)NBC,
+                                                       h->stripe_blk);
+    // steps 5-6 (slot_off doubles as the per-block cursor from here on)
+    k_bucket<<<blocks_for(S, 256), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, d_a, slot_off, bucket_key,
+                                                 bucket_seg);
+    int n2 = 2;
+    while (n2 < R) n2 <<= 1;
+    const size_t order_lds = sizeof(uint64_t) * (size_t)n2;
+    HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
+                                                            h->row_local, h->seg_len, slot_j, group_nnz, h->group_slot,
+                                                            group_blk);
+    HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
+    k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
+    // step 7
+    k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
+                                             slot_j, (int32_t)G, C, h->col_local, h->data);
+    HBP_HIP(hipGetLastError());
+    HBP_HIP(hipStreamSynchronize(st));
+    return HBP_OK;
+}
+
+int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t st)
+{
+    if (h->G > 0)
+        k_add_sign<<<blocks_for(h->G, 4), 256, 0, st>>>(h->group_ptr, h->group_slot, h->seg_len, (int32_t)h->G, d_out);
+    HBP_HIP(hipGetLastError());
+    return HBP_OK;
+}
+
+}  // namespace hbp

@@ -1,0 +1,72 @@
+// Internal declarations shared by the translation units of libhbp (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hbp.h"
+
+namespace hbp {
+
+constexpr int kWave = 64;            // gfx950 wavefront width
+constexpr int kMaxR = 8192;          // rows per block: one block's slots are ordered in 64 KB of LDS
+constexpr int kMaxC = 32768;         // columns per block: fp32 vector segment of 128 KB in LDS
+constexpr int64_t kMaxDense = int64_t(1) << 27;  // NBR * NBC table entries
+
+// Device-side view of the layout, passed by value to kernels.
+struct Layout {
+    int32_t R, C, W;
+    int32_t B, S, G;
+    int32_t NBR, NBC;
+    int64_t n_rows, n_cols;
+    const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
+    const int32_t *group_ptr, *group_slot;
+    const uint16_t *row_local, *seg_len, *col_local;
+    const float *data;
+};
+
+}  // namespace hbp
+
+struct hbp_handle_s {
+    int device;
+    int64_t n_rows, n_cols, nnz;
+    int32_t R, C, W, a;
+    int64_t NBR, NBC, B, S, G;
+    int32_t P, F, claim_chunk, threads;
+    double build_ms;
+    // device arrays (owned)
+    int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
+    int32_t *group_ptr, *group_slot;
+    uint16_t *row_local, *seg_len, *col_local;
+    float *data;
+    float *partial;      // [S] per-slot partial sums of the SpMV part
+    uint32_t *ticket;    // competitive-part ticket counter, zero between calls
+};
+
+namespace hbp {
+
+// error plumbing -----------------------------------------------------------------------
+void set_last_hip_error(hipError_t e);
+#define HBP_HIP(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) {                        \
+            hbp::set_last_hip_error(e_);               \
+            return e_ == hipErrorOutOfMemory ? HBP_ERR_OUT_OF_MEMORY : HBP_ERR_HIP; \
+        }                                              \
+    } while (0)
+
+// build (hbp_build.hip)
+int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+                 const hbp_params_t &p, hipStream_t stream);
+int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
+
+// spmv (hbp_spmv.hip)
+Layout hbp_view(const hbp_handle_s *h);
+int default_workers(int device, int32_t C, int32_t *threads_out, int32_t *workers_out);
+int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t stream);
+int launch_combine(const hbp_handle_s *h, float *y, hipStream_t stream);
+int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,
+               int64_t n_rows, hipStream_t stream);
+
+}  // namespace hbp

@@ -1,0 +1,16 @@
+"""Block-parameter presets for the five benchmark workloads (R rows x C columns per block,
+fixed share of the schedule, claim chunk).  Chosen by measurement on MI355X; the library's
+own defaults are the paper's 512 x 4096."""
+from __future__ import annotations
+
+PRESETS = {
+    1: dict(rows_per_block=512, cols_per_block=4096),
+    2: dict(rows_per_block=512, cols_per_block=32768),
+    3: dict(rows_per_block=2048, cols_per_block=32768),
+    4: dict(rows_per_block=2048, cols_per_block=32768),
+    5: dict(rows_per_block=2048, cols_per_block=32768),
+}
+
+
+def preset(config_number: int) -> dict:
+    return dict(PRESETS[config_number])

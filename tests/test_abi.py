@@ -1,0 +1,31 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/hbp.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_are_exported():
+    import paper_2504_08860_amd as H
+    if not os.path.exists(H.LIB_PATH):
+        from paper_2504_08860_amd.build import build_library
+        build_library()
+    lib = ctypes.CDLL(H.LIB_PATH)
+    header = open(os.path.join(ROOT, "include", "hbp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(hbp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(H.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_host_only_calls():
+    import paper_2504_08860_amd as H
+    p = H.hbp_default_params()
+    assert (p.rows_per_block, p.cols_per_block, p.group_width) == (512, 4096, 64)   # Section 3.1 sizes, wave64
+    assert H.hbp_status_string(0) == "ok" and "column" in H.hbp_status_string(-3)
+    assert H.lib().hbp_free(None) == 0
+    assert H.lib().hbp_get_info(None, None) == -1
+    assert H.lib().hbp_build(None, None, None, 1, 1, None, None, None) == -1
+    assert ctypes.sizeof(H.hbp_params_t) == 32

@@ -1,0 +1,182 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Layout arrays must be bit-equal; y must satisfy
+|y - y_ref| <= 1e-5 * sum_j |a_ij x_j| per row (the tolerance the benchmark spec states)."""
+import numpy as np
+import pytest
+
+from workloads import make_config, random_csr, worked_example_8x8
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
+                 "group_ptr", "group_slot", "row_local", "seg_len", "col_local", "data", "add_sign")
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2504_08860_amd as H
+    H.lib()
+    return H
+
+
+def to_dev(m):
+    import torch
+    t = lambda a: torch.from_numpy(a).cuda()
+    return t(m.ptr), t(m.col), t(m.val), t(m.x)
+
+
+def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
+    import torch
+    ptr, col, val, x = to_dev(m)
+    print(f"[case] {m.name} rows={m.n_rows} cols={m.n_cols} nnz={m.nnz} params={params}", flush=True)
+    h = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, **params)
+    try:
+        info = H.hbp_get_info(h)
+        o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
+                             W=info.group_width, hash_shift=params.get("hash_shift", -1),
+                             num_workers=info.num_workers,
+                             fixed_q8=params.get("fixed_fraction_q8", 128) if params.get("fixed_fraction_q8", -1) >= 0 else 128)
+        assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
+        assert info.hash_shift == o.a and info.fixed_per_worker == o.F
+        assert info.hash_b == max(1, info.rows_per_block // 9)
+        for name in LAYOUT_ARRAYS:
+            if name == "add_sign" and not check_add_sign:
+                continue
+            got, want = H.hbp_export(h, name), o.array(name)
+            if name == "data":
+                got, want = got.view(np.uint32), want.view(np.uint32)
+            assert got.shape == want.shape, name
+            assert np.array_equal(got, want), f"{name} differs at {np.flatnonzero(got != want)[:5]}"
+        y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+        y = torch.full((m.n_rows,), float("nan"), device="cuda")
+        for rep in range(2):  # the second call checks that the ticket counter was re-armed
+            y.fill_(float("nan"))
+            H.hbp_spmv(h, x, y)
+            torch.cuda.synchronize()
+            yh = y.cpu().numpy().astype(np.float64)
+            bad = np.flatnonzero(~(np.abs(yh - y_ref) <= TOL * s_abs))
+            assert bad.size == 0, f"rep {rep}: rows {bad[:5]} y {yh[bad[:5]]} ref {y_ref[bad[:5]]}"
+            assert np.all(yh[np.diff(m.ptr) == 0] == 0.0)
+        # per-slot partial sums against the oracle's walk through the layout
+        _, p_ref = o.spmv(m.x)
+        p = H.hbp_export(h, "partial").astype(np.float64)
+        slot_row = (np.repeat(o.array("blk_bm"), np.diff(o.array("slot_ptr"))).astype(np.int64) * o.R
+                    + o.array("row_local"))
+        assert np.all(np.abs(p - p_ref) <= TOL * s_abs[slot_row])
+        o.close()
+        return info
+    finally:
+        H.hbp_free(h)
+
+
+def test_worked_example(H, oracle):
+    check_against_oracle(H, oracle, worked_example_8x8(), rows_per_block=4, cols_per_block=4, group_width=2, hash_shift=0)
+
+
+SMALL = [
+    # rows, cols, density, seed, R, C, W, shift
+    (40, 40, 0.2, 1, 8, 8, 4, -1),
+    (77, 53, 0.3, 2, 16, 10, 4, 0),
+    (64, 200, 0.15, 3, 64, 32, 8, 1),
+    (129, 65, 0.5, 4, 32, 16, 3, 2),
+    (30, 300, 0.4, 5, 7, 50, 64, -1),
+    (200, 30, 0.1, 6, 512, 4096, 64, -1),
+    (1000, 1000, 0.02, 7, 100, 333, 64, -1),     # ragged everywhere, several tiles of 64 nonzeros
+    (5000, 3000, 0.01, 8, 512, 1024, 32, -1),
+    (3000, 9000, 0.05, 9, 8192, 32768, 64, -1),  # the largest block the library accepts
+    (2500, 700, 0.3, 10, 1, 1, 1, 0),            # degenerate 1 x 1 blocks
+]
+
+
+@pytest.mark.parametrize("case", SMALL)
+def test_small_random(H, oracle, case):
+    nr, nc, dens, seed, R, C, W, shift = case
+    m = random_csr(nr, nc, dens, seed, empty_row_frac=0.15)
+    check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, group_width=W, hash_shift=shift)
+
+
+@pytest.mark.parametrize("P,q8,chunk", [(1, 0, 1), (3, 256, 1), (7, 100, 5), (2000, 200, 2)])
+def test_schedule_variants(H, oracle, P, q8, chunk):
+    """y does not depend on how blocks are split into fixed and competitive parts."""
+    m = random_csr(3000, 3000, 0.01, 21, empty_row_frac=0.1)
+    info = check_against_oracle(H, oracle, m, rows_per_block=64, cols_per_block=128, num_workers=P,
+                                fixed_fraction_q8=q8, claim_chunk=chunk)
+    assert info.num_workers == P and info.claim_chunk == chunk
+
+
+@pytest.mark.parametrize("number,scale,R,C", [(1, 1.0, 512, 4096), (2, 0.02, 512, 4096), (2, 0.02, 256, 32768),
+                                              (3, 2**-6, 256, 1024), (4, 2**-7, 512, 2048), (5, 0.01, 512, 4096),
+                                              (5, 0.01, 2048, 32768)])
+def test_configs_reduced(H, oracle, number, scale, R, C):
+    check_against_oracle(H, oracle, make_config(number, scale), rows_per_block=R, cols_per_block=C)
+
+
+def test_long_rows_and_heavy_tail(H, oracle):
+    """A few rows far longer than the rest (one fills a whole block row), inside one group."""
+    rng = np.random.default_rng(3)
+    lens = np.r_[rng.integers(0, 6, 500), [4096, 3000, 1], rng.integers(0, 6, 300)]
+    n_cols = 4096
+    col = np.concatenate([np.sort(rng.choice(n_cols, n, replace=False)) for n in lens]).astype(np.int32)
+    ptr = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    from workloads import CsrMatrix
+    m = CsrMatrix("heavy", len(lens), n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32),
+                  rng.uniform(-1, 1, n_cols).astype(np.float32))
+    check_against_oracle(H, oracle, m, rows_per_block=256, cols_per_block=4096)
+    check_against_oracle(H, oracle, m, rows_per_block=256, cols_per_block=512)
+
+
+def test_empty_matrix_and_empty_rows(H, oracle):
+    import torch
+    ptr = torch.zeros(11, dtype=torch.int32, device="cuda")
+    col = torch.zeros(1, dtype=torch.int32, device="cuda")
+    val = torch.zeros(1, dtype=torch.float32, device="cuda")
+    h = H.hbp_build(ptr, col, val, 10, 5)
+    info = H.hbp_get_info(h)
+    assert (info.nnz, info.blocks, info.slots, info.groups) == (0, 0, 0, 0)
+    y = torch.full((10,), float("nan"), device="cuda")
+    H.hbp_spmv(h, torch.ones(5, device="cuda"), y)
+    assert torch.all(y == 0)
+    H.hbp_free(h)
+    # a single nonzero in the last row and column
+    m = random_csr(1, 1, 1.1, 0)
+    check_against_oracle(H, oracle, m)
+
+
+def test_invalid_inputs_are_errors(H):
+    import torch
+    m = random_csr(50, 60, 0.2, 1)
+    ptr, col, val, x = to_dev(m)
+    with pytest.raises(H.HbpError) as e:                      # column beyond n_cols
+        H.hbp_build(ptr, col, val, m.n_rows, 10)
+    assert e.value.status == -3
+    bad = col.clone(); bad[1], bad[0] = col[0].item(), col[1].item()
+    if m.ptr[1] >= 2:                                          # unsorted inside row 0
+        with pytest.raises(H.HbpError) as e:
+            H.hbp_build(ptr, bad, val, m.n_rows, m.n_cols)
+        assert e.value.status == -3
+    p2 = ptr.clone(); p2[3] = p2[2] - 1 if p2[2] > 0 else 99999
+    with pytest.raises(H.HbpError) as e:                      # decreasing row pointer
+        H.hbp_build(p2, col, val, m.n_rows, m.n_cols)
+    assert e.value.status == -2
+    for kw in (dict(rows_per_block=8193), dict(cols_per_block=32769), dict(group_width=65), dict(hash_shift=13)):
+        with pytest.raises(H.HbpError) as e:
+            H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, **kw)
+        assert e.value.status == -1
+    with pytest.raises(H.HbpError) as e:                      # block table too large
+        H.hbp_build(ptr, col, val, m.n_rows, 2**30, rows_per_block=1, cols_per_block=1)
+    assert e.value.status == -4
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+def test_csr_baselines(H, oracle, kind):
+    import torch
+    for m in (make_config(1), make_config(5, 0.01), random_csr(300, 200, 0.2, 4, empty_row_frac=0.2)):
+        ptr, col, val, x = to_dev(m)
+        y = torch.full((m.n_rows,), float("nan"), device="cuda")
+        H.hbp_csr_spmv(kind, ptr, col, val, x, y)
+        torch.cuda.synchronize()
+        y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+        assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs)
