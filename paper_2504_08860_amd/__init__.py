@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_08860_amd.build` "
                                "(or __graft_entry__.build()); there is no CPU fallback")
+        # PyTorch ships its own HIP runtime (same soname as the system one).  It has to be in
+        # the process before libhbp.so is loaded, so that both share one runtime and device
+        # pointers from torch tensors are valid in the library's calls.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.hbp_default_params.argtypes = [ctypes.POINTER(hbp_params_t)]
