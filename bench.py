@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--num-workers", type=int, default=-1)
     ap.add_argument("--fixed-q8", type=int, default=-2)
     ap.add_argument("--claim-chunk", type=int, default=-1)
+    ap.add_argument("--threads", type=int, default=0)
+    ap.add_argument("--rounds", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-csr", action="store_true")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
@@ -62,6 +64,8 @@ def main() -> int:
     if args.num_workers >= 0: params["num_workers"] = args.num_workers
     if args.fixed_q8 >= -1: params["fixed_fraction_q8"] = args.fixed_q8
     if args.claim_chunk >= 0: params["claim_chunk"] = args.claim_chunk
+    if args.threads: params["threads_per_worker"] = args.threads
+    if args.rounds: params["rounds_per_batch"] = args.rounds
 
     dev = lambda a: torch.from_numpy(a).cuda()
     ptr, col, val, x = dev(m.ptr), dev(m.col), dev(m.val), dev(m.x)
@@ -82,7 +86,7 @@ def main() -> int:
     info = H.hbp_get_info(h)
     log(f"[bench] R={info.rows_per_block} C={info.cols_per_block} W={info.group_width} a={info.hash_shift} "
         f"blocks={info.blocks} slots={info.slots} groups={info.groups} P={info.num_workers} "
-        f"F={info.fixed_per_worker} threads={info.threads_per_worker} build_ms={[round(b, 2) for b in build_ms]}")
+        f"fixed_q8={info.fixed_fraction_q8} threads={info.threads_per_worker} build_ms={[round(b, 2) for b in build_ms]}")
 
     # the timed region: exactly K steps between synchronisations
     for _ in range(args.warmup):
@@ -114,8 +118,8 @@ def main() -> int:
                    "rows_per_block": info.rows_per_block, "cols_per_block": info.cols_per_block,
                    "group_width": info.group_width, "hash_shift": info.hash_shift, "blocks": info.blocks,
                    "slots": info.slots, "groups": info.groups, "workers": info.num_workers,
-                   "fixed_per_worker": info.fixed_per_worker, "claim_chunk": info.claim_chunk,
-                   "threads_per_worker": info.threads_per_worker},
+                   "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
+                   "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "bytes_per_launch": info.bytes_spmv_part, "ms_per_launch": round(ms_part, 5)},

@@ -31,6 +31,14 @@
  *     stripe_blk          [B]      blocks of one row block, bn ascending (combine index)
  *     group_ptr           [G+1]    position of a group's first nonzero   (begin_ptr)
  *     group_slot          [G+1]    first slot of a group
+ *   Schedule (Section 3.3; the unit handed to a wavefront is a group, whose weight is its
+ *   nonzeros plus its slots):
+ *     col_group_ptr       [NBC+1]  first group of each block column
+ *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
+ *                                  the leading fixed_fraction of its weight as fixed part
+ *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
+ *                                  weight; worker w runs the fixed groups of range w
+ *     fixed_col           [P]      block column that holds a worker's first group
  *     row_local   u16     [S]      slot -> row inside its block          (output_hash)
  *     seg_len     u16     [S]      nonzeros of that row inside the block (add_sign is
  *                                  derived from these at run time)
@@ -73,9 +81,11 @@ typedef struct {
     int32_t cols_per_block;    /* C, 1..32768; 0 = default 4096                                 */
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for; 0 = device default */
-    int32_t fixed_fraction_q8; /* share of blocks pre-assigned to workers, in 1/256; -1 = default */
+    int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
-    int32_t claim_chunk;       /* consecutive blocks taken per competitive ticket; 0 = default  */
+    int32_t claim_chunk;       /* groups per wavefront in one competitive ticket; 0 = default    */
+    int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
+    int32_t rounds_per_batch;  /* rounds a wavefront loads before accumulating: 4, 8, 9, 16; 0 = default */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;
 
@@ -87,9 +97,10 @@ typedef struct {
     int64_t row_blocks, col_blocks;       /* NBR, NBC                                           */
     int64_t blocks, slots, groups;        /* B, S, G                                            */
     int32_t num_workers;         /* P                                                           */
-    int32_t fixed_per_worker;    /* F = floor(B * fixed_fraction_q8 / (256 P))                   */
+    int32_t fixed_fraction_q8;   /* share of the work that is pre-assigned, in 1/256            */
     int32_t claim_chunk;
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
+    int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
@@ -103,7 +114,8 @@ typedef enum {
     HBP_ARRAY_GROUP_SLOT = 8, HBP_ARRAY_ROW_LOCAL = 9, HBP_ARRAY_SEG_LEN = 10, HBP_ARRAY_COL_LOCAL = 11,
     HBP_ARRAY_DATA = 12,
     HBP_ARRAY_ADD_SIGN = 13, /* int32 [nnz], derived on the device from seg_len when exported   */
-    HBP_ARRAY_PARTIAL = 14   /* float [S], per-slot partial sums left by the last hbp_spmv      */
+    HBP_ARRAY_PARTIAL = 14,  /* float [S], per-slot partial sums left by the last hbp_spmv      */
+    HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */

@@ -24,9 +24,10 @@ ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
     "blk_group_ptr": (3, np.int32), "col_blk_ptr": (4, np.int32), "stripe_ptr": (5, np.int32),
     "stripe_blk": (6, np.int32), "group_ptr": (7, np.int32), "group_slot": (8, np.int32),
     "row_local": (9, np.uint16), "seg_len": (10, np.uint16), "col_local": (11, np.uint16),
-    "data": (12, np.float32), "add_sign": (13, np.int32),
+    "data": (12, np.float32), "add_sign": (13, np.int32), "col_group_ptr": (14, np.int32),
+    "comp_lo": (15, np.int32), "fixed_start": (16, np.int32), "fixed_col": (17, np.int32),
 }
-DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "F")
+DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8")
 
 
 def build(force: bool = False) -> str:

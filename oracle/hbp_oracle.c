@@ -126,7 +126,7 @@ typedef struct {
     int32_t R, C, W, a;
     int64_t NBR, NBC;   /* row blocks, column blocks */
     int64_t B, S, G;    /* non-empty blocks, slots (= segments), groups */
-    int64_t P, F;       /* workers, fixed blocks per worker (Section 3.3) */
+    int64_t P, fixed_q8; /* workers, share of the work that is pre-assigned in 1/256 (Section 3.3) */
     int32_t *blk_bm, *blk_bn;     /* B   : block coordinates, column-major order          */
     int32_t *slot_ptr;            /* B+1 : first slot of each block                        */
     int32_t *blk_group_ptr;       /* B+1 : first group of each block                       */
@@ -140,6 +140,10 @@ typedef struct {
     uint16_t *col_local;          /* nnz : column inside the block's column range          */
     float *data;                  /* nnz                                                   */
     int32_t *add_sign;            /* nnz : distance to the row's next nonzero, -1 at its end */
+    int32_t *col_group_ptr;       /* NBC+1 : first group of each block column                 */
+    int32_t *comp_lo;             /* NBC : first competitive group of a block column          */
+    int32_t *fixed_start;         /* P+1 : group ranges of the workers                        */
+    int32_t *fixed_col;           /* P   : block column holding a worker's first group        */
 } oracle_hbp;
 
 typedef struct { int64_t *cnt; int64_t NBR; int32_t R; } count_ctx;
@@ -165,12 +169,12 @@ void oracle_hbp_free(oracle_hbp *h)
     if (!h) return;
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_slot);
-    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->add_sign);
+    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
     free(h);
 }
 
 /* Build the compact layout.  hash_shift < 0 samples a.  num_workers P and fixed_q8
- * (share of blocks pre-assigned, in 1/256) give F = floor(B * fixed_q8 / (256 P)).
+ * (share of the work pre-assigned, in 1/256) define the schedule arrays.
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8)
@@ -287,24 +291,52 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
         h->stripe_ptr[NBR] = (int32_t)k;
     }
 
-    /* Section 3.3: the first P*F blocks of the (column-major) list are fixed, F per
-     * worker in list order; the rest are competitive, claimed in list order */
-    h->P = num_workers;
-    h->F = (B * (int64_t)fixed_q8) / (256 * num_workers);
+    /* Section 3.3, mixed execution allocation.  The unit handed to a wavefront is a group; the
+     * weight of a group is its nonzeros plus its slots, so Wt(g) = group_ptr[g] + group_slot[g]
+     * is the weight of all groups before g.
+     *   - every block column keeps the first fixed_q8/256 of its weight as its fixed part and
+     *     leaves the rest to competition: comp_lo[c] is the column's first competitive group;
+     *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
+     *     the first group of worker w; a worker runs the fixed groups inside its range and then
+     *     competes, starting with the column it is on. */
+    h->P = num_workers; h->fixed_q8 = fixed_q8;
+    h->col_group_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
+    h->comp_lo = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
+    h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
+    h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
+    for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
+    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)h->group_slot[g])
+    for (int64_t c = 0; c < NBC; c++) {
+        int64_t g0 = h->col_group_ptr[c], g1 = h->col_group_ptr[c + 1], g = g0;
+        while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;
+        h->comp_lo[c] = (int32_t)g;
+    }
+    {
+        int64_t g = 0, c = 0;
+        for (int64_t w = 0; w <= num_workers; w++) {
+            while (g < G && WT(g) * num_workers < w * WT(G)) g++;
+            h->fixed_start[w] = (int32_t)g;
+            if (w == num_workers) break;
+            while (c + 1 < NBC && h->col_group_ptr[c + 1] <= g) c++;   /* last column starting at or before g */
+            h->fixed_col[w] = (int32_t)c;
+        }
+    }
+    #undef WT
 
     free(cnt); free(cursor); free(compact_id); free(tq); free(tn); free(tj); free(slot_j); free(table);
     return h;
 }
 
-/* dims[0..13] = n_rows n_cols nnz R C W a NBR NBC B S G P F */
+/* dims[0..13] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 */
 void oracle_hbp_dims(const oracle_hbp *h, int64_t *dims)
 {
-    int64_t v[14] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->F };
+    int64_t v[14] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8 };
     memcpy(dims, v, sizeof v);
 }
 
 /* which: 0 blk_bm 1 blk_bn 2 slot_ptr 3 blk_group_ptr 4 col_blk_ptr 5 stripe_ptr 6 stripe_blk
- *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign.
+ *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign
+ *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col.
  * Copies the array into dst and returns its size in bytes (0 for an unknown id). */
 int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
 {
@@ -324,6 +356,10 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 11: src = h->col_local; bytes = 2 * h->nnz; break;
     case 12: src = h->data; bytes = 4 * h->nnz; break;
     case 13: src = h->add_sign; bytes = 4 * h->nnz; break;
+    case 14: src = h->col_group_ptr; bytes = 4 * (h->NBC + 1); break;
+    case 15: src = h->comp_lo; bytes = 4 * h->NBC; break;
+    case 16: src = h->fixed_start; bytes = 4 * (h->P + 1); break;
+    case 17: src = h->fixed_col; bytes = 4 * h->P; break;
     default: return 0;
     }
     if (dst && bytes) memcpy(dst, src, (size_t)bytes);

@@ -18,13 +18,15 @@ HBP_FLAG_VALIDATE = 1
 ARRAY_IDS = {
     "blk_bm": 0, "blk_bn": 1, "slot_ptr": 2, "blk_group_ptr": 3, "col_blk_ptr": 4, "stripe_ptr": 5,
     "stripe_blk": 6, "group_ptr": 7, "group_slot": 8, "row_local": 9, "seg_len": 10, "col_local": 11,
-    "data": 12, "add_sign": 13, "partial": 14,
+    "data": 12, "add_sign": 13, "partial": 14, "col_group_ptr": 15, "comp_lo": 16,
+    "fixed_start": 17, "fixed_col": 18,
 }
 ARRAY_DTYPES = {
     "blk_bm": "int32", "blk_bn": "int32", "slot_ptr": "int32", "blk_group_ptr": "int32", "col_blk_ptr": "int32",
     "stripe_ptr": "int32", "stripe_blk": "int32", "group_ptr": "int32", "group_slot": "int32",
     "row_local": "uint16", "seg_len": "uint16", "col_local": "uint16", "data": "float32", "add_sign": "int32",
-    "partial": "float32",
+    "partial": "float32", "col_group_ptr": "int32", "comp_lo": "int32",
+    "fixed_start": "int32", "fixed_col": "int32",
 }
 # every symbol include/hbp.h declares
 EXPORTED_SYMBOLS = (
@@ -36,7 +38,8 @@ EXPORTED_SYMBOLS = (
 class hbp_params_t(ctypes.Structure):
     _fields_ = [("rows_per_block", ctypes.c_int32), ("cols_per_block", ctypes.c_int32), ("group_width", ctypes.c_int32),
                 ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("hash_shift", ctypes.c_int32),
-                ("claim_chunk", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("claim_chunk", ctypes.c_int32), ("threads_per_worker", ctypes.c_int32),
+                ("rounds_per_batch", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
 
 class hbp_info_t(ctypes.Structure):
@@ -45,8 +48,8 @@ class hbp_info_t(ctypes.Structure):
                 ("hash_shift", ctypes.c_int32), ("hash_b", ctypes.c_int32),
                 ("row_blocks", ctypes.c_int64), ("col_blocks", ctypes.c_int64),
                 ("blocks", ctypes.c_int64), ("slots", ctypes.c_int64), ("groups", ctypes.c_int64),
-                ("num_workers", ctypes.c_int32), ("fixed_per_worker", ctypes.c_int32), ("claim_chunk", ctypes.c_int32),
-                ("threads_per_worker", ctypes.c_int32),
+                ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("claim_chunk", ctypes.c_int32),
+                ("threads_per_worker", ctypes.c_int32), ("rounds_per_batch", ctypes.c_int32),
                 ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
                 ("build_ms", ctypes.c_double)]
 

@@ -26,7 +26,7 @@ struct DeviceGuard {  // makes the handle's device current for the duration of a
 void free_arrays(hbp_handle_s *h)
 {
     void *ptrs[] = {h->blk_bm, h->blk_bn, h->slot_ptr, h->blk_group_ptr, h->col_blk_ptr, h->stripe_ptr, h->stripe_blk,
-                    h->group_ptr, h->group_slot, h->row_local, h->seg_len, h->col_local, h->data, h->partial, h->ticket};
+                    h->group_ptr, h->group_slot, h->col_group_ptr, h->comp_lo, h->fixed_start, h->fixed_col, h->row_local, h->seg_len, h->col_local, h->data, h->partial, h->ticket};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -45,6 +45,8 @@ int hbp_default_params(hbp_params_t *p)
     p->fixed_fraction_q8 = -1;
     p->hash_shift = -1;
     p->claim_chunk = 0;
+    p->threads_per_worker = 0;
+    p->rounds_per_batch = 0;
     p->flags = HBP_FLAG_VALIDATE;
     return HBP_OK;
 }
@@ -62,11 +64,15 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.rows_per_block == 0) p.rows_per_block = 512;
     if (p.cols_per_block == 0) p.cols_per_block = 4096;
     if (p.group_width == 0) p.group_width = 64;
-    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 128;
+    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
     if (p.claim_chunk == 0) p.claim_chunk = 1;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > (1 << 20) ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1)
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1 ||
+        (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
+         p.threads_per_worker != 1024) ||
+        (p.rounds_per_batch != 0 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 && p.rounds_per_batch != 9 &&
+         p.rounds_per_batch != 16))
         return HBP_ERR_INVALID_ARGUMENT;
 
     const auto t0 = std::chrono::steady_clock::now();
@@ -82,9 +88,11 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     int rc = HBP_OK;
     if (h->NBR * h->NBC > hbp::kMaxDense) rc = HBP_ERR_TOO_LARGE;
     int32_t threads = 0, workers = 0;
-    if (rc == HBP_OK) rc = hbp::default_workers(h->device, h->C, &threads, &workers);
+    if (rc == HBP_OK) rc = hbp::default_workers(h->device, h->C, p.threads_per_worker, &threads, &workers);
     if (rc == HBP_OK) {
         h->threads = threads;
+        h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
+        h->fixed_q8 = p.fixed_fraction_q8;
         h->P = p.num_workers > 0 ? p.num_workers : workers;
         rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
     }
@@ -94,8 +102,12 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         delete h;
         return rc;
     }
-    // Section 3.3: the first P*F list entries are fixed (F per worker), the rest competitive
-    h->F = (int32_t)((h->B * (int64_t)p.fixed_fraction_q8) / (256 * (int64_t)h->P));
+    rc = hbp::build_schedule(h, (hipStream_t)stream);
+    if (rc != HBP_OK) {
+        free_arrays(h);
+        delete h;
+        return rc;
+    }
     h->build_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *out = h;
     return HBP_OK;
@@ -163,8 +175,9 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->hash_b = h->R / 9 > 0 ? h->R / 9 : 1;
     info->row_blocks = h->NBR; info->col_blocks = h->NBC;
     info->blocks = h->B; info->slots = h->S; info->groups = h->G;
-    info->num_workers = h->P; info->fixed_per_worker = h->F; info->claim_chunk = h->claim_chunk;
+    info->num_workers = h->P; info->fixed_fraction_q8 = h->fixed_q8; info->claim_chunk = h->claim_chunk;
     info->threads_per_worker = h->threads;
+    info->rounds_per_batch = h->unroll;
     const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
     const int64_t grp = 4 * 2 * (h->G + 1);
     info->bytes_layout = blk + grp + 2 * 2 * h->S + 6 * h->nnz;
@@ -200,6 +213,10 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_DATA: src = h->data; bytes = 4 * (size_t)h->nnz; break;
     case HBP_ARRAY_ADD_SIGN: bytes = 4 * (size_t)h->nnz; break;
     case HBP_ARRAY_PARTIAL: src = h->partial; bytes = 4 * (size_t)h->S; break;
+    case HBP_ARRAY_COL_GROUP_PTR: src = h->col_group_ptr; bytes = 4 * (size_t)(h->NBC + 1); break;
+    case HBP_ARRAY_COMP_LO: src = h->comp_lo; bytes = 4 * (size_t)h->NBC; break;
+    case HBP_ARRAY_FIXED_START: src = h->fixed_start; bytes = 4 * (size_t)(h->P + 1); break;
+    case HBP_ARRAY_FIXED_COL: src = h->fixed_col; bytes = 4 * (size_t)h->P; break;
     default: return HBP_ERR_INVALID_ARGUMENT;
     }
     if (bytes_out) *bytes_out = bytes;

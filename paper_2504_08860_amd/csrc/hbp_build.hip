@@ -482,6 +482,61 @@ __global__ __launch_bounds__(256) void k_add_sign(const int32_t *__restrict__ gr
     }
 }
 
+// ------------------------------------------------------------------ Section 3.3: schedule
+//
+// Weight of a group = its nonzeros + its slots; Wt(g) = group_ptr[g] + group_slot[g] is the
+// weight of all groups before g.
+
+__global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict__ col_blk_ptr, const int32_t *__restrict__ blk_group_ptr,
+                                                       int32_t NBC, int32_t *__restrict__ col_group_ptr)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c <= NBC) col_group_ptr[c] = blk_group_ptr[col_blk_ptr[c]];
+}
+
+// comp_lo[c]: first group of column c left to competition, i.e. the first g in the column whose
+// preceding weight inside the column reaches fixed_q8/256 of the column's weight.
+__global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
+                                                 const int32_t *__restrict__ group_slot, int32_t NBC, int32_t fixed_q8,
+                                                 int32_t *__restrict__ comp_lo)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= NBC) return;
+    const int32_t g0 = col_group_ptr[c], g1 = col_group_ptr[c + 1];
+    const int64_t w0 = (int64_t)group_ptr[g0] + group_slot[g0];
+    const int64_t need = ((int64_t)group_ptr[g1] + group_slot[g1] - w0) * fixed_q8;
+    int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with (Wt(g) - w0) * 256 >= need
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (((int64_t)group_ptr[mid] + group_slot[mid] - w0) * 256 >= need) hi = mid; else lo = mid + 1;
+    }
+    comp_lo[c] = lo;
+}
+
+// fixed_start[w]: first g with Wt(g) * P >= w * Wt(G) (P contiguous ranges of equal weight);
+// fixed_col[w]: the last block column that starts at or before that group.
+__global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
+                                                     const int32_t *__restrict__ group_slot, int32_t NBC, int32_t G, int32_t P,
+                                                     int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
+{
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w > P) return;
+    const int64_t need = w * ((int64_t)group_ptr[G] + group_slot[G]);
+    int32_t lo = 0, hi = G;
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (((int64_t)group_ptr[mid] + group_slot[mid]) * P >= need) hi = mid; else lo = mid + 1;
+    }
+    fixed_start[w] = lo;
+    if (w == P) return;
+    int32_t c_lo = 0, c_hi = NBC - 1;  // largest c with col_group_ptr[c] <= lo
+    while (c_lo < c_hi) {
+        const int32_t mid = c_lo + ((c_hi - c_lo + 1) >> 1);
+        if (col_group_ptr[mid] <= lo) c_lo = mid; else c_hi = mid - 1;
+    }
+    fixed_col[w] = c_lo;
+}
+
 struct DeviceBuffers {  // frees every temporary on scope exit
     std::vector<void *> ptrs;
     ~DeviceBuffers() { for (void *p : ptrs) (void)hipFree(p); }
@@ -531,8 +586,16 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     // arrays whose size does not depend on the matrix content
     HBP_TRY(alloc_owned(&h->col_blk_ptr, NBC + 1));
     HBP_TRY(alloc_owned(&h->stripe_ptr, NBR + 1));
-    HBP_TRY(alloc_owned(&h->ticket, 1));
-    HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t), st));
+    HBP_TRY(alloc_owned(&h->ticket, NBC));
+    HBP_TRY(alloc_owned(&h->comp_lo, NBC));
+    HBP_TRY(alloc_owned(&h->col_group_ptr, NBC + 1));
+    HBP_TRY(alloc_owned(&h->fixed_start, (int64_t)h->P + 1));
+    HBP_TRY(alloc_owned(&h->fixed_col, (int64_t)h->P));
+    HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
+    HBP_HIP(hipMemsetAsync(h->comp_lo, 0, sizeof(int32_t) * (size_t)NBC, st));
+    HBP_HIP(hipMemsetAsync(h->col_group_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
+    HBP_HIP(hipMemsetAsync(h->fixed_start, 0, sizeof(int32_t) * (size_t)(h->P + 1), st));
+    HBP_HIP(hipMemsetAsync(h->fixed_col, 0, sizeof(int32_t) * (size_t)h->P, st));
     HBP_HIP(hipMemsetAsync(h->col_blk_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->stripe_ptr, 0, sizeof(int32_t) * (size_t)(NBR + 1), st));
 
@@ -650,6 +713,22 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     // step 7
     k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
                                              slot_j, (int32_t)G, C, h->col_local, h->data);
+    HBP_HIP(hipGetLastError());
+    HBP_HIP(hipStreamSynchronize(st));
+    return HBP_OK;
+}
+
+// Section 3.3: which groups are pre-assigned to which worker and which are left to competition.
+int build_schedule(hbp_handle_s *h, hipStream_t st)
+{
+    if (h->G > 0) {
+        const int32_t NBC = (int32_t)h->NBC;
+        k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
+        k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC, h->fixed_q8,
+                                                           h->comp_lo);
+        k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC,
+                                                                          (int32_t)h->G, h->P, h->fixed_start, h->fixed_col);
+    }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));
     return HBP_OK;

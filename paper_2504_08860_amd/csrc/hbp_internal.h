@@ -21,6 +21,7 @@ struct Layout {
     int64_t n_rows, n_cols;
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot;
+    const int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;  // schedule (Section 3.3)
     const uint16_t *row_local, *seg_len, *col_local;
     const float *data;
 };
@@ -32,15 +33,17 @@ struct hbp_handle_s {
     int64_t n_rows, n_cols, nnz;
     int32_t R, C, W, a;
     int64_t NBR, NBC, B, S, G;
-    int32_t P, F, claim_chunk, threads;
+    int32_t P, fixed_q8, claim_chunk, threads;
+    int32_t unroll;      // rounds taken per batch by the SpMV-part kernel (4, 8, 9 or 16)
     double build_ms;
     // device arrays (owned)
     int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     int32_t *group_ptr, *group_slot;
+    int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;
     uint16_t *row_local, *seg_len, *col_local;
     float *data;
     float *partial;      // [S] per-slot partial sums of the SpMV part
-    uint32_t *ticket;    // competitive-part ticket counter, zero between calls
+    uint32_t *ticket;    // [NBC] competitive-part ticket counters, zero between calls
 };
 
 namespace hbp {
@@ -59,11 +62,12 @@ void set_last_hip_error(hipError_t e);
 // build (hbp_build.hip)
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
                  const hbp_params_t &p, hipStream_t stream);
+int build_schedule(hbp_handle_s *h, hipStream_t stream);
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
 
 // spmv (hbp_spmv.hip)
 Layout hbp_view(const hbp_handle_s *h);
-int default_workers(int device, int32_t C, int32_t *threads_out, int32_t *workers_out);
+int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
 int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t stream);
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t stream);
 int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,

@@ -1,11 +1,11 @@
 // Two-step HBP SpMV (Fig. 1, Algorithm 3, Section 3.3) and the in-repo CSR baselines.
 //
-// SpMV part: P persistent workgroups ("workers").  A worker first runs its F fixed blocks,
-// a contiguous piece of the column-major block list, then claims chunks of the remaining
-// (competitive) blocks through an atomic ticket counter until none are left.  Before it
-// touches a block column it stages that column's slice of x in LDS; blocks of one column are
-// adjacent in the list, so a slice is staged once per run of blocks.  Each wavefront takes
-// groups of the run; lane q owns slot q of the group and walks its row round by round.  The
+// SpMV part: P persistent workgroups ("workers").  A worker first runs its fixed groups, a
+// contiguous piece of the column-major group list, then competes for the rest: each block
+// column has an atomic ticket counter over its competitive groups, and a worker draws tickets
+// from the column whose slice of x it has staged in LDS (the paper's single ticket lock, split
+// per column so that a 128 KB slice is not restaged for every claim).  A wavefront takes one
+// group at a time; lane q owns slot q of the group and walks its row round by round.  The
 // distance add_sign of Algorithm 3 is not read from memory: in round k the lanes still alive
 // are known from a ballot over the lane lengths, and a lane's element is the base of the
 // round plus the number of live lanes below it.
@@ -22,66 +22,194 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t P, int32_t F, int32_t chunk,
-                                                       const float *__restrict__ x, float *__restrict__ partial,
-                                                       uint32_t *__restrict__ ticket)
+// Wave-uniform read of a layout array that no kernel writes while an SpMV runs.  Going through
+// the constant address space lets the compiler use a scalar load, whose result lands in an
+// SGPR without a wait at the point of issue: this is what keeps the prefetch of the next
+// groups' metadata off the critical path.
+__device__ __forceinline__ int32_t uniform_load(const int32_t *p, int32_t i)
 {
-    extern __shared__ float xs[];  // the staged vector segment, C floats
-    __shared__ int32_t sh_ticket;
-    constexpr int kWaves = THREADS / 64;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int staged_bn = -1;
+    typedef const int32_t __attribute__((address_space(4))) *const_ptr;
+    return ((const_ptr)(uintptr_t)p)[i];
+}
 
-    auto run_blocks = [&](int32_t e0, int32_t e1) {  // list entries [e0, e1), uniform over the workgroup
-        int32_t b = e0;
-        while (b < e1) {
-            const int32_t bn = L.blk_bn[b];
-            const int32_t be = min(e1, L.col_blk_ptr[bn + 1]);  // end of the run of blocks in column bn
-            if (bn != staged_bn) {
-                __syncthreads();  // every wavefront is done with the previous slice
-                const int64_t c0 = (int64_t)bn * L.C;
-                const int32_t width = (int32_t)min((int64_t)L.C, L.n_cols - c0);
-                for (int32_t i = threadIdx.x; i < width; i += THREADS) xs[i] = x[c0 + i];
-                __syncthreads();
-                staged_bn = bn;
-            }
-            const int32_t g1 = L.blk_group_ptr[be];
-            for (int32_t g = L.blk_group_ptr[b] + wave; g < g1; g += kWaves) {
-                const int32_t s0 = L.group_slot[g], cnt = L.group_slot[g + 1] - s0;
-                const int32_t n = lane < cnt ? L.seg_len[s0 + lane] : 0;
-                int64_t base = L.group_ptr[g];
-                float acc = 0.f;
-                for (int32_t k = 0;; k++) {
-                    const uint64_t live = __ballot(k < n);
-                    if (!live) break;
-                    if (k < n) {
-                        const int64_t j = base + lanes_below(live);
-                        acc += L.data[j] * xs[L.col_local[j]];
-                    }
-                    base += __popcll(live);
-                }
-                if (lane < cnt) partial[s0 + lane] = acc;
-            }
-            b = be;
-        }
-    };
+// One group, one wavefront.  Lane q owns slot q and has n nonzeros.  Rounds are taken U at a
+// time ("a batch"): the U ballots give each round's live lanes, a lane's element in a round
+// sits at the round's base plus the number of live lanes below it, all 2U loads are issued,
+// then the products are accumulated through the staged vector segment.
+template <int U>
+struct Batch {
+    uint32_t c[U];
+    float v[U];
+};
 
-    // fixed part: worker w owns list entries [w F, (w+1) F)
-    run_blocks((int32_t)blockIdx.x * F, ((int32_t)blockIdx.x + 1) * F);
-    // competitive part: tickets hand out chunks of the rest of the list in order
-    const int64_t first = (int64_t)P * F;
-    for (;;) {
-        if (threadIdx.x == 0) sh_ticket = (int32_t)atomicAdd(ticket, 1u);
-        __syncthreads();
-        const int64_t e0 = first + (int64_t)sh_ticket * chunk;
-        __syncthreads();
-        if (e0 >= L.B) break;
-        run_blocks((int32_t)e0, (int32_t)min((int64_t)L.B, e0 + chunk));
+// Issues the loads of rounds k .. k+U-1 and advances base past them.  `first` is a position
+// that is always valid: lanes without an element in a round read it (and discard the
+// product), so no load is predicated.
+template <int U>
+__device__ __forceinline__ void issue_batch(Batch<U> &b, const uint16_t *__restrict__ col_local,
+                                            const float *__restrict__ data, uint32_t &base, uint32_t first, int32_t n,
+                                            int32_t k)
+{
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const uint64_t live = __ballot(k + u < n);
+        const uint32_t j = k + u < n ? base + (uint32_t)lanes_below(live) : first;
+        b.c[u] = __builtin_nontemporal_load(col_local + j);
+        b.v[u] = __builtin_nontemporal_load(data + j);
+        base += (uint32_t)__popcll(live);
     }
 }
 
-// Combine part.  Also re-arms the ticket counter for the next call (the SpMV part of this
+template <int U>
+__device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *xs, int32_t n, int32_t k)
+{
+    float xv[U], acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; u++) xv[u] = xs[b.c[u]];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+        const float p = b.v[u] * xv[u];
+        acc += k + u < n ? p : 0.f;
+    }
+    return acc;
+}
+
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
+                                                       const float *__restrict__ x, float *__restrict__ partial,
+                                                       uint32_t *__restrict__ col_ticket)
+{
+    extern __shared__ float xs[];  // the staged vector segment, C floats
+    __shared__ int32_t sh_next;
+    constexpr int kWaves = THREADS / 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int staged_bn = -1;
+
+    // Stage the vector segment of block column bn (uniform over the workgroup).
+    auto stage = [&](int32_t bn) {
+        if (bn == staged_bn) return;
+        __syncthreads();  // every wavefront is done with the previous segment
+        const int64_t c0 = (int64_t)bn * L.C;
+        const int32_t width = (int32_t)min((int64_t)L.C, L.n_cols - c0);
+        for (int32_t i = threadIdx.x; i < width; i += THREADS) xs[i] = x[c0 + i];
+        __syncthreads();
+        staged_bn = bn;
+    };
+
+    // This wavefront's groups g, g + stride, ... below g_end, as a two-deep software pipeline:
+    // while a group is walked, the lane lengths of the next one and the slot range / first
+    // position of the one after it are already on their way.
+    auto walk_range = [&](int32_t g, int32_t g_end, int32_t stride) {
+        int32_t s0 = 0, s1 = 0, n = 0, s0n = 0, s1n = 0;
+        uint32_t base = 0, basen = 0;  // positions stay 32-bit: nnz < 2^31
+        if (g < g_end) {
+            s0 = uniform_load(L.group_slot, g);
+            s1 = uniform_load(L.group_slot, g + 1);
+            base = (uint32_t)uniform_load(L.group_ptr, g);
+            n = s0 + lane < s1 ? L.seg_len[s0 + lane] : 0;
+        }
+        if (g + stride < g_end) {
+            s0n = uniform_load(L.group_slot, g + stride);
+            s1n = uniform_load(L.group_slot, g + stride + 1);
+            basen = (uint32_t)uniform_load(L.group_ptr, g + stride);
+        }
+        while (g < g_end) {
+            const int32_t g2 = g + 2 * stride;
+            int32_t s0nn = 0, s1nn = 0;
+            uint32_t basenn = 0;
+            if (g2 < g_end) {
+                s0nn = uniform_load(L.group_slot, g2);
+                s1nn = uniform_load(L.group_slot, g2 + 1);
+                basenn = (uint32_t)uniform_load(L.group_ptr, g2);
+            }
+            // first batch in straight-line code, with the next group's lane lengths requested
+            // right behind its loads; further batches only for rows longer than U
+            Batch<U> bt;
+            const uint32_t first = base;
+            issue_batch<U>(bt, L.col_local, L.data, base, first, n, 0);
+            const int32_t nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
+            float acc = consume_batch<U>(bt, xs, n, 0);
+            for (int32_t k = U; __ballot(k < n); k += U) {
+                issue_batch<U>(bt, L.col_local, L.data, base, first, n, k);
+                acc += consume_batch<U>(bt, xs, n, k);
+            }
+            if (s0 + lane < s1) partial[s0 + lane] = acc;
+            g += stride;
+            s0 = s0n; s1 = s1n; base = basen; n = nn;
+            s0n = s0nn; s1n = s1nn; basen = basenn;
+        }
+    };
+
+    // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
+    // worker w runs, column by column, the groups of its range that lie in the fixed part of
+    // their column (below comp_lo).  Groups are dealt round-robin to the wavefronts.
+    int32_t home = 0;
+    {
+        int32_t g = L.fixed_start[blockIdx.x];
+        const int32_t g_end = L.fixed_start[blockIdx.x + 1];
+        int32_t c = L.fixed_col[blockIdx.x];
+        home = c;
+        while (g < g_end) {
+            const int32_t c_end = L.col_group_ptr[c + 1];
+            if (g >= c_end) { c++; continue; }  // columns without groups
+            const int32_t ge = min(g_end, c_end), fe = min(ge, L.comp_lo[c]);
+            if (g < fe) {
+                stage(c);
+                walk_range(g + wave, fe, kWaves);
+            }
+            home = c;
+            g = ge;
+        }
+    }
+
+    // Competitive part.  Every block column has a ticket counter over its competitive groups,
+    // [comp_lo, end of column); a ticket is worth `chunk` groups per wavefront.  A worker keeps
+    // drawing from the column it is on (its segment is staged already); when that column runs
+    // dry it moves to the column with the most groups left, and stages that segment only once
+    // a ticket there has actually given it work.
+    const int32_t per_ticket = kWaves * chunk;
+    int32_t bn = home;
+    for (;;) {
+        if (threadIdx.x == 0) sh_next = (int32_t)atomicAdd(&col_ticket[bn], 1u);
+        __syncthreads();
+        const int64_t g0 = L.comp_lo[bn] + (int64_t)sh_next * per_ticket;
+        const int32_t hi = L.col_group_ptr[bn + 1];
+        __syncthreads();  // sh_next is rewritten below
+        if (g0 < hi) {
+            stage(bn);
+            walk_range((int32_t)g0 + wave, (int32_t)min((int64_t)hi, g0 + per_ticket), kWaves);
+            continue;
+        }
+        if (wave == 0) {  // this column is dry: look for the one with the most groups left
+            int32_t best = -1;
+            uint32_t best_left = 0;
+            for (int32_t c0 = 0; c0 < L.NBC; c0 += 64) {
+                int32_t c = c0 + lane;
+                uint32_t left = 0;
+                if (c < L.NBC) {
+                    const int64_t total = L.col_group_ptr[c + 1] - L.comp_lo[c];
+                    const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * per_ticket;
+                    left = used < total ? (uint32_t)(total - used) : 0u;
+                }
+#pragma unroll
+                for (int d = 32; d > 0; d >>= 1) {
+                    const uint32_t o_left = __shfl_xor(left, d);
+                    const int32_t o_c = __shfl_xor(c, d);
+                    if (o_left > left || (o_left == left && o_c < c)) { left = o_left; c = o_c; }
+                }
+                if (left > best_left) { best_left = left; best = c; }
+            }
+            if (lane == 0) sh_next = best;
+        }
+        __syncthreads();
+        bn = sh_next;
+        __syncthreads();
+        if (bn < 0) break;
+    }
+}
+
+// Combine part.  Also re-arms the per-column ticket counters for the next call (the SpMV part of this
 // call has finished: same stream).
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__restrict__ partial, float *__restrict__ y,
@@ -89,7 +217,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
 {
     extern __shared__ float ys[];  // R floats
     const int32_t bm = blockIdx.x;
-    if (bm == 0 && threadIdx.x == 0) *ticket = 0u;
+    for (int64_t i = (int64_t)bm * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
     const int64_t r0 = (int64_t)bm * L.R;
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
     for (int32_t i = threadIdx.x; i < rows; i += THREADS) ys[i] = 0.f;
@@ -144,18 +272,20 @@ Layout hbp_view(const hbp_handle_s *h)
     L.col_blk_ptr = h->col_blk_ptr; L.stripe_ptr = h->stripe_ptr; L.stripe_blk = h->stripe_blk;
     L.group_ptr = h->group_ptr; L.group_slot = h->group_slot;
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
+    L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
+    L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
     return L;
 }
 
 // Workers the schedule is built for when the caller does not say: as many workgroups as fit
 // on the device at once given the LDS a vector segment takes.
-int default_workers(int device, int32_t C, int32_t *threads_out, int32_t *workers_out)
+int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out)
 {
     hipDeviceProp_t prop;
     HBP_HIP(hipGetDeviceProperties(&prop, device));
     const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     const size_t lds = (size_t)C * sizeof(float) + 64;
-    const int threads = lds > 80 * 1024 ? 1024 : 512;
+    const int threads = threads_wanted ? threads_wanted : (lds > 80 * 1024 ? 1024 : 512);
     int per_cu = (int)((160 * 1024) / lds);
     const int by_threads = 2048 / threads;
     if (per_cu > by_threads) per_cu = by_threads;
@@ -165,22 +295,38 @@ int default_workers(int device, int32_t C, int32_t *threads_out, int32_t *worker
     return HBP_OK;
 }
 
+template <int THREADS, int U>
+static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
+{
+    const size_t lds = (size_t)h->C * sizeof(float);
+    static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
+    if (configured_device != h->device) {
+        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kMaxC * (int)sizeof(float)));
+        configured_device = h->device;
+    }
+    k_spmv_part<THREADS, U><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket);
+    HBP_HIP(hipGetLastError());
+    return HBP_OK;
+}
+
+template <int THREADS>
+static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
+{
+    switch (h->unroll) {
+    case 4: return launch_part<THREADS, 4>(h, L, x, st);
+    case 9: return launch_part<THREADS, 9>(h, L, x, st);
+    case 16: return launch_part<THREADS, 16>(h, L, x, st);
+    default: return launch_part<THREADS, 8>(h, L, x, st);
+    }
+}
+
 int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st)
 {
     const Layout L = hbp_view(h);
-    const size_t lds = (size_t)h->C * sizeof(float);
-    if (h->threads == 1024) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        k_spmv_part<1024><<<dim3((unsigned)h->P), 1024, lds, st>>>(L, h->P, h->F, h->claim_chunk, x, h->partial, h->ticket);
-    } else if (h->threads == 512) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<512>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        k_spmv_part<512><<<dim3((unsigned)h->P), 512, lds, st>>>(L, h->P, h->F, h->claim_chunk, x, h->partial, h->ticket);
-    } else {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<256>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        k_spmv_part<256><<<dim3((unsigned)h->P), 256, lds, st>>>(L, h->P, h->F, h->claim_chunk, x, h->partial, h->ticket);
-    }
-    HBP_HIP(hipGetLastError());
-    return HBP_OK;
+    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, st);
+    if (h->threads == 512) return launch_part_u<512>(h, L, x, st);
+    return launch_part_u<256>(h, L, x, st);
 }
 
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)

@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
-                 "group_ptr", "group_slot", "row_local", "seg_len", "col_local", "data", "add_sign")
+                 "group_ptr", "group_slot", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col", "row_local", "seg_len", "col_local", "data", "add_sign")
 
 
 @pytest.fixture(scope="module")
@@ -37,10 +37,9 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
         info = H.hbp_get_info(h)
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
                              W=info.group_width, hash_shift=params.get("hash_shift", -1),
-                             num_workers=info.num_workers,
-                             fixed_q8=params.get("fixed_fraction_q8", 128) if params.get("fixed_fraction_q8", -1) >= 0 else 128)
+                             num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
-        assert info.hash_shift == o.a and info.fixed_per_worker == o.F
+        assert info.hash_shift == o.a
         assert info.hash_b == max(1, info.rows_per_block // 9)
         for name in LAYOUT_ARRAYS:
             if name == "add_sign" and not check_add_sign:

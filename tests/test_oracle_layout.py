@@ -51,6 +51,10 @@ def test_worked_example_compact(oracle):
     y, partial = h.spmv(m.x)
     assert y.tolist() == g["y"]
     assert partial.tolist() == g["compact"]["partial"]
+    sch = g["schedule"]
+    h2 = build(oracle, m, R=g["R"], C=g["C"], W=g["W"], hash_shift=g["a"], num_workers=sch["P"], fixed_q8=sch["fixed_q8"])
+    for name in ("col_group_ptr", "comp_lo", "fixed_start", "fixed_col"):
+        assert h2.array(name).tolist() == sch[name], name
 
 
 # ---------------------------------------------------------------- brute force helpers
@@ -217,12 +221,39 @@ def test_equal_rows_any_w_is_ell(oracle):
 
 
 def test_schedule_split(oracle):
+    """Section 3.3 split: fixed groups of the P ranges and the per-column competitive tails cover
+    every group exactly once; ranges have equal weight up to one group; every column keeps the
+    stated share of its weight fixed, up to one group."""
     m = random_csr(300, 300, 0.05, 3)
-    for P, q8 in [(1, 128), (4, 192), (7, 255), (64, 256), (5, 0)]:
+    for P, q8 in [(1, 128), (4, 192), (7, 255), (64, 256), (5, 0), (1000, 100)]:
         h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8)
-        assert h.P == P and h.F == (h.B * q8) // (256 * P)
-        assert P * h.F <= h.B                                     # fixed lists are disjoint prefixes
-        # equal number of fixed blocks per worker; everything else is competitive
+        assert h.P == P and h.fixed_q8 == q8
+        wt = h.array("group_ptr").astype(np.int64) + h.array("group_slot")
+        cgp, comp_lo = h.array("col_group_ptr"), h.array("comp_lo")
+        fs, fc = h.array("fixed_start"), h.array("fixed_col")
+        assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
+        assert fs[0] == 0 and fs[-1] == h.G and np.all(np.diff(fs) >= 0)
+        col_of = np.searchsorted(cgp, np.arange(h.G), side="right") - 1
+        covered = np.zeros(h.G, dtype=np.int32)
+        for w in range(P):
+            gs = np.arange(fs[w], fs[w + 1])
+            covered[gs[gs < comp_lo[col_of[gs]]]] += 1            # the worker's fixed groups
+            if fs[w] < h.G:
+                assert fc[w] == col_of[fs[w]]
+            # equal weight: the range starts at the first group whose preceding weight reaches w/P
+            assert wt[fs[w]] * P >= w * wt[-1]
+            assert fs[w] == 0 or wt[fs[w] - 1] * P < w * wt[-1]
+        for c in range(h.NBC):
+            covered[comp_lo[c]:cgp[c + 1]] += 1                    # the column's competitive groups
+            assert cgp[c] <= comp_lo[c] <= cgp[c + 1]
+            tot = wt[cgp[c + 1]] - wt[cgp[c]]
+            assert (wt[comp_lo[c]] - wt[cgp[c]]) * 256 >= tot * q8
+            assert comp_lo[c] == cgp[c] or (wt[comp_lo[c] - 1] - wt[cgp[c]]) * 256 < tot * q8
+        assert np.all(covered == 1)
+        if q8 == 256:
+            assert np.array_equal(comp_lo, cgp[1:])                # nothing left to competition
+        if q8 == 0:
+            assert np.array_equal(comp_lo, cgp[:-1])               # everything competitive
 
 
 def test_hash_groups_similar_rows(oracle):
