@@ -41,6 +41,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-csr", action="store_true")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1",
@@ -87,6 +89,14 @@ def main() -> int:
     log(f"[bench] R={info.rows_per_block} C={info.cols_per_block} W={info.group_width} a={info.hash_shift} "
         f"blocks={info.blocks} slots={info.slots} groups={info.groups} P={info.num_workers} "
         f"fixed_q8={info.fixed_fraction_q8} threads={info.threads_per_worker} build_ms={[round(b, 2) for b in build_ms]}")
+
+    if args.calibrate_copy:  # a copy kernel of known size: 2^28 bytes read, 2^28 bytes written
+        src = torch.empty(1 << 26, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # the timed region: exactly K steps between synchronisations
     for _ in range(args.warmup):

@@ -74,7 +74,7 @@ __device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *x
     return acc;
 }
 
-template <int THREADS, int U>
+template <int THREADS, int U, int GP>
 __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                                                        const float *__restrict__ x, float *__restrict__ partial,
                                                        uint32_t *__restrict__ col_ticket)
@@ -97,48 +97,82 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         staged_bn = bn;
     };
 
-    // This wavefront's groups g, g + stride, ... below g_end, as a two-deep software pipeline:
-    // while a group is walked, the lane lengths of the next one and the slot range / first
-    // position of the one after it are already on their way.
+    // This wavefront's groups g, g + stride, ... below g_end, GP of them per iteration, as a
+    // two-deep software pipeline: while GP groups are walked, the lane lengths of the next GP
+    // and the slot ranges / first positions of the GP after those are already on their way.
+    // The loads of all GP groups' first batches are issued before any of them is consumed.
+    // A group index at or beyond g_end gives an idle lane set (n = 0, position 0).
     auto walk_range = [&](int32_t g, int32_t g_end, int32_t stride) {
-        int32_t s0 = 0, s1 = 0, n = 0, s0n = 0, s1n = 0;
-        uint32_t base = 0, basen = 0;  // positions stay 32-bit: nnz < 2^31
-        if (g < g_end) {
-            s0 = uniform_load(L.group_slot, g);
-            s1 = uniform_load(L.group_slot, g + 1);
-            base = (uint32_t)uniform_load(L.group_ptr, g);
-            n = s0 + lane < s1 ? L.seg_len[s0 + lane] : 0;
-        }
-        if (g + stride < g_end) {
-            s0n = uniform_load(L.group_slot, g + stride);
-            s1n = uniform_load(L.group_slot, g + stride + 1);
-            basen = (uint32_t)uniform_load(L.group_ptr, g + stride);
+        int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
+        uint32_t base[GP], basen[GP];
+        float done_acc[GP];
+#pragma unroll
+        for (int q = 0; q < GP; q++) {
+            const int32_t ga = g + q * stride, gb = g + (GP + q) * stride;
+            s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
+            base[q] = basen[q] = 0;
+            done_slot[q] = -1;
+            done_acc[q] = 0.f;
+            if (ga < g_end) {
+                s0[q] = uniform_load(L.group_slot, ga);
+                s1[q] = uniform_load(L.group_slot, ga + 1);
+                base[q] = (uint32_t)uniform_load(L.group_ptr, ga);
+                n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
+            }
+            if (gb < g_end) {
+                s0n[q] = uniform_load(L.group_slot, gb);
+                s1n[q] = uniform_load(L.group_slot, gb + 1);
+                basen[q] = (uint32_t)uniform_load(L.group_ptr, gb);
+            }
         }
         while (g < g_end) {
-            const int32_t g2 = g + 2 * stride;
-            int32_t s0nn = 0, s1nn = 0;
-            uint32_t basenn = 0;
-            if (g2 < g_end) {
-                s0nn = uniform_load(L.group_slot, g2);
-                s1nn = uniform_load(L.group_slot, g2 + 1);
-                basenn = (uint32_t)uniform_load(L.group_ptr, g2);
+            int32_t s0nn[GP], s1nn[GP], nn[GP];
+            uint32_t basenn[GP], first[GP];
+            Batch<U> bt[GP];
+            float acc[GP];
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                const int32_t gc = g + (2 * GP + q) * stride;
+                s0nn[q] = s1nn[q] = 0;
+                basenn[q] = 0;
+                if (gc < g_end) {
+                    s0nn[q] = uniform_load(L.group_slot, gc);
+                    s1nn[q] = uniform_load(L.group_slot, gc + 1);
+                    basenn[q] = (uint32_t)uniform_load(L.group_ptr, gc);
+                }
             }
-            // first batch in straight-line code, with the next group's lane lengths requested
-            // right behind its loads; further batches only for rows longer than U
-            Batch<U> bt;
-            const uint32_t first = base;
-            issue_batch<U>(bt, L.col_local, L.data, base, first, n, 0);
-            const int32_t nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
-            float acc = consume_batch<U>(bt, xs, n, 0);
-            for (int32_t k = U; __ballot(k < n); k += U) {
-                issue_batch<U>(bt, L.col_local, L.data, base, first, n, k);
-                acc += consume_batch<U>(bt, xs, n, k);
+            // first batches in straight-line code; the previous groups' partial sums are stored
+            // and the next groups' lane lengths requested right behind their loads
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                first[q] = base[q];
+                issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], 0);
             }
-            if (s0 + lane < s1) partial[s0 + lane] = acc;
-            g += stride;
-            s0 = s0n; s1 = s1n; base = basen; n = nn;
-            s0n = s0nn; s1n = s1nn; basen = basenn;
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
+                nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
+            }
+#pragma unroll
+            for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
+#pragma unroll
+            for (int q = 0; q < GP; q++)  // rows longer than U: further batches, one group at a time
+                for (int32_t k = U; __ballot(k < n[q]); k += U) {
+                    issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], k);
+                    acc[q] += consume_batch<U>(bt[q], xs, n[q], k);
+                }
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                done_acc[q] = acc[q];
+                done_slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
+                s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
+                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
+            }
+            g += GP * stride;
         }
+#pragma unroll
+        for (int q = 0; q < GP; q++)
+            if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
     };
 
     // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
@@ -222,11 +256,15 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
     for (int32_t i = threadIdx.x; i < rows; i += THREADS) ys[i] = 0.f;
     __syncthreads();
-    for (int32_t k = L.stripe_ptr[bm]; k < L.stripe_ptr[bm + 1]; k++) {
+    // wavefronts take the row block's blocks round-robin, lanes stride over a block's slots
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int32_t k1 = L.stripe_ptr[bm + 1];
+    for (int32_t k = L.stripe_ptr[bm] + wave; k < k1; k += THREADS / 64) {
         const int32_t b = L.stripe_blk[k];
         const int32_t s1 = L.slot_ptr[b + 1];
-        for (int32_t s = L.slot_ptr[b] + threadIdx.x; s < s1; s += THREADS)
-            atomicAdd(&ys[L.row_local[s]], partial[s]);  // LDS atomic; a block holds a row at most once
+        for (int32_t s = L.slot_ptr[b] + lane; s < s1; s += 64)
+            atomicAdd(&ys[L.row_local[s]], partial[s]);  // LDS atomic: other blocks may hold the same row
     }
     __syncthreads();
     for (int32_t i = threadIdx.x; i < rows; i += THREADS) y[r0 + i] = ys[i];
@@ -295,17 +333,17 @@ int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *thre
     return HBP_OK;
 }
 
-template <int THREADS, int U>
+template <int THREADS, int U, int GP>
 static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
 {
     const size_t lds = (size_t)h->C * sizeof(float);
     static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
     if (configured_device != h->device) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U, GP>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     kMaxC * (int)sizeof(float)));
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket);
+    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
@@ -313,11 +351,11 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, h
 template <int THREADS>
 static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
 {
-    switch (h->unroll) {
-    case 4: return launch_part<THREADS, 4>(h, L, x, st);
-    case 9: return launch_part<THREADS, 9>(h, L, x, st);
-    case 16: return launch_part<THREADS, 16>(h, L, x, st);
-    default: return launch_part<THREADS, 8>(h, L, x, st);
+    switch (h->unroll) {  // rounds per batch; short batches walk more groups at once
+    case 4: return launch_part<THREADS, 4, 4>(h, L, x, st);
+    case 9: return launch_part<THREADS, 9, 2>(h, L, x, st);
+    case 16: return launch_part<THREADS, 16, 1>(h, L, x, st);
+    default: return launch_part<THREADS, 8, 2>(h, L, x, st);
     }
 }
 
@@ -332,7 +370,10 @@ int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st)
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
 {
     const Layout L = hbp_view(h);
-    k_combine<256><<<dim3((unsigned)h->NBR), 256, (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+    if (h->R <= 1024)
+        k_combine<128><<<dim3((unsigned)h->NBR), 128, (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+    else
+        k_combine<256><<<dim3((unsigned)h->NBR), 256, (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
