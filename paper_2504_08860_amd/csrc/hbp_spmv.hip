@@ -243,31 +243,68 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     }
 }
 
-// Combine part.  Also re-arms the per-column ticket counters for the next call (the SpMV part of this
-// call has finished: same stream).
+// Combine part (Fig. 1): one workgroup per row block adds the partial sums of that row block's
+// blocks into LDS copies of its y slice and writes the slice out, zeros included.  The slot
+// ranges of up to kPass blocks are fetched in parallel first; then wavefronts take blocks
+// round-robin and lanes stride over a block's slots, four independent loads at a time.
+// Every wavefront accumulates into its own copy of the slice with plain LDS read-add-write:
+// a block holds a row at most once, so the lanes of one instruction never collide, and a
+// wavefront's LDS accesses complete in order.  (LDS float atomics would allow one shared copy
+// but run an order of magnitude slower on this hardware.)  The copies are summed on the way out.
+// Also re-arms the per-column ticket counters for the next call (the SpMV part of this call
+// has finished: same stream).
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__restrict__ partial, float *__restrict__ y,
                                                      uint32_t *__restrict__ ticket)
 {
-    extern __shared__ float ys[];  // R floats
+    extern __shared__ float ys_all[];  // kWaves copies of R floats
+    constexpr int kPass = 128, kWaves = THREADS / 64;
+    __shared__ int32_t range[2 * kPass];
     const int32_t bm = blockIdx.x;
     for (int64_t i = (int64_t)bm * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
     const int64_t r0 = (int64_t)bm * L.R;
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
-    for (int32_t i = threadIdx.x; i < rows; i += THREADS) ys[i] = 0.f;
-    __syncthreads();
-    // wavefronts take the row block's blocks round-robin, lanes stride over a block's slots
+    for (int32_t i = threadIdx.x; i < kWaves * L.R; i += THREADS) ys_all[i] = 0.f;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float *ys = ys_all + wave * L.R;
     const int32_t k1 = L.stripe_ptr[bm + 1];
-    for (int32_t k = L.stripe_ptr[bm] + wave; k < k1; k += THREADS / 64) {
-        const int32_t b = L.stripe_blk[k];
-        const int32_t s1 = L.slot_ptr[b + 1];
-        for (int32_t s = L.slot_ptr[b] + lane; s < s1; s += 64)
-            atomicAdd(&ys[L.row_local[s]], partial[s]);  // LDS atomic: other blocks may hold the same row
+    for (int32_t k0 = L.stripe_ptr[bm]; k0 < k1; k0 += kPass) {
+        const int32_t nb = min(kPass, k1 - k0);
+        __syncthreads();  // slices zeroed / previous pass done with range[]
+        for (int32_t t = threadIdx.x; t < nb; t += THREADS) {
+            const int32_t b = L.stripe_blk[k0 + t];
+            range[2 * t] = L.slot_ptr[b];
+            range[2 * t + 1] = L.slot_ptr[b + 1];
+        }
+        __syncthreads();
+        for (int32_t i = wave; i < nb; i += kWaves) {
+            const int32_t s1 = range[2 * i + 1];
+            for (int32_t s = range[2 * i] + lane; s < s1; s += 256) {
+                uint32_t r[4];
+                float p[4], o[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
+                    r[u] = L.row_local[idx];
+                    p[u] = partial[idx];
+                }
+                // the (up to) 256 slots are distinct rows of one block: read all, then write all
+#pragma unroll
+                for (int u = 0; u < 4; u++) o[u] = ys[r[u]];
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
+            }
+        }
     }
     __syncthreads();
-    for (int32_t i = threadIdx.x; i < rows; i += THREADS) y[r0 + i] = ys[i];
+    for (int32_t i = threadIdx.x; i < rows; i += THREADS) {
+        float sum = ys_all[i];
+#pragma unroll
+        for (int w = 1; w < kWaves; w++) sum += ys_all[w * L.R + i];
+        y[r0 + i] = sum;
+    }
 }
 
 // ------------------------------------------------------------------ CSR baselines (Algorithm 1)
@@ -370,10 +407,16 @@ int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st)
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
 {
     const Layout L = hbp_view(h);
+    static int configured_device = -1;
+    if (configured_device != h->device) {
+        HBP_HIP(hipFuncSetAttribute((const void *)k_combine<256>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    4 * kMaxR * (int)sizeof(float)));
+        configured_device = h->device;
+    }
     if (h->R <= 1024)
-        k_combine<128><<<dim3((unsigned)h->NBR), 128, (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<128><<<dim3((unsigned)h->NBR), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     else
-        k_combine<256><<<dim3((unsigned)h->NBR), 256, (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<256><<<dim3((unsigned)h->NBR), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
