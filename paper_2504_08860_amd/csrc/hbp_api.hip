@@ -155,6 +155,25 @@ int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int i
     return HBP_OK;
 }
 
+// Investigation hook (not part of the public header): per-wavefront timestamps of one SpMV-part
+// launch, 4 x uint64 per wavefront: start, end of fixed part, end, time spent staging (10 ns ticks).
+int hbp_debug_timeline(hbp_handle_t h, const float *x, float *y, void *stream, uint64_t *host_out, size_t capacity)
+{
+    if (!h || !x || !y || !host_out) return HBP_ERR_INVALID_ARGUMENT;
+    const size_t n = (size_t)h->P * (h->threads / 64) * 4;
+    if (capacity < n * sizeof(uint64_t)) return HBP_ERR_INVALID_ARGUMENT;
+    uint64_t *d = nullptr;
+    HBP_HIP(hipMalloc((void **)&d, n * sizeof(uint64_t)));
+    int rc = hbp::launch_spmv_part(h, x, (hipStream_t)stream, d);
+    if (rc == HBP_OK) rc = hbp::launch_combine(h, y, (hipStream_t)stream);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(host_out, d, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
+    (void)hipFree(d);
+    if (rc != HBP_OK) return rc;
+    HBP_HIP(e);
+    return HBP_OK;
+}
+
 int hbp_free(hbp_handle_t h)
 {
     if (!h) return HBP_OK;

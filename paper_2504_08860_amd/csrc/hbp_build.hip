@@ -686,7 +686,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_TRY(alloc_owned(&h->stripe_blk, B + 1));
     HBP_TRY(alloc_owned(&h->group_ptr, G + 1)); HBP_TRY(alloc_owned(&h->group_slot, G + 1));
     HBP_TRY(alloc_owned(&h->row_local, S + 1)); HBP_TRY(alloc_owned(&h->seg_len, S + 1));
-    HBP_TRY(alloc_owned(&h->col_local, nnz + 1)); HBP_TRY(alloc_owned(&h->data, nnz + 1));
+    // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
+    HBP_TRY(alloc_owned(&h->col_local, nnz + 256)); HBP_TRY(alloc_owned(&h->data, nnz + 256));
     HBP_TRY(alloc_owned(&h->partial, S + 1));
     uint32_t *bucket_key, *bucket_seg, *group_nnz;
     int32_t *slot_j, *group_blk;

@@ -68,7 +68,7 @@ int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
 // spmv (hbp_spmv.hip)
 Layout hbp_view(const hbp_handle_s *h);
 int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
-int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t stream);
+int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t stream, uint64_t *timeline = nullptr);
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t stream);
 int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,
                int64_t n_rows, hipStream_t stream);

@@ -74,110 +74,216 @@ __device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *x
     return acc;
 }
 
+// Fast path for a full group whose 64 rows all have the same length n0 >= 4: its nonzeros are
+// one contiguous run of 64 n0 elements in which element o belongs to the row of lane o mod 64.
+// The run is read in 256-element chunks aligned to 1 KB (data) / 512 B (columns), four
+// consecutive elements per lane with one 16-byte and one 8-byte load.  With d = distance from
+// the first chunk's start to the run, lane l's j-th element of every chunk belongs to the row
+// of lane (4 l + j - d) mod 64, so a lane keeps four running sums and no shuffle is needed
+// until the end, when the four lanes l, l^16, l^32, l^48 that serve the same rows are added.
+// Lanes whose four elements lie outside the run load nothing; elements outside the run that
+// share a 16-byte quad with it are read but contribute nothing.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <int CH>
+struct WideBatch {
+    f32x4 v[CH];
+    u32x2 c[CH];
+};
+
+template <int CH>
+__device__ __forceinline__ void issue_wide(WideBatch<CH> &b, const uint16_t *__restrict__ col_local,
+                                           const float *__restrict__ data, uint32_t chunk0, uint32_t i0, uint32_t run_begin,
+                                           uint32_t run_end, int lane)
+{
+#pragma unroll
+    for (int u = 0; u < CH; u++) {
+        const uint32_t p = chunk0 + 256u * (i0 + u) + 4u * (uint32_t)lane;
+        b.v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        b.c[u] = u32x2{0u, 0u};
+        if (p + 3u >= run_begin && p < run_end) {  // lanes whose four elements miss the run load nothing
+            b.v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(data + p));
+            b.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(col_local + p));
+        }
+    }
+}
+
+template <int CH>
+__device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float *xs, uint32_t chunk0, uint32_t i0,
+                                             uint32_t run_begin, uint32_t run_end, int lane, float (&acc)[4])
+{
+    uint32_t c[CH][4];
+    bool ok[CH][4];
+    float xv[CH][4];
+#pragma unroll
+    for (int u = 0; u < CH; u++) {
+        const uint32_t p = chunk0 + 256u * (i0 + u) + 4u * (uint32_t)lane;
+        const uint32_t lo = b.c[u].x, hi = b.c[u].y;
+        c[u][0] = lo & 0xffffu; c[u][1] = lo >> 16; c[u][2] = hi & 0xffffu; c[u][3] = hi >> 16;
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            ok[u][j] = p + j >= run_begin && p + j < run_end;
+            c[u][j] = ok[u][j] ? c[u][j] : 0u;  // never index the segment with a foreign column
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < CH; u++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) xv[u][j] = xs[c[u][j]];
+#pragma unroll
+    for (int u = 0; u < CH; u++) {
+        const float v[4] = {b.v[u].x, b.v[u].y, b.v[u].z, b.v[u].w};
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const float prod = v[j] * xv[u][j];
+            acc[j] += ok[u][j] ? prod : 0.f;
+        }
+    }
+}
+
 template <int THREADS, int U, int GP>
 __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                                                        const float *__restrict__ x, float *__restrict__ partial,
-                                                       uint32_t *__restrict__ col_ticket)
+                                                       uint32_t *__restrict__ col_ticket, uint64_t *__restrict__ dbg)
 {
+    const uint64_t dbg_t0 = dbg ? wall_clock64() : 0;
+    uint64_t dbg_stage = 0, dbg_fixed_end = 0;
     extern __shared__ float xs[];  // the staged vector segment, C floats
-    __shared__ int32_t sh_next;
+    __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
+    __shared__ int32_t sh_grp;   // next group of the current range, drawn by the wavefronts
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int staged_bn = -1;
 
     // Stage the vector segment of block column bn (uniform over the workgroup).
-    auto stage = [&](int32_t bn) {
+    auto stage = [&](int32_t bn) __attribute__((always_inline)) {
         if (bn == staged_bn) return;
+        const uint64_t t_in = dbg ? wall_clock64() : 0;
         __syncthreads();  // every wavefront is done with the previous segment
         const int64_t c0 = (int64_t)bn * L.C;
         const int32_t width = (int32_t)min((int64_t)L.C, L.n_cols - c0);
-        for (int32_t i = threadIdx.x; i < width; i += THREADS) xs[i] = x[c0 + i];
+        // 16-byte loads, eight in flight per thread, when the slice is 16-byte aligned
+        const float *src = x + c0;
+        const int32_t n4 = (reinterpret_cast<uintptr_t>(src) & 15u) == 0 ? width >> 2 : 0;
+        for (int32_t i0 = 0; i0 < n4; i0 += THREADS * 8) {
+            f32x4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const int32_t i = min(i0 + u * THREADS + (int32_t)threadIdx.x, n4 - 1);
+                t[u] = reinterpret_cast<const f32x4 *>(src)[i];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const int32_t i = i0 + u * THREADS + (int32_t)threadIdx.x;
+                if (i < n4) reinterpret_cast<f32x4 *>(xs)[i] = t[u];
+            }
+        }
+        for (int32_t i = 4 * n4 + threadIdx.x; i < width; i += THREADS) xs[i] = src[i];
         __syncthreads();
         staged_bn = bn;
+        if (dbg) dbg_stage += wall_clock64() - t_in;
     };
 
-    // This wavefront's groups g, g + stride, ... below g_end, GP of them per iteration, as a
-    // two-deep software pipeline: while GP groups are walked, the lane lengths of the next GP
-    // and the slot ranges / first positions of the GP after those are already on their way.
-    // The loads of all GP groups' first batches are issued before any of them is consumed.
-    // A group index at or beyond g_end gives an idle lane set (n = 0, position 0).
-    auto walk_range = [&](int32_t g, int32_t g_end, int32_t stride) {
-        int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
-        uint32_t base[GP], basen[GP];
-        float done_acc[GP];
-#pragma unroll
-        for (int q = 0; q < GP; q++) {
-            const int32_t ga = g + q * stride, gb = g + (GP + q) * stride;
-            s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
-            base[q] = basen[q] = 0;
-            done_slot[q] = -1;
-            done_acc[q] = 0.f;
-            if (ga < g_end) {
-                s0[q] = uniform_load(L.group_slot, ga);
-                s1[q] = uniform_load(L.group_slot, ga + 1);
-                base[q] = (uint32_t)uniform_load(L.group_ptr, ga);
-                n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
-            }
-            if (gb < g_end) {
-                s0n[q] = uniform_load(L.group_slot, gb);
-                s1n[q] = uniform_load(L.group_slot, gb + 1);
-                basen[q] = (uint32_t)uniform_load(L.group_ptr, gb);
-            }
+    // The wavefronts of the worker share out the groups [*, g_end) of the current range by
+    // drawing group indices from an LDS counter (wavefronts do not progress at the same speed,
+    // so a static deal would leave the slow ones behind).  Each wavefront keeps three draws in
+    // hand and runs them as a two-deep software pipeline: while a group is walked, the lane
+    // lengths of the next one and the slot range / first position of the one after it are
+    // already on their way, and the partial sums of the previous one are stored behind the
+    // current group's loads.
+    auto draw_group = [&]() __attribute__((always_inline)) {
+        int32_t v = 0;
+        if (lane == 0) v = atomicAdd(&sh_grp, 1);
+        return (int32_t)__builtin_amdgcn_readfirstlane(v);
+    };
+    auto walk_range = [&](int32_t g_end) __attribute__((always_inline)) {
+        int32_t g = draw_group(), g1 = draw_group(), g2 = draw_group();
+        int32_t s0 = 0, s1 = 0, n = 0, s0n = 0, s1n = 0;
+        uint32_t base = 0, basen = 0;  // positions stay 32-bit: nnz < 2^31
+        if (g < g_end) {
+            s0 = uniform_load(L.group_slot, g);
+            s1 = uniform_load(L.group_slot, g + 1);
+            base = (uint32_t)uniform_load(L.group_ptr, g);
+            n = s0 + lane < s1 ? L.seg_len[s0 + lane] : 0;
         }
+        if (g1 < g_end) {
+            s0n = uniform_load(L.group_slot, g1);
+            s1n = uniform_load(L.group_slot, g1 + 1);
+            basen = (uint32_t)uniform_load(L.group_ptr, g1);
+        }
+        float done_acc = 0.f;
+        int32_t done_slot = -1;
         while (g < g_end) {
-            int32_t s0nn[GP], s1nn[GP], nn[GP];
-            uint32_t basenn[GP], first[GP];
-            Batch<U> bt[GP];
-            float acc[GP];
-#pragma unroll
-            for (int q = 0; q < GP; q++) {
-                const int32_t gc = g + (2 * GP + q) * stride;
-                s0nn[q] = s1nn[q] = 0;
-                basenn[q] = 0;
-                if (gc < g_end) {
-                    s0nn[q] = uniform_load(L.group_slot, gc);
-                    s1nn[q] = uniform_load(L.group_slot, gc + 1);
-                    basenn[q] = (uint32_t)uniform_load(L.group_ptr, gc);
-                }
+            const int32_t g3 = draw_group();  // before the scalar loads: its wait would cover them too
+            int32_t s0nn = 0, s1nn = 0, nn = 0;
+            uint32_t basenn = 0;
+            if (g2 < g_end) {
+                s0nn = uniform_load(L.group_slot, g2);
+                s1nn = uniform_load(L.group_slot, g2 + 1);
+                basenn = (uint32_t)uniform_load(L.group_ptr, g2);
             }
-            // first batches in straight-line code; the previous groups' partial sums are stored
-            // and the next groups' lane lengths requested right behind their loads
-#pragma unroll
-            for (int q = 0; q < GP; q++) {
-                first[q] = base[q];
-                issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], 0);
-            }
-#pragma unroll
-            for (int q = 0; q < GP; q++) {
-                if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
-                nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
-            }
-#pragma unroll
-            for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
-#pragma unroll
-            for (int q = 0; q < GP; q++)  // rows longer than U: further batches, one group at a time
-                for (int32_t k = U; __ballot(k < n[q]); k += U) {
-                    issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], k);
-                    acc[q] += consume_batch<U>(bt[q], xs, n[q], k);
+            const int32_t n0 = __builtin_amdgcn_readfirstlane(n);
+            float acc;
+            int32_t slot;
+            if (s1 - s0 == 64 && n0 >= 4 && __ballot(n != n0) == 0) {
+                // full group, equal rows: aligned wide loads
+                constexpr int CH = 4;
+                const uint32_t chunk0 = base & ~255u, run_end = base + 64u * (uint32_t)n0;
+                const uint32_t n_chunks = (run_end - chunk0 + 255u) >> 8;
+                float a4[4] = {0.f, 0.f, 0.f, 0.f};
+                WideBatch<CH> wb;
+                issue_wide<CH>(wb, L.col_local, L.data, chunk0, 0, base, run_end, lane);
+                if (done_slot >= 0) partial[done_slot] = done_acc;
+                nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
+                consume_wide<CH>(wb, xs, chunk0, 0, base, run_end, lane, a4);
+                for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
+                    issue_wide<CH>(wb, L.col_local, L.data, chunk0, i0, base, run_end, lane);
+                    consume_wide<CH>(wb, xs, chunk0, i0, base, run_end, lane, a4);
                 }
 #pragma unroll
-            for (int q = 0; q < GP; q++) {
-                done_acc[q] = acc[q];
-                done_slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
-                s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
-                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
+                for (int j = 0; j < 4; j++) {
+                    a4[j] += __shfl_xor(a4[j], 16);
+                    a4[j] += __shfl_xor(a4[j], 32);
+                }
+                const int m = lane >> 4;  // this lane reports the m-th of its four rows
+                acc = m == 0 ? a4[0] : m == 1 ? a4[1] : m == 2 ? a4[2] : a4[3];
+                slot = s0 + (int32_t)((4u * (uint32_t)(lane & 15) + (uint32_t)m + 256u - (base - chunk0)) & 63u);
+            } else {
+                // general group: round by round, U rounds per batch
+                Batch<U> bt;
+                const uint32_t first = base;
+                issue_batch<U>(bt, L.col_local, L.data, base, first, n, 0);
+                if (done_slot >= 0) partial[done_slot] = done_acc;
+                nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
+                acc = consume_batch<U>(bt, xs, n, 0);
+                for (int32_t k = U; __ballot(k < n); k += U) {
+                    issue_batch<U>(bt, L.col_local, L.data, base, first, n, k);
+                    acc += consume_batch<U>(bt, xs, n, k);
+                }
+                slot = s0 + lane < s1 ? s0 + lane : -1;
             }
-            g += GP * stride;
+            done_acc = acc;
+            done_slot = slot;
+            g = g1; g1 = g2; g2 = g3;
+            s0 = s0n; s1 = s1n; base = basen; n = nn;
+            s0n = s0nn; s1n = s1nn; basen = basenn;
         }
-#pragma unroll
-        for (int q = 0; q < GP; q++)
-            if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
+        if (done_slot >= 0) partial[done_slot] = done_acc;
+    };
+
+    // Runs the groups [g_begin, g_end) of the staged column with all wavefronts of the worker.
+    auto run_range = [&](int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
+        __syncthreads();  // every wavefront has left the previous range
+        if (threadIdx.x == 0) sh_grp = g_begin;
+        __syncthreads();
+        walk_range(g_end);
     };
 
     // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
     // worker w runs, column by column, the groups of its range that lie in the fixed part of
-    // their column (below comp_lo).  Groups are dealt round-robin to the wavefronts.
+    // their column (below comp_lo).
     int32_t home = 0;
     {
         int32_t g = L.fixed_start[blockIdx.x];
@@ -190,7 +296,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
             const int32_t ge = min(g_end, c_end), fe = min(ge, L.comp_lo[c]);
             if (g < fe) {
                 stage(c);
-                walk_range(g + wave, fe, kWaves);
+                run_range(g, fe);
             }
             home = c;
             g = ge;
@@ -202,6 +308,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     // drawing from the column it is on (its segment is staged already); when that column runs
     // dry it moves to the column with the most groups left, and stages that segment only once
     // a ticket there has actually given it work.
+    if (dbg) dbg_fixed_end = wall_clock64();
     const int32_t per_ticket = kWaves * chunk;
     int32_t bn = home;
     for (;;) {
@@ -212,7 +319,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         __syncthreads();  // sh_next is rewritten below
         if (g0 < hi) {
             stage(bn);
-            walk_range((int32_t)g0 + wave, (int32_t)min((int64_t)hi, g0 + per_ticket), kWaves);
+            run_range((int32_t)g0, (int32_t)min((int64_t)hi, g0 + per_ticket));
             continue;
         }
         if (wave == 0) {  // this column is dry: look for the one with the most groups left
@@ -240,6 +347,10 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         bn = sh_next;
         __syncthreads();
         if (bn < 0) break;
+    }
+    if (dbg && lane == 0) {
+        uint64_t *o = dbg + ((size_t)blockIdx.x * kWaves + wave) * 4;
+        o[0] = dbg_t0; o[1] = dbg_fixed_end; o[2] = wall_clock64(); o[3] = dbg_stage;
     }
 }
 
@@ -371,7 +482,7 @@ int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *thre
 }
 
 template <int THREADS, int U, int GP>
-static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
+static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st, uint64_t *dbg)
 {
     const size_t lds = (size_t)h->C * sizeof(float);
     static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
@@ -380,28 +491,28 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, h
                                     kMaxC * (int)sizeof(float)));
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket);
+    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket, dbg);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
 template <int THREADS>
-static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st)
+static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st, uint64_t *dbg)
 {
     switch (h->unroll) {  // rounds per batch; short batches walk more groups at once
-    case 4: return launch_part<THREADS, 4, 4>(h, L, x, st);
-    case 9: return launch_part<THREADS, 9, 2>(h, L, x, st);
-    case 16: return launch_part<THREADS, 16, 1>(h, L, x, st);
-    default: return launch_part<THREADS, 8, 2>(h, L, x, st);
+    case 4: return launch_part<THREADS, 4, 4>(h, L, x, st, dbg);
+    case 9: return launch_part<THREADS, 9, 2>(h, L, x, st, dbg);
+    case 16: return launch_part<THREADS, 16, 1>(h, L, x, st, dbg);
+    default: return launch_part<THREADS, 8, 2>(h, L, x, st, dbg);
     }
 }
 
-int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st)
+int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st, uint64_t *dbg)
 {
     const Layout L = hbp_view(h);
-    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, st);
-    if (h->threads == 512) return launch_part_u<512>(h, L, x, st);
-    return launch_part_u<256>(h, L, x, st);
+    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, st, dbg);
+    if (h->threads == 512) return launch_part_u<512>(h, L, x, st, dbg);
+    return launch_part_u<256>(h, L, x, st, dbg);
 }
 
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
