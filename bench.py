@@ -38,6 +38,7 @@ def main() -> int:
     ap.add_argument("--claim-chunk", type=int, default=-1)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--rounds", type=int, default=0)
+    ap.add_argument("--slot-weight", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-csr", action="store_true")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
@@ -68,6 +69,7 @@ def main() -> int:
     if args.claim_chunk >= 0: params["claim_chunk"] = args.claim_chunk
     if args.threads: params["threads_per_worker"] = args.threads
     if args.rounds: params["rounds_per_batch"] = args.rounds
+    if args.slot_weight: params["slot_weight"] = args.slot_weight
 
     dev = lambda a: torch.from_numpy(a).cuda()
     ptr, col, val, x = dev(m.ptr), dev(m.col), dev(m.val), dev(m.x)
@@ -129,7 +131,7 @@ def main() -> int:
                    "group_width": info.group_width, "hash_shift": info.hash_shift, "blocks": info.blocks,
                    "slots": info.slots, "groups": info.groups, "workers": info.num_workers,
                    "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
-                   "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch},
+                   "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "bytes_per_launch": info.bytes_spmv_part, "ms_per_launch": round(ms_part, 5)},

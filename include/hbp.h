@@ -32,7 +32,7 @@
  *     group_ptr           [G+1]    position of a group's first nonzero   (begin_ptr)
  *     group_slot          [G+1]    first slot of a group
  *   Schedule (Section 3.3; the unit handed to a wavefront is a group, whose weight is its
- *   nonzeros plus its slots):
+ *   nonzeros plus slot_weight times its slots):
  *     col_group_ptr       [NBC+1]  first group of each block column
  *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
  *                                  the leading fixed_fraction of its weight as fixed part
@@ -86,6 +86,7 @@ typedef struct {
     int32_t claim_chunk;       /* groups per wavefront in one competitive ticket; 0 = default    */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads before accumulating: 4, 8, 9, 16; 0 = default */
+    int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 1..64; 0 = default     */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;
 
@@ -101,6 +102,8 @@ typedef struct {
     int32_t claim_chunk;
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
+    int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
+    int32_t reserved;
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */

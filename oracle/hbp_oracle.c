@@ -177,9 +177,10 @@ void oracle_hbp_free(oracle_hbp *h)
  * (share of the work pre-assigned, in 1/256) define the schedule arrays.
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
-                             int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8)
+                             int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
+                             int32_t slot_weight)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -292,8 +293,8 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     }
 
     /* Section 3.3, mixed execution allocation.  The unit handed to a wavefront is a group; the
-     * weight of a group is its nonzeros plus its slots, so Wt(g) = group_ptr[g] + group_slot[g]
-     * is the weight of all groups before g.
+     * weight of a group is its nonzeros plus slot_weight times its slots, so
+     * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] is the weight of all groups before g.
      *   - every block column keeps the first fixed_q8/256 of its weight as its fixed part and
      *     leaves the rest to competition: comp_lo[c] is the column's first competitive group;
      *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
@@ -305,7 +306,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
-    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)h->group_slot[g])
+    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g])
     for (int64_t c = 0; c < NBC; c++) {
         int64_t g0 = h->col_group_ptr[c], g1 = h->col_group_ptr[c + 1], g = g0;
         while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;

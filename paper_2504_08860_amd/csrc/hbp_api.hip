@@ -47,6 +47,7 @@ int hbp_default_params(hbp_params_t *p)
     p->claim_chunk = 0;
     p->threads_per_worker = 0;
     p->rounds_per_batch = 0;
+    p->slot_weight = 0;
     p->flags = HBP_FLAG_VALIDATE;
     return HBP_OK;
 }
@@ -66,9 +67,10 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.group_width == 0) p.group_width = 64;
     if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
     if (p.claim_chunk == 0) p.claim_chunk = 1;
+    if (p.slot_weight == 0) p.slot_weight = 4;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > (1 << 20) ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1 ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1 || p.slot_weight < 1 || p.slot_weight > 64 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
         (p.rounds_per_batch != 0 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 && p.rounds_per_batch != 9 &&
@@ -93,6 +95,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         h->threads = threads;
         h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
         h->fixed_q8 = p.fixed_fraction_q8;
+        h->slot_weight = p.slot_weight;
         h->P = p.num_workers > 0 ? p.num_workers : workers;
         rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
     }
@@ -197,6 +200,7 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->num_workers = h->P; info->fixed_fraction_q8 = h->fixed_q8; info->claim_chunk = h->claim_chunk;
     info->threads_per_worker = h->threads;
     info->rounds_per_batch = h->unroll;
+    info->slot_weight = h->slot_weight;
     const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
     const int64_t grp = 4 * 2 * (h->G + 1);
     info->bytes_layout = blk + grp + 2 * 2 * h->S + 6 * h->nnz;

@@ -484,8 +484,9 @@ __global__ __launch_bounds__(256) void k_add_sign(const int32_t *__restrict__ gr
 
 // ------------------------------------------------------------------ Section 3.3: schedule
 //
-// Weight of a group = its nonzeros + its slots; Wt(g) = group_ptr[g] + group_slot[g] is the
-// weight of all groups before g.
+// Weight of a group = its nonzeros + SW times its slots (SW = slot_weight: the per-row cost of a
+// group measured in nonzeros); Wt(g) = group_ptr[g] + SW * group_slot[g] is the weight of all
+// groups before g.
 
 __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict__ col_blk_ptr, const int32_t *__restrict__ blk_group_ptr,
                                                        int32_t NBC, int32_t *__restrict__ col_group_ptr)
@@ -498,17 +499,17 @@ __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict
 // preceding weight inside the column reaches fixed_q8/256 of the column's weight.
 __global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
                                                  const int32_t *__restrict__ group_slot, int32_t NBC, int32_t fixed_q8,
-                                                 int32_t *__restrict__ comp_lo)
+                                                 int64_t SW, int32_t *__restrict__ comp_lo)
 {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (c >= NBC) return;
     const int32_t g0 = col_group_ptr[c], g1 = col_group_ptr[c + 1];
-    const int64_t w0 = (int64_t)group_ptr[g0] + group_slot[g0];
-    const int64_t need = ((int64_t)group_ptr[g1] + group_slot[g1] - w0) * fixed_q8;
+    const int64_t w0 = (int64_t)group_ptr[g0] + SW * group_slot[g0];
+    const int64_t need = ((int64_t)group_ptr[g1] + SW * group_slot[g1] - w0) * fixed_q8;
     int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with (Wt(g) - w0) * 256 >= need
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
-        if (((int64_t)group_ptr[mid] + group_slot[mid] - w0) * 256 >= need) hi = mid; else lo = mid + 1;
+        if (((int64_t)group_ptr[mid] + SW * group_slot[mid] - w0) * 256 >= need) hi = mid; else lo = mid + 1;
     }
     comp_lo[c] = lo;
 }
@@ -517,15 +518,15 @@ __global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col
 // fixed_col[w]: the last block column that starts at or before that group.
 __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
                                                      const int32_t *__restrict__ group_slot, int32_t NBC, int32_t G, int32_t P,
-                                                     int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
+                                                     int64_t SW, int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
 {
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (w > P) return;
-    const int64_t need = w * ((int64_t)group_ptr[G] + group_slot[G]);
+    const int64_t need = w * ((int64_t)group_ptr[G] + SW * group_slot[G]);
     int32_t lo = 0, hi = G;
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
-        if (((int64_t)group_ptr[mid] + group_slot[mid]) * P >= need) hi = mid; else lo = mid + 1;
+        if (((int64_t)group_ptr[mid] + SW * group_slot[mid]) * P >= need) hi = mid; else lo = mid + 1;
     }
     fixed_start[w] = lo;
     if (w == P) return;
@@ -726,9 +727,10 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
         const int32_t NBC = (int32_t)h->NBC;
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
         k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC, h->fixed_q8,
-                                                           h->comp_lo);
+                                                           (int64_t)h->slot_weight, h->comp_lo);
         k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC,
-                                                                          (int32_t)h->G, h->P, h->fixed_start, h->fixed_col);
+                                                                          (int32_t)h->G, h->P, (int64_t)h->slot_weight, h->fixed_start,
+                                                                          h->fixed_col);
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

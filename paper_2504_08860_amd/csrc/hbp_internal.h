@@ -18,6 +18,7 @@ struct Layout {
     int32_t R, C, W;
     int32_t B, S, G;
     int32_t NBR, NBC;
+    int32_t competitive;  // 0 when every group is fixed (nothing to compete for)
     int64_t n_rows, n_cols;
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot;
@@ -33,7 +34,7 @@ struct hbp_handle_s {
     int64_t n_rows, n_cols, nnz;
     int32_t R, C, W, a;
     int64_t NBR, NBC, B, S, G;
-    int32_t P, fixed_q8, claim_chunk, threads;
+    int32_t P, fixed_q8, slot_weight, claim_chunk, threads;
     int32_t unroll;      // rounds taken per batch by the SpMV-part kernel (4, 8, 9 or 16)
     double build_ms;
     // device arrays (owned)

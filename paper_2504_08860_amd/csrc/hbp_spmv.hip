@@ -311,7 +311,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     if (dbg) dbg_fixed_end = wall_clock64();
     const int32_t per_ticket = kWaves * chunk;
     int32_t bn = home;
-    for (;;) {
+    while (L.competitive) {
         if (threadIdx.x == 0) sh_next = (int32_t)atomicAdd(&col_ticket[bn], 1u);
         __syncthreads();
         const int64_t g0 = L.comp_lo[bn] + (int64_t)sh_next * per_ticket;
@@ -453,6 +453,7 @@ Layout hbp_view(const hbp_handle_s *h)
     L.R = h->R; L.C = h->C; L.W = h->W;
     L.B = (int32_t)h->B; L.S = (int32_t)h->S; L.G = (int32_t)h->G;
     L.NBR = (int32_t)h->NBR; L.NBC = (int32_t)h->NBC;
+    L.competitive = h->fixed_q8 < 256 ? 1 : 0;
     L.n_rows = h->n_rows; L.n_cols = h->n_cols;
     L.blk_bm = h->blk_bm; L.blk_bn = h->blk_bn; L.slot_ptr = h->slot_ptr; L.blk_group_ptr = h->blk_group_ptr;
     L.col_blk_ptr = h->col_blk_ptr; L.stripe_ptr = h->stripe_ptr; L.stripe_blk = h->stripe_blk;

@@ -28,4 +28,25 @@ def test_host_only_calls():
     assert H.lib().hbp_free(None) == 0
     assert H.lib().hbp_get_info(None, None) == -1
     assert H.lib().hbp_build(None, None, None, 1, 1, None, None, None) == -1
-    assert ctypes.sizeof(H.hbp_params_t) == 40
+    assert ctypes.sizeof(H.hbp_params_t) == 44
+
+
+def test_struct_layout_matches_header(tmp_path):
+    """The ctypes mirrors of hbp_params_t / hbp_info_t have the C compiler's sizes and offsets."""
+    import subprocess
+    import paper_2504_08860_amd as H
+    src = tmp_path / "layout.c"
+    fields_p = [f[0] for f in H.hbp_params_t._fields_]
+    fields_i = [f[0] for f in H.hbp_info_t._fields_]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hbp.h"', 'int main(void){',
+             'printf("%zu %zu\\n", sizeof(hbp_params_t), sizeof(hbp_info_t));']
+    lines += [f'printf("%zu\\n", offsetof(hbp_params_t, {f}));' for f in fields_p]
+    lines += [f'printf("%zu\\n", offsetof(hbp_info_t, {f}));' for f in fields_i]
+    lines += ['return 0;}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I" + os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)]).decode().split()
+    assert [int(out[0]), int(out[1])] == [ctypes.sizeof(H.hbp_params_t), ctypes.sizeof(H.hbp_info_t)]
+    want = [getattr(H.hbp_params_t, f).offset for f in fields_p] + [getattr(H.hbp_info_t, f).offset for f in fields_i]
+    assert [int(v) for v in out[2:]] == want

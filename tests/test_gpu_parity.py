@@ -37,7 +37,8 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
         info = H.hbp_get_info(h)
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
                              W=info.group_width, hash_shift=params.get("hash_shift", -1),
-                             num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8)
+                             num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
+                             slot_weight=info.slot_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a
         assert info.hash_b == max(1, info.rows_per_block // 9)

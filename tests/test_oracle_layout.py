@@ -225,10 +225,10 @@ def test_schedule_split(oracle):
     every group exactly once; ranges have equal weight up to one group; every column keeps the
     stated share of its weight fixed, up to one group."""
     m = random_csr(300, 300, 0.05, 3)
-    for P, q8 in [(1, 128), (4, 192), (7, 255), (64, 256), (5, 0), (1000, 100)]:
-        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8)
+    for P, q8, sw in [(1, 128, 1), (4, 192, 4), (7, 255, 1), (64, 256, 6), (5, 0, 2), (1000, 100, 1)]:
+        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw)
         assert h.P == P and h.fixed_q8 == q8
-        wt = h.array("group_ptr").astype(np.int64) + h.array("group_slot")
+        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64)
         cgp, comp_lo = h.array("col_group_ptr"), h.array("comp_lo")
         fs, fc = h.array("fixed_start"), h.array("fixed_col")
         assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
