@@ -83,9 +83,11 @@ typedef struct {
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for; 0 = device default */
     int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
-    int32_t claim_chunk;       /* groups per wavefront in one competitive ticket; 0 = default    */
+    int32_t claim_chunk;       /* groups per wavefront in one competitive ticket; 0 = sized so that a
+                                  worker draws about six tickets                                   */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
-    int32_t rounds_per_batch;  /* rounds a wavefront loads before accumulating: 4, 8, 9, 16; 0 = default */
+    int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
+                                  (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
     int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 1..64; 0 = default     */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;

@@ -66,15 +66,14 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.cols_per_block == 0) p.cols_per_block = 4096;
     if (p.group_width == 0) p.group_width = 64;
     if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
-    if (p.claim_chunk == 0) p.claim_chunk = 1;
     if (p.slot_weight == 0) p.slot_weight = 4;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > (1 << 20) ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 1 || p.slot_weight < 1 || p.slot_weight > 64 ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.slot_weight < 1 || p.slot_weight > 64 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
-        (p.rounds_per_batch != 0 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 && p.rounds_per_batch != 9 &&
-         p.rounds_per_batch != 16))
+        (p.rounds_per_batch != 0 && p.rounds_per_batch != 2 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 &&
+         p.rounds_per_batch != 9 && p.rounds_per_batch != 16))
         return HBP_ERR_INVALID_ARGUMENT;
 
     const auto t0 = std::chrono::steady_clock::now();
@@ -104,6 +103,13 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         free_arrays(h);
         delete h;
         return rc;
+    }
+    if (p.claim_chunk == 0) {
+        // default ticket size: about six tickets per worker over the competitive part
+        const int64_t competitive = h->G * (256 - h->fixed_q8) / 256;
+        const int64_t per_ticket = competitive / (6 * (int64_t)h->P);
+        int64_t chunk = per_ticket / (h->threads / 64);
+        h->claim_chunk = (int32_t)(chunk < 1 ? 1 : chunk > 4096 ? 4096 : chunk);
     }
     rc = hbp::build_schedule(h, (hipStream_t)stream);
     if (rc != HBP_OK) {

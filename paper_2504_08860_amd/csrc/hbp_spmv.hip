@@ -152,6 +152,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     extern __shared__ float xs[];  // the staged vector segment, C floats
     __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
     __shared__ int32_t sh_grp;   // next group of the current range, drawn by the wavefronts
+    __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -187,90 +188,172 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     };
 
     // The wavefronts of the worker share out the groups [*, g_end) of the current range by
-    // drawing group indices from an LDS counter (wavefronts do not progress at the same speed,
-    // so a static deal would leave the slow ones behind).  Each wavefront keeps three draws in
-    // hand and runs them as a two-deep software pipeline: while a group is walked, the lane
-    // lengths of the next one and the slot range / first position of the one after it are
-    // already on their way, and the partial sums of the previous one are stored behind the
-    // current group's loads.
-    auto draw_group = [&]() __attribute__((always_inline)) {
+    // drawing packs of GP consecutive groups from an LDS counter (wavefronts do not progress at
+    // the same speed, so a static deal would leave the slow ones behind).  Each wavefront keeps
+    // three draws in hand and runs them as a two-deep software pipeline: while a pack is
+    // walked, the lane lengths of the next one and the slot ranges / first positions of the one
+    // after it are already on their way, and the partial sums of the previous one are stored
+    // behind the current pack's loads.  GP > 1 is for matrices whose groups hold few nonzeros:
+    // the first batches of all GP groups are issued before any is consumed.  A group index at
+    // or beyond g_end gives an idle lane set (n = 0, position 0).
+    auto draw_pack = [&]() __attribute__((always_inline)) {
         int32_t v = 0;
-        if (lane == 0) v = atomicAdd(&sh_grp, 1);
+        if (lane == 0) v = atomicAdd(&sh_grp, GP);
         return (int32_t)__builtin_amdgcn_readfirstlane(v);
     };
     auto walk_range = [&](int32_t g_end) __attribute__((always_inline)) {
-        int32_t g = draw_group(), g1 = draw_group(), g2 = draw_group();
-        int32_t s0 = 0, s1 = 0, n = 0, s0n = 0, s1n = 0;
-        uint32_t base = 0, basen = 0;  // positions stay 32-bit: nnz < 2^31
-        if (g < g_end) {
-            s0 = uniform_load(L.group_slot, g);
-            s1 = uniform_load(L.group_slot, g + 1);
-            base = (uint32_t)uniform_load(L.group_ptr, g);
-            n = s0 + lane < s1 ? L.seg_len[s0 + lane] : 0;
-        }
-        if (g1 < g_end) {
-            s0n = uniform_load(L.group_slot, g1);
-            s1n = uniform_load(L.group_slot, g1 + 1);
-            basen = (uint32_t)uniform_load(L.group_ptr, g1);
-        }
-        float done_acc = 0.f;
-        int32_t done_slot = -1;
-        while (g < g_end) {
-            const int32_t g3 = draw_group();  // before the scalar loads: its wait would cover them too
-            int32_t s0nn = 0, s1nn = 0, nn = 0;
-            uint32_t basenn = 0;
-            if (g2 < g_end) {
-                s0nn = uniform_load(L.group_slot, g2);
-                s1nn = uniform_load(L.group_slot, g2 + 1);
-                basenn = (uint32_t)uniform_load(L.group_ptr, g2);
+        int32_t g = draw_pack(), g1 = draw_pack(), g2 = draw_pack();
+        int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
+        uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
+        float done_acc[GP];
+#pragma unroll
+        for (int q = 0; q < GP; q++) {
+            s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
+            base[q] = basen[q] = 0;
+            done_slot[q] = -1;
+            done_acc[q] = 0.f;
+            if (g + q < g_end) {
+                s0[q] = uniform_load(L.group_slot, g + q);
+                s1[q] = uniform_load(L.group_slot, g + q + 1);
+                base[q] = (uint32_t)uniform_load(L.group_ptr, g + q);
+                n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
             }
-            const int32_t n0 = __builtin_amdgcn_readfirstlane(n);
-            float acc;
-            int32_t slot;
-            if (s1 - s0 == 64 && n0 >= 4 && __ballot(n != n0) == 0) {
-                // full group, equal rows: aligned wide loads
-                constexpr int CH = 4;
-                const uint32_t chunk0 = base & ~255u, run_end = base + 64u * (uint32_t)n0;
-                const uint32_t n_chunks = (run_end - chunk0 + 255u) >> 8;
-                float a4[4] = {0.f, 0.f, 0.f, 0.f};
-                WideBatch<CH> wb;
-                issue_wide<CH>(wb, L.col_local, L.data, chunk0, 0, base, run_end, lane);
-                if (done_slot >= 0) partial[done_slot] = done_acc;
-                nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
-                consume_wide<CH>(wb, xs, chunk0, 0, base, run_end, lane, a4);
-                for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
-                    issue_wide<CH>(wb, L.col_local, L.data, chunk0, i0, base, run_end, lane);
-                    consume_wide<CH>(wb, xs, chunk0, i0, base, run_end, lane, a4);
+            if (g1 + q < g_end) {
+                s0n[q] = uniform_load(L.group_slot, g1 + q);
+                s1n[q] = uniform_load(L.group_slot, g1 + q + 1);
+                basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
+            }
+        }
+        while (g < g_end) {
+            const int32_t g3 = draw_pack();  // before the scalar loads: its wait would cover them too
+            int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
+            uint32_t basenn[GP];
+            float acc[GP];
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                s0nn[q] = s1nn[q] = nn[q] = 0;
+                basenn[q] = 0;
+                if (g2 + q < g_end) {
+                    s0nn[q] = uniform_load(L.group_slot, g2 + q);
+                    s1nn[q] = uniform_load(L.group_slot, g2 + q + 1);
+                    basenn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q);
+                }
+            }
+            bool wide = false;
+            if constexpr (GP == 1) {
+                const int32_t n0 = __builtin_amdgcn_readfirstlane(n[0]);
+                wide = s1[0] - s0[0] == 64 && n0 >= 4 && __ballot(n[0] != n0) == 0;
+                if (wide) {
+                    // full group, equal rows: aligned wide loads
+                    constexpr int CH = 4;
+                    const uint32_t chunk0 = base[0] & ~255u, run_end = base[0] + 64u * (uint32_t)n0;
+                    const uint32_t n_chunks = (run_end - chunk0 + 255u) >> 8;
+                    float a4[4] = {0.f, 0.f, 0.f, 0.f};
+                    WideBatch<CH> wb;
+                    issue_wide<CH>(wb, L.col_local, L.data, chunk0, 0, base[0], run_end, lane);
+                    if (done_slot[0] >= 0) partial[done_slot[0]] = done_acc[0];
+                    nn[0] = s0n[0] + lane < s1n[0] ? L.seg_len[s0n[0] + lane] : 0;
+                    consume_wide<CH>(wb, xs, chunk0, 0, base[0], run_end, lane, a4);
+                    for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
+                        issue_wide<CH>(wb, L.col_local, L.data, chunk0, i0, base[0], run_end, lane);
+                        consume_wide<CH>(wb, xs, chunk0, i0, base[0], run_end, lane, a4);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        a4[j] += __shfl_xor(a4[j], 16);
+                        a4[j] += __shfl_xor(a4[j], 32);
+                    }
+                    const int m = lane >> 4;  // this lane reports the m-th of its four rows
+                    acc[0] = m == 0 ? a4[0] : m == 1 ? a4[1] : m == 2 ? a4[2] : a4[3];
+                    slot[0] = s0[0] + (int32_t)((4u * (uint32_t)(lane & 15) + (uint32_t)m + 256u - (base[0] - chunk0)) & 63u);
+                }
+            }
+            if (!wide) {
+                // general groups: round by round, U rounds per batch
+                Batch<U> bt[GP];
+                uint32_t first[GP];
+#pragma unroll
+                for (int q = 0; q < GP; q++) {
+                    first[q] = base[q];
+                    issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], 0);
                 }
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    a4[j] += __shfl_xor(a4[j], 16);
-                    a4[j] += __shfl_xor(a4[j], 32);
+                for (int q = 0; q < GP; q++) {
+                    if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
+                    nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
                 }
-                const int m = lane >> 4;  // this lane reports the m-th of its four rows
-                acc = m == 0 ? a4[0] : m == 1 ? a4[1] : m == 2 ? a4[2] : a4[3];
-                slot = s0 + (int32_t)((4u * (uint32_t)(lane & 15) + (uint32_t)m + 256u - (base - chunk0)) & 63u);
-            } else {
-                // general group: round by round, U rounds per batch
-                Batch<U> bt;
-                const uint32_t first = base;
-                issue_batch<U>(bt, L.col_local, L.data, base, first, n, 0);
-                if (done_slot >= 0) partial[done_slot] = done_acc;
-                nn = s0n + lane < s1n ? L.seg_len[s0n + lane] : 0;
-                acc = consume_batch<U>(bt, xs, n, 0);
-                for (int32_t k = U; __ballot(k < n); k += U) {
-                    issue_batch<U>(bt, L.col_local, L.data, base, first, n, k);
-                    acc += consume_batch<U>(bt, xs, n, k);
+#pragma unroll
+                for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
+#pragma unroll
+                for (int q = 0; q < GP; q++) {  // rows longer than U, one group at a time
+                    int32_t k = U;
+                    for (;;) {
+                        const uint64_t live = __ballot(k < n[q]);
+                        if (!live) break;
+                        const int32_t m = __popcll(live);
+                        if (m > 32 || __ballot(k + 2 * U < n[q]) != live) {
+                            // many rows still going, or one of them ends soon: a deep batch of rounds
+                            constexpr int UL = 16;
+                            Batch<UL> deep;
+                            issue_batch<UL>(deep, L.col_local, L.data, base[q], first[q], n[q], k);
+                            acc[q] += consume_batch<UL>(deep, xs, n[q], k);
+                            k += UL;
+                            continue;
+                        }
+                        // Few rows left, all of them with at least 2U more rounds.  Until the
+                        // shortest of them ends, the live set is
+                        // constant and the rounds k .. k_end-1 form one contiguous span in which
+                        // element o belongs to the (o mod m)-th live row.  The whole wavefront
+                        // reads the span: lanes 0 .. S-1 (S = largest multiple of m up to 64) take
+                        // elements lane, lane + S, ..., all for one row each, and the per-lane
+                        // sums are handed to the owning lanes through LDS.
+                        int32_t k_end = k < n[q] ? n[q] : 0x7fffffff;
+#pragma unroll
+                        for (int d = 32; d > 0; d >>= 1) k_end = min(k_end, __shfl_xor(k_end, d));
+                        const uint32_t span = (uint32_t)m * (uint32_t)(k_end - k);
+                        const uint32_t S = (64u / (uint32_t)m) * (uint32_t)m;
+                        float sum = 0.f;
+                        if ((uint32_t)lane < S) {
+                            uint32_t o = (uint32_t)lane;
+                            for (; o + 3u * S < span; o += 4u * S) {
+                                uint32_t c4[4];
+                                float v4[4];
+#pragma unroll
+                                for (int u = 0; u < 4; u++) {
+                                    c4[u] = __builtin_nontemporal_load(L.col_local + base[q] + o + u * S);
+                                    v4[u] = __builtin_nontemporal_load(L.data + base[q] + o + u * S);
+                                }
+#pragma unroll
+                                for (int u = 0; u < 4; u++) sum += v4[u] * xs[c4[u]];
+                            }
+                            for (; o < span; o += S) sum += L.data[base[q] + o] * xs[L.col_local[base[q] + o]];
+                        }
+                        float *hand = sh_hand + wave * 64;
+                        hand[lane] = sum;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        if (k < n[q])
+                            for (uint32_t t = (uint32_t)lanes_below(live); t < S; t += (uint32_t)m) acc[q] += hand[t];
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        base[q] += span;
+                        k = k_end;
+                    }
+                    slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
                 }
-                slot = s0 + lane < s1 ? s0 + lane : -1;
             }
-            done_acc = acc;
-            done_slot = slot;
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                done_acc[q] = acc[q];
+                done_slot[q] = slot[q];
+                s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
+                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
+            }
             g = g1; g1 = g2; g2 = g3;
-            s0 = s0n; s1 = s1n; base = basen; n = nn;
-            s0n = s0nn; s1n = s1nn; basen = basenn;
         }
-        if (done_slot >= 0) partial[done_slot] = done_acc;
+#pragma unroll
+        for (int q = 0; q < GP; q++)
+            if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
     };
 
     // Runs the groups [g_begin, g_end) of the staged column with all wavefronts of the worker.
@@ -500,11 +583,12 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, h
 template <int THREADS>
 static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st, uint64_t *dbg)
 {
-    switch (h->unroll) {  // rounds per batch; short batches walk more groups at once
+    switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
+    case 2: return launch_part<THREADS, 2, 8>(h, L, x, st, dbg);
     case 4: return launch_part<THREADS, 4, 4>(h, L, x, st, dbg);
-    case 9: return launch_part<THREADS, 9, 2>(h, L, x, st, dbg);
+    case 9: return launch_part<THREADS, 9, 1>(h, L, x, st, dbg);
     case 16: return launch_part<THREADS, 16, 1>(h, L, x, st, dbg);
-    default: return launch_part<THREADS, 8, 2>(h, L, x, st, dbg);
+    default: return launch_part<THREADS, 8, 1>(h, L, x, st, dbg);
     }
 }
 
