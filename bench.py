@@ -24,6 +24,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), or None."""
+    import glob
+    import re
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*_pmc.md")):
+        for line in open(path):
+            m = re.match(r"TRAFFIC_BYTES_PER_LAUNCH kernel=(\S+) workload=(\S+) bytes=(\d+)", line)
+            if m and m.group(1) == kernel and m.group(2) == workload:
+                return int(m.group(3))
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +83,7 @@ def main() -> int:
     if args.threads: params["threads_per_worker"] = args.threads
     if args.rounds: params["rounds_per_batch"] = args.rounds
     if args.slot_weight: params["slot_weight"] = args.slot_weight
+    overridden = params != preset(args.config)
 
     dev = lambda a: torch.from_numpy(a).cuda()
     ptr, col, val, x = dev(m.ptr), dev(m.col), dev(m.val), dev(m.x)
@@ -133,7 +147,8 @@ def main() -> int:
                    "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
                    "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic("k_spmv_part", m.name) if args.scale == 1.0 and not overridden else None,
                      "bytes_per_launch": info.bytes_spmv_part, "ms_per_launch": round(ms_part, 5)},
         "whole_call": {"effective_GBps": round(eff_gbs, 1), "frac_of_hbm_peak": round(eff_gbs / HBM_PEAK_GBS, 4),
                        "algorithmic_bytes": alg_call, "csr_equivalent_bytes": csr_equiv,
