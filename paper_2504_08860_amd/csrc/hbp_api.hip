@@ -25,9 +25,7 @@ struct DeviceGuard {  // makes the handle's device current for the duration of a
 
 void free_arrays(hbp_handle_s *h)
 {
-    void *ptrs[] = {h->blk_bm, h->blk_bn, h->slot_ptr, h->blk_group_ptr, h->col_blk_ptr, h->stripe_ptr, h->stripe_blk,
-                    h->group_ptr, h->group_slot, h->col_group_ptr, h->comp_lo, h->fixed_start, h->fixed_col, h->row_local, h->seg_len, h->col_local, h->data, h->partial, h->ticket};
-    for (void *p : ptrs)
+    for (void *p : h->arena)
         if (p) (void)hipFree(p);
 }
 

@@ -280,13 +280,13 @@ __global__ __launch_bounds__(256) void k_seg_flags(const int32_t *__restrict__ c
     }
 }
 
-// Segment records in CSR order, and the per-block segment counts.
+// Segment records in CSR order.
 __global__ __launch_bounds__(256) void k_seg_emit(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
                                                   const uint64_t *__restrict__ seg_bits, const uint32_t *__restrict__ word_off,
                                                   const int32_t *__restrict__ word_row, int64_t nnz, int64_t n_cols,
                                                   int32_t R, int32_t C, int32_t NBR, int64_t n_words,
                                                   int32_t *__restrict__ seg_j, int32_t *__restrict__ seg_row,
-                                                  int32_t *__restrict__ seg_bn, uint32_t *__restrict__ dense_cnt)
+                                                  int32_t *__restrict__ seg_bn)
 {
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -307,7 +307,6 @@ __global__ __launch_bounds__(256) void k_seg_emit(const int32_t *__restrict__ pt
     seg_j[s] = (int32_t)j;
     seg_row[s] = lo;
     seg_bn[s] = bn;
-    atomicAdd(&dense_cnt[(int64_t)bn * NBR + lo / R], 1u);
 }
 
 // ------------------------------------------------------------------ step 4: block table
@@ -362,6 +361,43 @@ __global__ __launch_bounds__(256) void k_stripe_fill(const uint32_t *__restrict_
 
 // ------------------------------------------------------------------ steps 5-6: hash + placement
 
+// Wave-aggregated fetch-add: lanes of the wavefront that target the same counter are served by
+// one atomic (neighbouring segments mostly fall into the same block, and same-address atomics
+// serialise).  Returns, for an active lane, the value its own atomicAdd(&counters[key], 1) would
+// have returned in some serial order.  After a few distinct keys the rest go one by one.
+__device__ __forceinline__ uint32_t aggregated_add(uint32_t *counters, int64_t key, bool active)
+{
+    const int lane = threadIdx.x & 63;
+    uint64_t todo = __ballot(active);
+    uint32_t result = 0;
+    for (int it = 0; todo && it < 8; it++) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int64_t k = __shfl(key, leader);
+        const uint64_t same = __ballot(active && key == k) & todo;
+        uint32_t base = 0;
+        if (lane == leader) base = atomicAdd(&counters[k], (uint32_t)__popcll(same));
+        base = __shfl(base, leader);
+        if ((same >> lane) & 1ull) result = base + (uint32_t)lanes_below(same);
+        todo &= ~same;
+    }
+    if ((todo >> lane) & 1ull) result = atomicAdd(&counters[key], 1u);
+    return result;
+}
+
+// Segments per block of the (column block, row block) table.
+// The segment count is still on the device (last entry of the scan) and the records of a
+// malformed matrix are incomplete, hence S_ptr and err.
+__global__ __launch_bounds__(256) void k_count_blocks(const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_bn,
+                                                      const uint32_t *__restrict__ S_ptr, const int32_t *__restrict__ err,
+                                                      int32_t R, int32_t NBR, uint32_t *__restrict__ dense_cnt)
+{
+    if (*err) return;
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = s < (int64_t)*S_ptr;
+    const int64_t d = active ? (int64_t)seg_bn[s] * NBR + seg_row[s] / R : 0;
+    aggregated_add(dense_cnt, d, active);
+}
+
 // Bucketed scatter: (key << 16 | local row, segment id) into the block's slot range.
 __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_j, const int32_t *__restrict__ seg_row,
                                                 const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR,
@@ -369,12 +405,14 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_
                                                 uint32_t *__restrict__ bucket_key, uint32_t *__restrict__ bucket_seg)
 {
     const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (s >= S) return;
+    const bool active = s < S;
+    const int32_t row = active ? seg_row[s] : 0;
+    const int64_t d = active ? (int64_t)seg_bn[s] * NBR + row / R : 0;
+    const uint32_t pos = aggregated_add(cursor, d, active);
+    if (!active) return;
     const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-    const int32_t row = seg_row[s];
     const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u;
     const uint32_t key = hash_key(n, (uint32_t)*a_ptr, b, R_u);
-    const uint32_t pos = atomicAdd(&cursor[(int64_t)seg_bn[s] * NBR + row / R], 1u);
     bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
     bucket_seg[pos] = (uint32_t)s;
 }
@@ -538,28 +576,35 @@ __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__
     fixed_col[w] = c_lo;
 }
 
-struct DeviceBuffers {  // frees every temporary on scope exit
-    std::vector<void *> ptrs;
-    ~DeviceBuffers() { for (void *p : ptrs) (void)hipFree(p); }
+// One device allocation carved into 256-byte aligned arrays: reserve() every array first,
+// commit() allocates once and hands out the pointers.  hipMalloc/hipFree calls are a large part
+// of the preprocessing time otherwise (each hipFree synchronises the device).
+class Arena {
+public:
+    explicit Arena(bool owned_by_caller) : keep_(owned_by_caller) {}
+    ~Arena() { if (!keep_ && base_) (void)hipFree(base_); }
     template <typename T>
-    int alloc(T **out, int64_t count)
+    void reserve(T **out, int64_t count)
     {
-        void *p = nullptr;
-        HBP_HIP(hipMalloc(&p, (size_t)(count > 0 ? count : 1) * sizeof(T)));
-        ptrs.push_back(p);
-        *out = (T *)p;
+        const size_t bytes = ((size_t)(count > 0 ? count : 1) * sizeof(T) + 255) & ~(size_t)255;
+        slots_.push_back({(void **)out, total_});
+        total_ += bytes;
+    }
+    int commit()
+    {
+        HBP_HIP(hipMalloc(&base_, total_ ? total_ : 256));
+        for (auto &s : slots_) *s.out = (char *)base_ + s.offset;
         return HBP_OK;
     }
-};
+    void *base() const { return base_; }
 
-template <typename T>
-int alloc_owned(T **out, int64_t count)
-{
-    void *p = nullptr;
-    HBP_HIP(hipMalloc(&p, (size_t)(count > 0 ? count : 1) * sizeof(T)));
-    *out = (T *)p;
-    return HBP_OK;
-}
+private:
+    struct Slot { void **out; size_t offset; };
+    std::vector<Slot> slots_;
+    size_t total_ = 0;
+    void *base_ = nullptr;
+    bool keep_;
+};
 
 inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
@@ -585,59 +630,64 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     h->nnz = nnz;
 
     // arrays whose size does not depend on the matrix content
-    HBP_TRY(alloc_owned(&h->col_blk_ptr, NBC + 1));
-    HBP_TRY(alloc_owned(&h->stripe_ptr, NBR + 1));
-    HBP_TRY(alloc_owned(&h->ticket, NBC));
-    HBP_TRY(alloc_owned(&h->comp_lo, NBC));
-    HBP_TRY(alloc_owned(&h->col_group_ptr, NBC + 1));
-    HBP_TRY(alloc_owned(&h->fixed_start, (int64_t)h->P + 1));
-    HBP_TRY(alloc_owned(&h->fixed_col, (int64_t)h->P));
+    Arena own0(true);
+    own0.reserve(&h->col_blk_ptr, NBC + 1);
+    own0.reserve(&h->stripe_ptr, NBR + 1);
+    own0.reserve(&h->ticket, NBC);
+    own0.reserve(&h->comp_lo, NBC);
+    own0.reserve(&h->col_group_ptr, NBC + 1);
+    own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
+    own0.reserve(&h->fixed_col, (int64_t)h->P);
+    HBP_TRY(own0.commit());
+    h->arena[0] = own0.base();
     HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
+    HBP_HIP(hipMemsetAsync(h->col_blk_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
+    HBP_HIP(hipMemsetAsync(h->stripe_ptr, 0, sizeof(int32_t) * (size_t)(NBR + 1), st));
     HBP_HIP(hipMemsetAsync(h->comp_lo, 0, sizeof(int32_t) * (size_t)NBC, st));
     HBP_HIP(hipMemsetAsync(h->col_group_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_start, 0, sizeof(int32_t) * (size_t)(h->P + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_col, 0, sizeof(int32_t) * (size_t)h->P, st));
-    HBP_HIP(hipMemsetAsync(h->col_blk_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
-    HBP_HIP(hipMemsetAsync(h->stripe_ptr, 0, sizeof(int32_t) * (size_t)(NBR + 1), st));
 
     if (nnz == 0) {  // empty matrix: no blocks; the combine part alone writes y = 0
         h->B = h->S = h->G = 0;
         h->a = p.hash_shift >= 0 ? p.hash_shift : 0;
-        HBP_TRY(alloc_owned(&h->blk_bm, 1)); HBP_TRY(alloc_owned(&h->blk_bn, 1));
-        HBP_TRY(alloc_owned(&h->slot_ptr, 1)); HBP_TRY(alloc_owned(&h->blk_group_ptr, 1));
-        HBP_TRY(alloc_owned(&h->stripe_blk, 1)); HBP_TRY(alloc_owned(&h->group_ptr, 1));
-        HBP_TRY(alloc_owned(&h->group_slot, 1)); HBP_TRY(alloc_owned(&h->row_local, 1));
-        HBP_TRY(alloc_owned(&h->seg_len, 1)); HBP_TRY(alloc_owned(&h->col_local, 1));
-        HBP_TRY(alloc_owned(&h->data, 1)); HBP_TRY(alloc_owned(&h->partial, 1));
+        Arena own1(true);
+        own1.reserve(&h->blk_bm, 1); own1.reserve(&h->blk_bn, 1); own1.reserve(&h->slot_ptr, 1);
+        own1.reserve(&h->blk_group_ptr, 1); own1.reserve(&h->stripe_blk, 1); own1.reserve(&h->group_ptr, 1);
+        own1.reserve(&h->group_slot, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
+        own1.reserve(&h->col_local, 1); own1.reserve(&h->data, 1); own1.reserve(&h->partial, 1);
+        HBP_TRY(own1.commit());
+        h->arena[1] = own1.base();
         HBP_HIP(hipMemsetAsync(h->slot_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->blk_group_ptr, 0, 4, st));
         HBP_HIP(hipMemsetAsync(h->group_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->group_slot, 0, 4, st));
         HBP_HIP(hipStreamSynchronize(st));
         return HBP_OK;
     }
 
-    DeviceBuffers tmp;
+    Arena tmp(false);
     const int64_t n_words = (nnz + 63) / 64;
     const int64_t scan_n = std::max<int64_t>(std::max<int64_t>(n_words, D), std::max<int64_t>(NBR, nnz / W + D)) + 1;
     uint32_t *row_bits, *seg_cnt, *word_off, *dense_cnt, *slot_off, *group_off, *blk_id, *scan_tmp, *hist, *stripe_cnt;
     uint64_t *seg_bits;
     int32_t *word_row, *seg_j, *seg_row, *seg_bn, *d_a, *d_err;
-    HBP_TRY(tmp.alloc(&row_bits, (nnz + 31) / 32 + 1));
-    HBP_TRY(tmp.alloc(&seg_bits, n_words));
-    HBP_TRY(tmp.alloc(&seg_cnt, n_words));
-    HBP_TRY(tmp.alloc(&word_off, n_words + 1));
-    HBP_TRY(tmp.alloc(&word_row, n_words + 1));
-    HBP_TRY(tmp.alloc(&seg_j, nnz + 1));     // S <= nnz: sized by the bound, no host round trip needed
-    HBP_TRY(tmp.alloc(&seg_row, nnz));
-    HBP_TRY(tmp.alloc(&seg_bn, nnz));
-    HBP_TRY(tmp.alloc(&dense_cnt, D));
-    HBP_TRY(tmp.alloc(&slot_off, D + 1));
-    HBP_TRY(tmp.alloc(&group_off, D + 1));
-    HBP_TRY(tmp.alloc(&blk_id, D + 1));
-    HBP_TRY(tmp.alloc(&stripe_cnt, NBR));
-    HBP_TRY(tmp.alloc(&scan_tmp, scan_n / kScanTile + 2));
-    HBP_TRY(tmp.alloc(&hist, 16));
-    HBP_TRY(tmp.alloc(&d_a, 1));
-    HBP_TRY(tmp.alloc(&d_err, 1));
+    tmp.reserve(&row_bits, (nnz + 31) / 32 + 1);
+    tmp.reserve(&seg_bits, n_words);
+    tmp.reserve(&seg_cnt, n_words);
+    tmp.reserve(&word_off, n_words + 1);
+    tmp.reserve(&word_row, n_words + 1);
+    tmp.reserve(&seg_j, nnz + 1);     // S <= nnz: sized by the bound, no host round trip needed
+    tmp.reserve(&seg_row, nnz);
+    tmp.reserve(&seg_bn, nnz);
+    tmp.reserve(&dense_cnt, D);
+    tmp.reserve(&slot_off, D + 1);
+    tmp.reserve(&group_off, D + 1);
+    tmp.reserve(&blk_id, D + 1);
+    tmp.reserve(&stripe_cnt, NBR);
+    tmp.reserve(&scan_tmp, scan_n / kScanTile + 2);
+    tmp.reserve(&hist, 16);
+    tmp.reserve(&d_a, 1);
+    tmp.reserve(&d_err, 1);
+    HBP_TRY(tmp.commit());
     HBP_HIP(hipMemsetAsync(row_bits, 0, sizeof(uint32_t) * (size_t)((nnz + 31) / 32 + 1), st));
     HBP_HIP(hipMemsetAsync(dense_cnt, 0, sizeof(uint32_t) * (size_t)D, st));
     HBP_HIP(hipMemsetAsync(hist, 0, sizeof(uint32_t) * 16, st));
@@ -659,7 +709,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
                                                        (p.flags & HBP_FLAG_VALIDATE) ? 1 : 0, seg_bits, seg_cnt, d_err);
     HBP_TRY(exclusive_scan<kOpIdentity>(seg_cnt, word_off, n_words, 1, scan_tmp, st));
     k_seg_emit<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_ptr, csr_col, seg_bits, word_off, word_row, nnz, n_cols, R, C,
-                                                      (int32_t)NBR, n_words, seg_j, seg_row, seg_bn, dense_cnt);
+                                                      (int32_t)NBR, n_words, seg_j, seg_row, seg_bn);
+    k_count_blocks<<<blocks_for(nnz, 256), 256, 0, st>>>(seg_row, seg_bn, word_off + n_words, d_err, R, (int32_t)NBR, dense_cnt);
     // step 4: scans over the block table
     HBP_TRY(exclusive_scan<kOpIdentity>(dense_cnt, slot_off, D, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpCeilDivW>(dense_cnt, group_off, D, (uint32_t)W, scan_tmp, st));
@@ -682,18 +733,23 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     const int64_t S = totals[0], G = totals[1], B = totals[2];
     h->S = S; h->G = G; h->B = B; h->a = a;
 
-    HBP_TRY(alloc_owned(&h->blk_bm, B + 1)); HBP_TRY(alloc_owned(&h->blk_bn, B + 1));
-    HBP_TRY(alloc_owned(&h->slot_ptr, B + 1)); HBP_TRY(alloc_owned(&h->blk_group_ptr, B + 1));
-    HBP_TRY(alloc_owned(&h->stripe_blk, B + 1));
-    HBP_TRY(alloc_owned(&h->group_ptr, G + 1)); HBP_TRY(alloc_owned(&h->group_slot, G + 1));
-    HBP_TRY(alloc_owned(&h->row_local, S + 1)); HBP_TRY(alloc_owned(&h->seg_len, S + 1));
+    Arena own1(true);
+    own1.reserve(&h->blk_bm, B + 1); own1.reserve(&h->blk_bn, B + 1);
+    own1.reserve(&h->slot_ptr, B + 1); own1.reserve(&h->blk_group_ptr, B + 1);
+    own1.reserve(&h->stripe_blk, B + 1);
+    own1.reserve(&h->group_ptr, G + 1); own1.reserve(&h->group_slot, G + 1);
+    own1.reserve(&h->row_local, S + 1); own1.reserve(&h->seg_len, S + 1);
     // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
-    HBP_TRY(alloc_owned(&h->col_local, nnz + 256)); HBP_TRY(alloc_owned(&h->data, nnz + 256));
-    HBP_TRY(alloc_owned(&h->partial, S + 1));
+    own1.reserve(&h->col_local, nnz + 256); own1.reserve(&h->data, nnz + 256);
+    own1.reserve(&h->partial, S + 1);
+    HBP_TRY(own1.commit());
+    h->arena[1] = own1.base();
+    Arena tmp2(false);
     uint32_t *bucket_key, *bucket_seg, *group_nnz;
     int32_t *slot_j, *group_blk;
-    HBP_TRY(tmp.alloc(&bucket_key, S)); HBP_TRY(tmp.alloc(&bucket_seg, S));
-    HBP_TRY(tmp.alloc(&slot_j, S)); HBP_TRY(tmp.alloc(&group_nnz, G + 1)); HBP_TRY(tmp.alloc(&group_blk, G + 1));
+    tmp2.reserve(&bucket_key, S); tmp2.reserve(&bucket_seg, S);
+    tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_blk, G + 1);
+    HBP_TRY(tmp2.commit());
 
     k_compact_blocks<<<blocks_for(std::max<int64_t>(D, NBC) + 1, 256), 256, 0, st>>>(
         dense_cnt, slot_off, group_off, blk_id, D, (int32_t)NBR, (int32_t)NBC, h->blk_bm, h->blk_bn, h->slot_ptr,

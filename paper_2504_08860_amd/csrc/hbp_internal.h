@@ -37,7 +37,9 @@ struct hbp_handle_s {
     int32_t P, fixed_q8, slot_weight, claim_chunk, threads;
     int32_t unroll;      // rounds taken per batch by the SpMV-part kernel (4, 8, 9 or 16)
     double build_ms;
-    // device arrays (owned)
+    // device arrays (owned): views into two allocations, arena[0] sized before the matrix is
+    // looked at, arena[1] after the segment, group and block counts are known
+    void *arena[2];
     int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     int32_t *group_ptr, *group_slot;
     int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;
