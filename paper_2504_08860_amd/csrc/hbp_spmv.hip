@@ -157,12 +157,20 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int staged_bn = -1;
+    // Workgroups are dispatched round-robin over the 8 XCDs, each with its own L2.  Workers with
+    // neighbouring ranges share block columns, hence slices of x: runs of four consecutive
+    // workers are placed on one XCD (a slice is then fetched into that L2 once and re-staged from
+    // there), successive runs on successive XCDs so that no XCD gets one contiguous part of the
+    // matrix.
+    const int32_t n_workers = (int32_t)gridDim.x;
+    int32_t worker = (int32_t)blockIdx.x;
+    if ((n_workers & 31) == 0) {
+        const int32_t xcd = worker & 7, i = worker >> 3;
+        worker = (((i >> 2) << 3) + xcd) * 4 + (i & 3);
+    }
 
-    // Stage the vector segment of block column bn (uniform over the workgroup).
-    auto stage = [&](int32_t bn) __attribute__((always_inline)) {
-        if (bn == staged_bn) return;
-        const uint64_t t_in = dbg ? wall_clock64() : 0;
-        __syncthreads();  // every wavefront is done with the previous segment
+    // Copies the vector segment of block column bn into LDS (no barriers: the caller orders it).
+    auto copy_slice = [&](int32_t bn) __attribute__((always_inline)) {
         const int64_t c0 = (int64_t)bn * L.C;
         const int32_t width = (int32_t)min((int64_t)L.C, L.n_cols - c0);
         // 16-byte loads, eight in flight per thread, when the slice is 16-byte aligned
@@ -182,9 +190,6 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
             }
         }
         for (int32_t i = 4 * n4 + threadIdx.x; i < width; i += THREADS) xs[i] = src[i];
-        __syncthreads();
-        staged_bn = bn;
-        if (dbg) dbg_stage += wall_clock64() - t_in;
     };
 
     // The wavefronts of the worker share out the groups [*, g_end) of the current range by
@@ -201,7 +206,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         if (lane == 0) v = atomicAdd(&sh_grp, GP);
         return (int32_t)__builtin_amdgcn_readfirstlane(v);
     };
-    auto walk_range = [&](int32_t g_end) __attribute__((always_inline)) {
+    // Runs the groups [g_begin, g_end) of block column bn with all wavefronts of the worker.
+    auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
+        const uint64_t t_in = dbg ? wall_clock64() : 0;
+        __syncthreads();  // every wavefront has left the previous range (and its slice of x)
+        if (threadIdx.x == 0) sh_grp = g_begin;
+        __syncthreads();
         int32_t g = draw_pack(), g1 = draw_pack(), g2 = draw_pack();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
         uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
@@ -224,6 +234,13 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                 basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
             }
         }
+        // the first packs' metadata is on its way while the slice of x is staged
+        if (bn != staged_bn) {
+            copy_slice(bn);
+            __syncthreads();
+            staged_bn = bn;
+        }
+        if (dbg) dbg_stage += wall_clock64() - t_in;
         while (g < g_end) {
             const int32_t g3 = draw_pack();  // before the scalar loads: its wait would cover them too
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
@@ -356,30 +373,21 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
             if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
     };
 
-    // Runs the groups [g_begin, g_end) of the staged column with all wavefronts of the worker.
-    auto run_range = [&](int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
-        __syncthreads();  // every wavefront has left the previous range
-        if (threadIdx.x == 0) sh_grp = g_begin;
-        __syncthreads();
-        walk_range(g_end);
-    };
-
     // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
     // worker w runs, column by column, the groups of its range that lie in the fixed part of
     // their column (below comp_lo).
     int32_t home = 0;
     {
-        int32_t g = L.fixed_start[blockIdx.x];
-        const int32_t g_end = L.fixed_start[blockIdx.x + 1];
-        int32_t c = L.fixed_col[blockIdx.x];
+        int32_t g = L.fixed_start[worker];
+        const int32_t g_end = L.fixed_start[worker + 1];
+        int32_t c = L.fixed_col[worker];
         home = c;
         while (g < g_end) {
             const int32_t c_end = L.col_group_ptr[c + 1];
             if (g >= c_end) { c++; continue; }  // columns without groups
             const int32_t ge = min(g_end, c_end), fe = min(ge, L.comp_lo[c]);
             if (g < fe) {
-                stage(c);
-                run_range(g, fe);
+                run_range(c, g, fe);
             }
             home = c;
             g = ge;
@@ -401,8 +409,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         const int32_t hi = L.col_group_ptr[bn + 1];
         __syncthreads();  // sh_next is rewritten below
         if (g0 < hi) {
-            stage(bn);
-            run_range((int32_t)g0, (int32_t)min((int64_t)hi, g0 + per_ticket));
+            run_range(bn, (int32_t)g0, (int32_t)min((int64_t)hi, g0 + per_ticket));
             continue;
         }
         if (wave == 0) {  // this column is dry: look for the one with the most groups left
