@@ -53,10 +53,14 @@ __device__ __forceinline__ void issue_batch(Batch<U> &b, const uint16_t *__restr
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const uint64_t live = __ballot(k + u < n);
-        const uint32_t j = k + u < n ? base + (uint32_t)lanes_below(live) : first;
-        b.c[u] = __builtin_nontemporal_load(col_local + j);
-        b.v[u] = __builtin_nontemporal_load(data + j);
-        base += (uint32_t)__popcll(live);
+        b.c[u] = 0;
+        b.v[u] = 0.f;
+        if (live) {  // wave-uniform: rounds past every row's end issue nothing
+            const uint32_t j = k + u < n ? base + (uint32_t)lanes_below(live) : first;
+            b.c[u] = __builtin_nontemporal_load(col_local + j);
+            b.v[u] = __builtin_nontemporal_load(data + j);
+            base += (uint32_t)__popcll(live);
+        }
     }
 }
 
