@@ -32,13 +32,22 @@
  *     group_ptr           [G+1]    position of a group's first nonzero   (begin_ptr)
  *     group_slot          [G+1]    first slot of a group
  *   Schedule (Section 3.3; the unit handed to a wavefront is a group, whose weight is its
- *   nonzeros plus slot_weight times its slots):
+ *   nonzeros plus slot_weight times its slots plus group_weight):
  *     col_group_ptr       [NBC+1]  first group of each block column
  *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
  *                                  the leading fixed_fraction of its weight as fixed part
  *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
  *                                  weight; worker w runs the fixed groups of range w
  *     fixed_col           [P]      block column that holds a worker's first group
+ *   Combine units (Section 3.3, combine part: one workgroup per unit instead of one per row
+ *   block, so that a row block with very many slots does not hold up the rest):
+ *     unit_ptr            [NBR+1]  first unit of each row block; a row block has
+ *                                  u = max(1, ceil(its slots / combine_unit_slots)) units
+ *     unit_stripe         [U]      row block of a unit
+ *     unit_k              [U+1]    first stripe_blk entry of a unit: unit i of a row block starts at
+ *                                  the first entry whose preceding slots times u reach i times the
+ *                                  row block's slots; unit_k[U] = B
+ *     multi_stripes       [NM]     row blocks with more than one unit, ascending
  *     row_local   u16     [S]      slot -> row inside its block          (output_hash)
  *     seg_len     u16     [S]      nonzeros of that row inside the block (add_sign is
  *                                  derived from these at run time)
@@ -89,6 +98,12 @@ typedef struct {
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
     int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 1..64; 0 = default     */
+    int32_t combine_unit_slots;/* slots one workgroup of the combine part should get at most: a row block
+                                  with more is cut into several units; >= 64; 0 = default 16384      */
+    int32_t group_weight;      /* schedule weight of a group on top of its nonzeros and slots, in
+                                  nonzeros: 0..1024; -1 = default                                    */
+    int32_t heavy_group_nnz;   /* a group with at least this many nonzeros is walked by all wavefronts of
+                                  its worker together instead of one; >= 1; 0 = default 32768        */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;
 
@@ -105,7 +120,11 @@ typedef struct {
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
-    int32_t reserved;
+    int32_t combine_unit_slots;  /* slots per combine unit the row blocks were cut for          */
+    int32_t heavy_group_nnz;     /* nonzeros from which a group is shared by a worker's wavefronts */
+    int32_t group_weight;        /* schedule weight of a group, in nonzeros                     */
+    int64_t combine_units;       /* U: workgroups of the combine part                           */
+    int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
@@ -120,7 +139,8 @@ typedef enum {
     HBP_ARRAY_DATA = 12,
     HBP_ARRAY_ADD_SIGN = 13, /* int32 [nnz], derived on the device from seg_len when exported   */
     HBP_ARRAY_PARTIAL = 14,  /* float [S], per-slot partial sums left by the last hbp_spmv      */
-    HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18
+    HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
+    HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */
@@ -142,7 +162,8 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
  * the SpMV part (Algorithm 3 per block; workers take their fixed blocks, then claim
  * competitive ones through an atomic ticket counter, Section 3.3) writes one partial sum
  * per slot; the combine part adds the partial sums of each row and writes y.
- *   x DEVICE float [n_cols], read only;  y DEVICE float [n_rows], overwritten.
+ *   x DEVICE float [n_cols], read only;  y DEVICE float [n_rows], overwritten (both kernels
+ *   write it: x and y must not overlap).
  * Asynchronous on `stream`.  A handle supports one SpMV in flight at a time: calls on the
  * same stream serialise by themselves; calls on different streams must be ordered by the
  * caller (they share the partial-sum buffer and the ticket counter). */

@@ -144,6 +144,11 @@ typedef struct {
     int32_t *comp_lo;             /* NBC : first competitive group of a block column          */
     int32_t *fixed_start;         /* P+1 : group ranges of the workers                        */
     int32_t *fixed_col;           /* P   : block column holding a worker's first group        */
+    int64_t U, NM;                /* combine units, row blocks cut into more than one unit    */
+    int32_t *unit_ptr;            /* NBR+1 : units of each row block                          */
+    int32_t *unit_stripe;         /* U   : row block of a unit                                */
+    int32_t *unit_k;              /* U+1 : first stripe_blk entry of a unit                   */
+    int32_t *multi_stripes;       /* NM  : row blocks with more than one unit, ascending      */
 } oracle_hbp;
 
 typedef struct { int64_t *cnt; int64_t NBR; int32_t R; } count_ctx;
@@ -170,6 +175,7 @@ void oracle_hbp_free(oracle_hbp *h)
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_slot);
     free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
+    free(h->unit_ptr); free(h->unit_stripe); free(h->unit_k); free(h->multi_stripes);
     free(h);
 }
 
@@ -178,9 +184,9 @@ void oracle_hbp_free(oracle_hbp *h)
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
-                             int32_t slot_weight)
+                             int32_t slot_weight, int32_t group_weight, int32_t unit_slots)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1 || group_weight < 0 || unit_slots < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -293,8 +299,9 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     }
 
     /* Section 3.3, mixed execution allocation.  The unit handed to a wavefront is a group; the
-     * weight of a group is its nonzeros plus slot_weight times its slots, so
-     * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] is the weight of all groups before g.
+     * weight of a group is its nonzeros plus slot_weight times its slots plus group_weight, so
+     * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] + group_weight * g is the weight of all
+     * groups before g.
      *   - every block column keeps the first fixed_q8/256 of its weight as its fixed part and
      *     leaves the rest to competition: comp_lo[c] is the column's first competitive group;
      *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
@@ -306,7 +313,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
-    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g])
+    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g] + (int64_t)group_weight * (int64_t)(g))
     for (int64_t c = 0; c < NBC; c++) {
         int64_t g0 = h->col_group_ptr[c], g1 = h->col_group_ptr[c + 1], g = g0;
         while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;
@@ -324,20 +331,63 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     }
     #undef WT
 
+    /* Work units of the combine part.  A row block with many slots is cut into
+     * u = ceil(slots / unit_slots) units of consecutive stripe_blk entries; unit i starts at the
+     * first entry whose preceding slots, times u, reach i times the row block's slots. */
+    {
+        int64_t *cum = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B + 1));
+        cum[0] = 0;
+        for (int64_t k = 0; k < B; k++) {
+            int64_t b = h->stripe_blk[k];
+            cum[k + 1] = cum[k] + (h->slot_ptr[b + 1] - h->slot_ptr[b]);
+        }
+        h->unit_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBR + 1));
+        int64_t U = 0, NM = 0;
+        for (int64_t bm = 0; bm < NBR; bm++) {
+            int64_t slots = cum[h->stripe_ptr[bm + 1]] - cum[h->stripe_ptr[bm]];
+            int64_t u = (slots + unit_slots - 1) / unit_slots;
+            if (u < 1) u = 1;
+            h->unit_ptr[bm] = (int32_t)U;
+            U += u;
+            if (u > 1) NM++;
+        }
+        h->unit_ptr[NBR] = (int32_t)U;
+        h->U = U; h->NM = NM;
+        h->unit_stripe = (int32_t *)malloc(sizeof(int32_t) * (size_t)(U + 1));
+        h->unit_k = (int32_t *)malloc(sizeof(int32_t) * (size_t)(U + 1));
+        h->multi_stripes = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NM + 1));
+        int64_t nm = 0;
+        for (int64_t bm = 0; bm < NBR; bm++) {
+            int64_t k0 = h->stripe_ptr[bm], k1 = h->stripe_ptr[bm + 1];
+            int64_t slots = cum[k1] - cum[k0], u = h->unit_ptr[bm + 1] - h->unit_ptr[bm];
+            int64_t k = k0;
+            for (int64_t i = 0; i < u; i++) {
+                while (k < k1 && (cum[k] - cum[k0]) * u < i * slots) k++;
+                h->unit_stripe[h->unit_ptr[bm] + i] = (int32_t)bm;
+                h->unit_k[h->unit_ptr[bm] + i] = (int32_t)k;
+            }
+            if (u > 1) h->multi_stripes[nm++] = (int32_t)bm;
+        }
+        h->unit_k[U] = (int32_t)B;
+        free(cum);
+    }
+
     free(cnt); free(cursor); free(compact_id); free(tq); free(tn); free(tj); free(slot_j); free(table);
     return h;
 }
 
-/* dims[0..13] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 */
+/* dims[0..15] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 U NM */
 void oracle_hbp_dims(const oracle_hbp *h, int64_t *dims)
 {
-    int64_t v[14] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8 };
+    int64_t v[16] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8,
+                      h->U, h->NM };
     memcpy(dims, v, sizeof v);
 }
 
 /* which: 0 blk_bm 1 blk_bn 2 slot_ptr 3 blk_group_ptr 4 col_blk_ptr 5 stripe_ptr 6 stripe_blk
  *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign
- *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col.
+ *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col
+ *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes.
  * Copies the array into dst and returns its size in bytes (0 for an unknown id). */
 int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
 {
@@ -361,6 +411,10 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 15: src = h->comp_lo; bytes = 4 * h->NBC; break;
     case 16: src = h->fixed_start; bytes = 4 * (h->P + 1); break;
     case 17: src = h->fixed_col; bytes = 4 * h->P; break;
+    case 18: src = h->unit_ptr; bytes = 4 * (h->NBR + 1); break;
+    case 19: src = h->unit_stripe; bytes = 4 * h->U; break;
+    case 20: src = h->unit_k; bytes = 4 * (h->U + 1); break;
+    case 21: src = h->multi_stripes; bytes = 4 * h->NM; break;
     default: return 0;
     }
     if (dst && bytes) memcpy(dst, src, (size_t)bytes);

@@ -46,6 +46,9 @@ int hbp_default_params(hbp_params_t *p)
     p->threads_per_worker = 0;
     p->rounds_per_batch = 0;
     p->slot_weight = 0;
+    p->combine_unit_slots = 0;
+    p->heavy_group_nnz = 0;
+    p->group_weight = -1;
     p->flags = HBP_FLAG_VALIDATE;
     return HBP_OK;
 }
@@ -65,9 +68,13 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.group_width == 0) p.group_width = 64;
     if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
     if (p.slot_weight == 0) p.slot_weight = 4;
+    if (p.combine_unit_slots == 0) p.combine_unit_slots = 16384;
+    if (p.heavy_group_nnz == 0) p.heavy_group_nnz = 32768;
+    if (p.group_weight < 0) p.group_weight = 0;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > (1 << 20) ||
         p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.slot_weight < 1 || p.slot_weight > 64 ||
+        p.combine_unit_slots < 64 || p.heavy_group_nnz < 1 || p.group_weight > 1024 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
         (p.rounds_per_batch != 0 && p.rounds_per_batch != 2 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 &&
@@ -93,6 +100,9 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
         h->fixed_q8 = p.fixed_fraction_q8;
         h->slot_weight = p.slot_weight;
+        h->unit_slots = p.combine_unit_slots;
+        h->heavy_nnz = p.heavy_group_nnz;
+        h->group_weight = p.group_weight;
         h->P = p.num_workers > 0 ? p.num_workers : workers;
         rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
     }
@@ -125,7 +135,7 @@ int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream)
     if (!h || !x || !y) return HBP_ERR_INVALID_ARGUMENT;
     DeviceGuard guard(h->device);
     if (!guard.ok) return HBP_ERR_HIP;
-    int rc = hbp::launch_spmv_part(h, x, (hipStream_t)stream);
+    int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream);
     if (rc != HBP_OK) return rc;
     return hbp::launch_combine(h, y, (hipStream_t)stream);
 }
@@ -143,7 +153,7 @@ int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int i
     int rc = HBP_OK;
     for (int i = 0; i < iters && rc == HBP_OK; i++) {
         HBP_HIP(hipEventRecord(ev[0], st));
-        rc = hbp::launch_spmv_part(h, x, st);
+        rc = hbp::launch_spmv_part(h, x, y, st);
         HBP_HIP(hipEventRecord(ev[1], st));
         if (rc == HBP_OK) rc = hbp::launch_combine(h, y, st);
         HBP_HIP(hipEventRecord(ev[2], st));
@@ -171,7 +181,7 @@ int hbp_debug_timeline(hbp_handle_t h, const float *x, float *y, void *stream, u
     if (capacity < n * sizeof(uint64_t)) return HBP_ERR_INVALID_ARGUMENT;
     uint64_t *d = nullptr;
     HBP_HIP(hipMalloc((void **)&d, n * sizeof(uint64_t)));
-    int rc = hbp::launch_spmv_part(h, x, (hipStream_t)stream, d);
+    int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream, d);
     if (rc == HBP_OK) rc = hbp::launch_combine(h, y, (hipStream_t)stream);
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e == hipSuccess) e = hipMemcpy(host_out, d, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
@@ -205,6 +215,11 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->threads_per_worker = h->threads;
     info->rounds_per_batch = h->unroll;
     info->slot_weight = h->slot_weight;
+    info->combine_unit_slots = h->unit_slots;
+    info->heavy_group_nnz = h->heavy_nnz;
+    info->group_weight = h->group_weight;
+    info->combine_units = h->U;
+    info->split_row_blocks = h->NM;
     const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
     const int64_t grp = 4 * 2 * (h->G + 1);
     info->bytes_layout = blk + grp + 2 * 2 * h->S + 6 * h->nnz;
@@ -244,6 +259,10 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_COMP_LO: src = h->comp_lo; bytes = 4 * (size_t)h->NBC; break;
     case HBP_ARRAY_FIXED_START: src = h->fixed_start; bytes = 4 * (size_t)(h->P + 1); break;
     case HBP_ARRAY_FIXED_COL: src = h->fixed_col; bytes = 4 * (size_t)h->P; break;
+    case HBP_ARRAY_UNIT_PTR: src = h->unit_ptr; bytes = 4 * (size_t)(h->NBR + 1); break;
+    case HBP_ARRAY_UNIT_STRIPE: src = h->unit_stripe; bytes = 4 * (size_t)h->U; break;
+    case HBP_ARRAY_UNIT_K: src = h->unit_k; bytes = 4 * (size_t)(h->U + 1); break;
+    case HBP_ARRAY_MULTI_STRIPES: src = h->multi_stripes; bytes = 4 * (size_t)h->NM; break;
     default: return HBP_ERR_INVALID_ARGUMENT;
     }
     if (bytes_out) *bytes_out = bytes;

@@ -218,6 +218,16 @@ __global__ void k_pick_shift(const uint32_t *__restrict__ hist, int32_t *__restr
     *a_out = a;
 }
 
+// Empty matrix: one empty combine unit per row block (it writes the zeros of y).
+__global__ __launch_bounds__(256) void k_iota_units(int32_t *unit_ptr, int32_t *unit_stripe, int32_t *unit_k, int32_t NBR)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i > NBR) return;
+    unit_ptr[i] = (int32_t)i;
+    unit_k[i] = 0;
+    if (i < NBR) unit_stripe[i] = (int32_t)i;
+}
+
 __global__ void k_set_i32(int32_t *p, int32_t v)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
@@ -520,11 +530,72 @@ __global__ __launch_bounds__(256) void k_add_sign(const int32_t *__restrict__ gr
     }
 }
 
+// ------------------------------------------------------------------ combine work units
+//
+// A row block with many slots is cut into u = ceil(slots / unit_slots) units of consecutive
+// stripe_blk entries, so that no workgroup of the combine part gets much more than unit_slots
+// slots; unit i starts at the first entry whose preceding slots, times u, reach i times the row
+// block's slots.
+
+__global__ __launch_bounds__(256) void k_stripe_sizes(const int32_t *__restrict__ stripe_blk, const int32_t *__restrict__ slot_ptr,
+                                                      int32_t B, uint32_t *__restrict__ size)
+{
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= B) return;
+    const int32_t b = stripe_blk[k];
+    size[k] = (uint32_t)(slot_ptr[b + 1] - slot_ptr[b]);
+}
+
+__global__ __launch_bounds__(256) void k_unit_count(const int32_t *__restrict__ stripe_ptr, const uint32_t *__restrict__ cum,
+                                                    int32_t NBR, int32_t unit_slots, uint32_t *__restrict__ units)
+{
+    const int64_t bm = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (bm >= NBR) return;
+    const int64_t slots = (int64_t)cum[stripe_ptr[bm + 1]] - (int64_t)cum[stripe_ptr[bm]];
+    const int64_t u = (slots + unit_slots - 1) / unit_slots;
+    units[bm] = (uint32_t)(u < 1 ? 1 : u);
+}
+
+// multi[bm] = 1 when the row block has more than one unit (input of the scan that numbers them)
+__global__ __launch_bounds__(256) void k_unit_multi(const uint32_t *__restrict__ units, int32_t NBR, uint32_t *__restrict__ multi)
+{
+    const int64_t bm = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (bm < NBR) multi[bm] = units[bm] > 1 ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(256) void k_unit_fill(const int32_t *__restrict__ stripe_ptr, const uint32_t *__restrict__ cum,
+                                                   const int32_t *__restrict__ unit_ptr, const uint32_t *__restrict__ multi_idx,
+                                                   int32_t NBR, int32_t B, int32_t *__restrict__ unit_stripe,
+                                                   int32_t *__restrict__ unit_k, int32_t *__restrict__ multi_stripes)
+{
+    const int64_t bm = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (bm >= NBR) return;
+    const int32_t k0 = stripe_ptr[bm], k1 = stripe_ptr[bm + 1];
+    const int32_t u0 = unit_ptr[bm], u = unit_ptr[bm + 1] - u0;
+    const int64_t base = cum[k0], slots = (int64_t)cum[k1] - base;
+    for (int32_t i = 0; i < u; i++) {
+        int32_t lo = k0, hi = k1;  // smallest k in [k0, k1] with (cum[k] - base) * u >= i * slots
+        while (lo < hi) {
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            if (((int64_t)cum[mid] - base) * u >= (int64_t)i * slots) hi = mid; else lo = mid + 1;
+        }
+        unit_stripe[u0 + i] = (int32_t)bm;
+        unit_k[u0 + i] = lo;
+    }
+    if (u > 1) multi_stripes[multi_idx[bm]] = (int32_t)bm;
+    if (bm == NBR - 1) unit_k[u0 + u] = B;
+}
+
 // ------------------------------------------------------------------ Section 3.3: schedule
 //
-// Weight of a group = its nonzeros + SW times its slots (SW = slot_weight: the per-row cost of a
-// group measured in nonzeros); Wt(g) = group_ptr[g] + SW * group_slot[g] is the weight of all
-// groups before g.
+// Weight of a group = its nonzeros + SW times its slots + GW (SW = slot_weight, GW = group_weight:
+// the per-row and per-group costs of a group measured in nonzeros);
+// Wt(g) = group_ptr[g] + SW * group_slot[g] + GW * g is the weight of all groups before g.
+struct Weights {
+    const int32_t *group_ptr, *group_slot;
+    int64_t SW, GW;
+    __device__ __forceinline__ int64_t before(int32_t g) const { return (int64_t)group_ptr[g] + SW * group_slot[g] + GW * g; }
+};
 
 __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict__ col_blk_ptr, const int32_t *__restrict__ blk_group_ptr,
                                                        int32_t NBC, int32_t *__restrict__ col_group_ptr)
@@ -535,36 +606,34 @@ __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict
 
 // comp_lo[c]: first group of column c left to competition, i.e. the first g in the column whose
 // preceding weight inside the column reaches fixed_q8/256 of the column's weight.
-__global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
-                                                 const int32_t *__restrict__ group_slot, int32_t NBC, int32_t fixed_q8,
-                                                 int64_t SW, int32_t *__restrict__ comp_lo)
+__global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, Weights wt, int32_t NBC,
+                                                 int32_t fixed_q8, int32_t *__restrict__ comp_lo)
 {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (c >= NBC) return;
     const int32_t g0 = col_group_ptr[c], g1 = col_group_ptr[c + 1];
-    const int64_t w0 = (int64_t)group_ptr[g0] + SW * group_slot[g0];
-    const int64_t need = ((int64_t)group_ptr[g1] + SW * group_slot[g1] - w0) * fixed_q8;
+    const int64_t w0 = wt.before(g0);
+    const int64_t need = (wt.before(g1) - w0) * fixed_q8;
     int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with (Wt(g) - w0) * 256 >= need
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
-        if (((int64_t)group_ptr[mid] + SW * group_slot[mid] - w0) * 256 >= need) hi = mid; else lo = mid + 1;
+        if ((wt.before(mid) - w0) * 256 >= need) hi = mid; else lo = mid + 1;
     }
     comp_lo[c] = lo;
 }
 
 // fixed_start[w]: first g with Wt(g) * P >= w * Wt(G) (P contiguous ranges of equal weight);
 // fixed_col[w]: the last block column that starts at or before that group.
-__global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ group_ptr,
-                                                     const int32_t *__restrict__ group_slot, int32_t NBC, int32_t G, int32_t P,
-                                                     int64_t SW, int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
+__global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, Weights wt, int32_t NBC, int32_t G,
+                                                     int32_t P, int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
 {
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (w > P) return;
-    const int64_t need = w * ((int64_t)group_ptr[G] + SW * group_slot[G]);
+    const int64_t need = w * wt.before(G);
     int32_t lo = 0, hi = G;
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
-        if (((int64_t)group_ptr[mid] + SW * group_slot[mid]) * P >= need) hi = mid; else lo = mid + 1;
+        if (wt.before(mid) * P >= need) hi = mid; else lo = mid + 1;
     }
     fixed_start[w] = lo;
     if (w == P) return;
@@ -638,6 +707,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own0.reserve(&h->col_group_ptr, NBC + 1);
     own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
     own0.reserve(&h->fixed_col, (int64_t)h->P);
+    own0.reserve(&h->unit_ptr, NBR + 1);
     HBP_TRY(own0.commit());
     h->arena[0] = own0.base();
     HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
@@ -656,8 +726,11 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         own1.reserve(&h->blk_group_ptr, 1); own1.reserve(&h->stripe_blk, 1); own1.reserve(&h->group_ptr, 1);
         own1.reserve(&h->group_slot, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
         own1.reserve(&h->col_local, 1); own1.reserve(&h->data, 1); own1.reserve(&h->partial, 1);
+        own1.reserve(&h->unit_stripe, NBR + 1); own1.reserve(&h->unit_k, NBR + 2); own1.reserve(&h->multi_stripes, 1);
         HBP_TRY(own1.commit());
         h->arena[1] = own1.base();
+        h->U = NBR; h->NM = 0;
+        k_iota_units<<<blocks_for(NBR + 1, 256), 256, 0, st>>>(h->unit_ptr, h->unit_stripe, h->unit_k, (int32_t)NBR);
         HBP_HIP(hipMemsetAsync(h->slot_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->blk_group_ptr, 0, 4, st));
         HBP_HIP(hipMemsetAsync(h->group_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->group_slot, 0, 4, st));
         HBP_HIP(hipStreamSynchronize(st));
@@ -742,9 +815,14 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
     own1.reserve(&h->col_local, nnz + 256); own1.reserve(&h->data, nnz + 256);
     own1.reserve(&h->partial, S + 1);
+    const int64_t max_units = NBR + S / h->unit_slots + 2;
+    own1.reserve(&h->unit_stripe, max_units); own1.reserve(&h->unit_k, max_units + 1);
+    own1.reserve(&h->multi_stripes, NBR);
     HBP_TRY(own1.commit());
     h->arena[1] = own1.base();
     Arena tmp2(false);
+    uint32_t *stripe_cum, *unit_cnt, *multi_idx;
+    tmp2.reserve(&stripe_cum, B + 1); tmp2.reserve(&unit_cnt, NBR + 1); tmp2.reserve(&multi_idx, NBR + 1);
     uint32_t *bucket_key, *bucket_seg, *group_nnz;
     int32_t *slot_j, *group_blk;
     tmp2.reserve(&bucket_key, S); tmp2.reserve(&bucket_seg, S);
@@ -756,6 +834,15 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         h->blk_group_ptr, h->col_blk_ptr);
     k_stripe_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(dense_cnt, blk_id, h->stripe_ptr, (int32_t)NBR, (int32_t)NBC,
                                                        h->stripe_blk);
+    // combine work units
+    k_stripe_sizes<<<blocks_for(B, 256), 256, 0, st>>>(h->stripe_blk, h->slot_ptr, (int32_t)B, stripe_cum);
+    HBP_TRY(exclusive_scan<kOpIdentity>(stripe_cum, stripe_cum, B, 1, scan_tmp, st));
+    k_unit_count<<<blocks_for(NBR, 256), 256, 0, st>>>(h->stripe_ptr, stripe_cum, (int32_t)NBR, h->unit_slots, unit_cnt);
+    k_unit_multi<<<blocks_for(NBR, 256), 256, 0, st>>>(unit_cnt, (int32_t)NBR, multi_idx);
+    HBP_TRY(exclusive_scan<kOpIdentity>(unit_cnt, (uint32_t *)h->unit_ptr, NBR, 1, scan_tmp, st));
+    HBP_TRY(exclusive_scan<kOpIdentity>(multi_idx, multi_idx, NBR, 1, scan_tmp, st));
+    k_unit_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(h->stripe_ptr, stripe_cum, h->unit_ptr, multi_idx, (int32_t)NBR, (int32_t)B,
+                                                     h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
     k_bucket<<<blocks_for(S, 256), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, d_a, slot_off, bucket_key,
                                                  bucket_seg);
@@ -772,7 +859,11 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
                                              slot_j, (int32_t)G, C, h->col_local, h->data);
     HBP_HIP(hipGetLastError());
+    uint32_t n_units = 0, n_multi = 0;
+    HBP_HIP(hipMemcpyAsync(&n_units, h->unit_ptr + NBR, 4, hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&n_multi, multi_idx + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipStreamSynchronize(st));
+    h->U = n_units; h->NM = n_multi;
     return HBP_OK;
 }
 
@@ -782,11 +873,10 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
     if (h->G > 0) {
         const int32_t NBC = (int32_t)h->NBC;
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
-        k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC, h->fixed_q8,
-                                                           (int64_t)h->slot_weight, h->comp_lo);
-        k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, h->group_ptr, h->group_slot, NBC,
-                                                                          (int32_t)h->G, h->P, (int64_t)h->slot_weight, h->fixed_start,
-                                                                          h->fixed_col);
+        const Weights wt{h->group_ptr, h->group_slot, (int64_t)h->slot_weight, (int64_t)h->group_weight};
+        k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
+        k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, (int32_t)h->G, h->P,
+                                                                          h->fixed_start, h->fixed_col);
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

@@ -23,6 +23,9 @@ struct Layout {
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot;
     const int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;  // schedule (Section 3.3)
+    const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
+    int32_t NM;                                                        // row blocks with several units
+    int32_t heavy_nnz;  // a group with at least this many nonzeros is walked by all wavefronts of a worker
     const uint16_t *row_local, *seg_len, *col_local;
     const float *data;
 };
@@ -43,6 +46,11 @@ struct hbp_handle_s {
     int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     int32_t *group_ptr, *group_slot;
     int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;
+    int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;
+    int64_t U, NM;       // combine work units, row blocks cut into several units
+    int32_t unit_slots;  // target slots per combine unit
+    int32_t group_weight;  // schedule weight of a group on top of its nonzeros and slots
+    int32_t heavy_nnz;   // groups with at least this many nonzeros are shared by a worker's wavefronts
     uint16_t *row_local, *seg_len, *col_local;
     float *data;
     float *partial;      // [S] per-slot partial sums of the SpMV part
@@ -71,7 +79,7 @@ int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
 // spmv (hbp_spmv.hip)
 Layout hbp_view(const hbp_handle_s *h);
 int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
-int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t stream, uint64_t *timeline = nullptr);
+int launch_spmv_part(const hbp_handle_s *h, const float *x, float *y, hipStream_t stream, uint64_t *timeline = nullptr);
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t stream);
 int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,
                int64_t n_rows, hipStream_t stream);

@@ -149,7 +149,8 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float
 template <int THREADS, int U, int GP>
 __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                                                        const float *__restrict__ x, float *__restrict__ partial,
-                                                       uint32_t *__restrict__ col_ticket, uint64_t *__restrict__ dbg)
+                                                       float *__restrict__ y, uint32_t *__restrict__ col_ticket,
+                                                       uint64_t *__restrict__ dbg)
 {
     const uint64_t dbg_t0 = dbg ? wall_clock64() : 0;
     uint64_t dbg_stage = 0, dbg_fixed_end = 0;
@@ -157,6 +158,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
     __shared__ int32_t sh_grp;   // next group of the current range, drawn by the wavefronts
     __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
+    constexpr int kHeavyCap = 64;
+    __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
+    __shared__ int32_t sh_heavy_n;
+    __shared__ int32_t sh_lens[THREADS];  // per wavefront: segment lengths of the heavy group being cut
+    __shared__ int32_t sh_cut_k[THREADS / 64 + 1];   // heavy group: first round of every wavefront's share
+    __shared__ uint32_t sh_cut_pos[THREADS / 64 + 1];  // and the nonzeros before that round
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -168,6 +175,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     // matrix.
     const int32_t n_workers = (int32_t)gridDim.x;
     int32_t worker = (int32_t)blockIdx.x;
+    // Row blocks that the combine part cuts into several units are summed into y with atomic
+    // adds: their rows of y start at zero.
+    for (int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x; i < (int64_t)L.NM * L.R; i += (int64_t)n_workers * THREADS) {
+        const int64_t row = (int64_t)L.multi_stripes[i / L.R] * L.R + i % L.R;
+        if (row < L.n_rows) y[row] = 0.f;
+    }
     if ((n_workers & 31) == 0) {
         const int32_t xcd = worker & 7, i = worker >> 3;
         worker = (((i >> 2) << 3) + xcd) * 4 + (i & 3);
@@ -210,32 +223,101 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         if (lane == 0) v = atomicAdd(&sh_grp, GP);
         return (int32_t)__builtin_amdgcn_readfirstlane(v);
     };
+    // Rounds k, k+1, ... of one group until no lane has a nonzero left (lane q has n; `base` is
+    // the position of round k, `first` any valid position of the group), added into acc.
+    auto walk_rounds = [&](uint32_t &base, uint32_t first, int32_t n, int32_t k, float &acc) __attribute__((always_inline)) {
+        for (;;) {
+            const uint64_t live = __ballot(k < n);
+            if (!live) break;
+            const int32_t m = __popcll(live);
+            if (m > 32 || __ballot(k + 2 * U < n) != live) {
+                // many rows still going, or one of them ends soon: a deep batch of rounds
+                constexpr int UL = 16;
+                Batch<UL> deep;
+                issue_batch<UL>(deep, L.col_local, L.data, base, first, n, k);
+                acc += consume_batch<UL>(deep, xs, n, k);
+                k += UL;
+                continue;
+            }
+            // Few rows left, all of them with at least 2U more rounds.  Until the shortest of
+            // them ends, the live set is constant and the rounds k .. k_end-1 form one contiguous
+            // span in which element o belongs to the (o mod m)-th live row.  The whole wavefront
+            // reads the span: lanes 0 .. S-1 (S = largest multiple of m up to 64) take elements
+            // lane, lane + S, ..., all for one row each, and the per-lane sums are handed to the
+            // owning lanes through LDS.
+            int32_t k_end = k < n ? n : 0x7fffffff;
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) k_end = min(k_end, __shfl_xor(k_end, d));
+            const uint32_t span = (uint32_t)m * (uint32_t)(k_end - k);
+            const uint32_t S = (64u / (uint32_t)m) * (uint32_t)m;
+            float sum = 0.f;
+            if ((uint32_t)lane < S) {
+                uint32_t o = (uint32_t)lane;
+                for (; o + 3u * S < span; o += 4u * S) {
+                    uint32_t c4[4];
+                    float v4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; u++) {
+                        c4[u] = __builtin_nontemporal_load(L.col_local + base + o + u * S);
+                        v4[u] = __builtin_nontemporal_load(L.data + base + o + u * S);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; u++) sum += v4[u] * xs[c4[u]];
+                }
+                for (; o < span; o += S) sum += L.data[base + o] * xs[L.col_local[base + o]];
+            }
+            float *hand = sh_hand + wave * 64;
+            hand[lane] = sum;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (k < n)
+                for (uint32_t t = (uint32_t)lanes_below(live); t < S; t += (uint32_t)m) acc += hand[t];
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            base += span;
+            k = k_end;
+        }
+    };
+    // A group with at least heavy_nnz nonzeros would keep one wavefront busy long after the rest
+    // of the worker has run dry.  The wavefront that draws one puts it on the worker's list
+    // instead (true), unless the list is full (then it walks the group alone).
+    auto defer_heavy = [&](int32_t group, uint32_t count) __attribute__((always_inline)) {
+        if (count < (uint32_t)L.heavy_nnz) return false;
+        int32_t idx = 0;
+        if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
+        idx = __builtin_amdgcn_readfirstlane(idx);
+        if (idx >= kHeavyCap) return false;
+        if (lane == 0) sh_heavy[idx] = group;
+        return true;
+    };
     // Runs the groups [g_begin, g_end) of block column bn with all wavefronts of the worker.
     auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
         const uint64_t t_in = dbg ? wall_clock64() : 0;
         __syncthreads();  // every wavefront has left the previous range (and its slice of x)
-        if (threadIdx.x == 0) sh_grp = g_begin;
+        if (threadIdx.x == 0) { sh_grp = g_begin; sh_heavy_n = 0; }
         __syncthreads();
         int32_t g = draw_pack(), g1 = draw_pack(), g2 = draw_pack();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
-        uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
+        uint32_t base[GP], basen[GP], cntn[GP];  // positions stay 32-bit: nnz < 2^31
         float done_acc[GP];
 #pragma unroll
         for (int q = 0; q < GP; q++) {
             s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
-            base[q] = basen[q] = 0;
+            base[q] = basen[q] = cntn[q] = 0;
             done_slot[q] = -1;
             done_acc[q] = 0.f;
             if (g + q < g_end) {
                 s0[q] = uniform_load(L.group_slot, g + q);
                 s1[q] = uniform_load(L.group_slot, g + q + 1);
                 base[q] = (uint32_t)uniform_load(L.group_ptr, g + q);
+                if (defer_heavy(g + q, (uint32_t)uniform_load(L.group_ptr, g + q + 1) - base[q])) s1[q] = s0[q];
                 n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
             }
             if (g1 + q < g_end) {
                 s0n[q] = uniform_load(L.group_slot, g1 + q);
                 s1n[q] = uniform_load(L.group_slot, g1 + q + 1);
                 basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
+                cntn[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q + 1) - basen[q];
             }
         }
         // the first packs' metadata is on its way while the slice of x is staged
@@ -248,17 +330,21 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         while (g < g_end) {
             const int32_t g3 = draw_pack();  // before the scalar loads: its wait would cover them too
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
-            uint32_t basenn[GP];
+            uint32_t basenn[GP], cntnn[GP];
             float acc[GP];
 #pragma unroll
             for (int q = 0; q < GP; q++) {
                 s0nn[q] = s1nn[q] = nn[q] = 0;
-                basenn[q] = 0;
+                basenn[q] = cntnn[q] = 0;
                 if (g2 + q < g_end) {
                     s0nn[q] = uniform_load(L.group_slot, g2 + q);
                     s1nn[q] = uniform_load(L.group_slot, g2 + q + 1);
                     basenn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q);
+                    cntnn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q + 1) - basenn[q];
                 }
+                // the next pack's metadata has arrived an iteration ago: heavy groups among them go
+                // to the worker's list and look empty to this wavefront
+                if (defer_heavy(g1 + q, cntn[q])) s1n[q] = s0n[q];
             }
             bool wide = false;
             if constexpr (GP == 1) {
@@ -307,59 +393,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                 for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
 #pragma unroll
                 for (int q = 0; q < GP; q++) {  // rows longer than U, one group at a time
-                    int32_t k = U;
-                    for (;;) {
-                        const uint64_t live = __ballot(k < n[q]);
-                        if (!live) break;
-                        const int32_t m = __popcll(live);
-                        if (m > 32 || __ballot(k + 2 * U < n[q]) != live) {
-                            // many rows still going, or one of them ends soon: a deep batch of rounds
-                            constexpr int UL = 16;
-                            Batch<UL> deep;
-                            issue_batch<UL>(deep, L.col_local, L.data, base[q], first[q], n[q], k);
-                            acc[q] += consume_batch<UL>(deep, xs, n[q], k);
-                            k += UL;
-                            continue;
-                        }
-                        // Few rows left, all of them with at least 2U more rounds.  Until the
-                        // shortest of them ends, the live set is
-                        // constant and the rounds k .. k_end-1 form one contiguous span in which
-                        // element o belongs to the (o mod m)-th live row.  The whole wavefront
-                        // reads the span: lanes 0 .. S-1 (S = largest multiple of m up to 64) take
-                        // elements lane, lane + S, ..., all for one row each, and the per-lane
-                        // sums are handed to the owning lanes through LDS.
-                        int32_t k_end = k < n[q] ? n[q] : 0x7fffffff;
-#pragma unroll
-                        for (int d = 32; d > 0; d >>= 1) k_end = min(k_end, __shfl_xor(k_end, d));
-                        const uint32_t span = (uint32_t)m * (uint32_t)(k_end - k);
-                        const uint32_t S = (64u / (uint32_t)m) * (uint32_t)m;
-                        float sum = 0.f;
-                        if ((uint32_t)lane < S) {
-                            uint32_t o = (uint32_t)lane;
-                            for (; o + 3u * S < span; o += 4u * S) {
-                                uint32_t c4[4];
-                                float v4[4];
-#pragma unroll
-                                for (int u = 0; u < 4; u++) {
-                                    c4[u] = __builtin_nontemporal_load(L.col_local + base[q] + o + u * S);
-                                    v4[u] = __builtin_nontemporal_load(L.data + base[q] + o + u * S);
-                                }
-#pragma unroll
-                                for (int u = 0; u < 4; u++) sum += v4[u] * xs[c4[u]];
-                            }
-                            for (; o < span; o += S) sum += L.data[base[q] + o] * xs[L.col_local[base[q] + o]];
-                        }
-                        float *hand = sh_hand + wave * 64;
-                        hand[lane] = sum;
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        if (k < n[q])
-                            for (uint32_t t = (uint32_t)lanes_below(live); t < S; t += (uint32_t)m) acc[q] += hand[t];
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        base[q] += span;
-                        k = k_end;
-                    }
+                    walk_rounds(base[q], first[q], n[q], U, acc[q]);
                     slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
                 }
             }
@@ -368,13 +402,73 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                 done_acc[q] = acc[q];
                 done_slot[q] = slot[q];
                 s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
-                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
+                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q]; cntn[q] = cntnn[q];
             }
             g = g1; g1 = g2; g2 = g3;
         }
 #pragma unroll
         for (int q = 0; q < GP; q++)
             if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
+
+        // Heavy groups of this range: all wavefronts of the worker walk each of them together.
+        // Wavefront w takes the rounds [k_w, k_{w+1}), where k_w is the first round that has
+        // w / kWaves of the group's nonzeros before it, and the per-lane sums of the wavefronts
+        // are added in LDS in wavefront order.
+        __syncthreads();
+        const int32_t n_heavy = min(sh_heavy_n, kHeavyCap);
+        for (int32_t i = 0; i < n_heavy; i++) {
+            const int32_t gh = sh_heavy[i];
+            const int32_t hs0 = uniform_load(L.group_slot, gh), hs1 = uniform_load(L.group_slot, gh + 1);
+            const uint32_t b0 = (uint32_t)uniform_load(L.group_ptr, gh);
+            const uint32_t total = (uint32_t)uniform_load(L.group_ptr, gh + 1) - b0;
+            const int32_t len = hs0 + lane < hs1 ? (int32_t)L.seg_len[hs0 + lane] : 0;
+            int32_t *lens = sh_lens + wave * 64;
+            lens[lane] = len;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // nonzeros of the group in rounds 0 .. k-1; every lane may ask for another k
+            auto before = [&](int32_t k) __attribute__((always_inline)) {
+                uint32_t sum = 0;
+#pragma unroll 16
+                for (int t = 0; t < 64; t++) sum += (uint32_t)min(lens[t], k);
+                return sum;
+            };
+            // smallest k with before(k) >= target, by three 64-way splits of (0, 65536]: a segment
+            // has fewer than 65536 nonzeros, so before(65536) = total >= target
+            const uint32_t target = (uint32_t)(((uint64_t)total * (uint32_t)wave) / (uint32_t)kWaves);
+            int32_t cut_k = 0;
+            uint32_t cut_pos = 0;
+            if (target > 0) {
+                int32_t lo = 0;
+                auto split = [&](int32_t step) __attribute__((always_inline)) {
+                    // candidates lo + step, lo + 2 step, ...: the last one is known to reach the target
+                    const uint32_t got = before(lo + (lane + 1) * step);
+                    const int first = __builtin_ctzll(__ballot(got >= target));
+                    lo += first * step;
+                    return (uint32_t)__shfl(got, first);
+                };
+                split(1024);
+                split(16);
+                cut_pos = split(1);
+                cut_k = lo + 1;
+            }
+            if (lane == 0) { sh_cut_k[wave] = cut_k; sh_cut_pos[wave] = cut_pos; }
+            if (threadIdx.x == 0) sh_cut_k[kWaves] = 0x10000;
+            __syncthreads();
+            const int32_t k_lo = sh_cut_k[wave], k_hi = sh_cut_k[wave + 1];
+            uint32_t pos = b0 + sh_cut_pos[wave];
+            float sum = 0.f;
+            walk_rounds(pos, b0, min(len, k_hi), k_lo, sum);
+            sh_hand[threadIdx.x] = sum;
+            __syncthreads();
+            if (wave == 0 && hs0 + lane < hs1) {
+                float total_sum = sh_hand[lane];
+#pragma unroll
+                for (int w = 1; w < kWaves; w++) total_sum += sh_hand[w * 64 + lane];
+                partial[hs0 + lane] = total_sum;
+            }
+            __syncthreads();  // sh_hand and the cuts are reused by the next heavy group
+        }
     };
 
     // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
@@ -465,16 +559,21 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
     extern __shared__ float ys_all[];  // kWaves copies of R floats
     constexpr int kPass = 128, kWaves = THREADS / 64;
     __shared__ int32_t range[2 * kPass];
-    const int32_t bm = blockIdx.x;
-    for (int64_t i = (int64_t)bm * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
+    // One workgroup per combine unit: entries [unit_k[j], unit_k[j + 1]) of stripe_blk, all of row
+    // block bm.  A row block with a single unit is stored; the units of a split row block add
+    // their sums into y, which the SpMV part has zeroed.
+    const int32_t unit = blockIdx.x;
+    const int32_t bm = L.unit_stripe[unit];
+    const bool split = L.unit_ptr[bm + 1] - L.unit_ptr[bm] > 1;
+    for (int64_t i = (int64_t)unit * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
     const int64_t r0 = (int64_t)bm * L.R;
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
     for (int32_t i = threadIdx.x; i < kWaves * L.R; i += THREADS) ys_all[i] = 0.f;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float *ys = ys_all + wave * L.R;
-    const int32_t k1 = L.stripe_ptr[bm + 1];
-    for (int32_t k0 = L.stripe_ptr[bm]; k0 < k1; k0 += kPass) {
+    const int32_t k1 = L.unit_k[unit + 1];
+    for (int32_t k0 = L.unit_k[unit]; k0 < k1; k0 += kPass) {
         const int32_t nb = min(kPass, k1 - k0);
         __syncthreads();  // slices zeroed / previous pass done with range[]
         for (int32_t t = threadIdx.x; t < nb; t += THREADS) {
@@ -508,7 +607,8 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
         float sum = ys_all[i];
 #pragma unroll
         for (int w = 1; w < kWaves; w++) sum += ys_all[w * L.R + i];
-        y[r0 + i] = sum;
+        if (split) atomicAdd(&y[r0 + i], sum);
+        else y[r0 + i] = sum;
     }
 }
 
@@ -555,6 +655,9 @@ Layout hbp_view(const hbp_handle_s *h)
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
     L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
     L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
+    L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
+    L.NM = (int32_t)h->NM;
+    L.heavy_nnz = h->heavy_nnz;
     return L;
 }
 
@@ -577,7 +680,7 @@ int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *thre
 }
 
 template <int THREADS, int U, int GP>
-static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st, uint64_t *dbg)
+static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     const size_t lds = (size_t)h->C * sizeof(float);
     static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
@@ -586,29 +689,29 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, h
                                     kMaxC * (int)sizeof(float)));
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, h->ticket, dbg);
+    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, y, h->ticket, dbg);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
 template <int THREADS>
-static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, hipStream_t st, uint64_t *dbg)
+static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
-    case 2: return launch_part<THREADS, 2, 8>(h, L, x, st, dbg);
-    case 4: return launch_part<THREADS, 4, 4>(h, L, x, st, dbg);
-    case 9: return launch_part<THREADS, 9, 1>(h, L, x, st, dbg);
-    case 16: return launch_part<THREADS, 16, 1>(h, L, x, st, dbg);
-    default: return launch_part<THREADS, 8, 1>(h, L, x, st, dbg);
+    case 2: return launch_part<THREADS, 2, 8>(h, L, x, y, st, dbg);
+    case 4: return launch_part<THREADS, 4, 4>(h, L, x, y, st, dbg);
+    case 9: return launch_part<THREADS, 9, 1>(h, L, x, y, st, dbg);
+    case 16: return launch_part<THREADS, 16, 1>(h, L, x, y, st, dbg);
+    default: return launch_part<THREADS, 8, 1>(h, L, x, y, st, dbg);
     }
 }
 
-int launch_spmv_part(const hbp_handle_s *h, const float *x, hipStream_t st, uint64_t *dbg)
+int launch_spmv_part(const hbp_handle_s *h, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     const Layout L = hbp_view(h);
-    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, st, dbg);
-    if (h->threads == 512) return launch_part_u<512>(h, L, x, st, dbg);
-    return launch_part_u<256>(h, L, x, st, dbg);
+    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, y, st, dbg);
+    if (h->threads == 512) return launch_part_u<512>(h, L, x, y, st, dbg);
+    return launch_part_u<256>(h, L, x, y, st, dbg);
 }
 
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
@@ -621,9 +724,9 @@ int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
         configured_device = h->device;
     }
     if (h->R <= 1024)
-        k_combine<128><<<dim3((unsigned)h->NBR), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<128><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     else
-        k_combine<256><<<dim3((unsigned)h->NBR), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<256><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }

@@ -10,7 +10,8 @@ pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
-                 "group_ptr", "group_slot", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col", "row_local", "seg_len", "col_local", "data", "add_sign")
+                 "group_ptr", "group_slot", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col",
+                 "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
 
 
 @pytest.fixture(scope="module")
@@ -38,9 +39,11 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
                              W=info.group_width, hash_shift=params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
-                             slot_weight=info.slot_weight)
+                             slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
+                             group_weight=info.group_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a
+        assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
         assert info.hash_b == max(1, info.rows_per_block // 9)
         for name in LAYOUT_ARRAYS:
             if name == "add_sign" and not check_add_sign:
@@ -98,12 +101,12 @@ def test_small_random(H, oracle, case):
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, group_width=W, hash_shift=shift)
 
 
-@pytest.mark.parametrize("P,q8,chunk", [(1, 0, 1), (3, 256, 1), (7, 100, 5), (2000, 200, 2)])
-def test_schedule_variants(H, oracle, P, q8, chunk):
+@pytest.mark.parametrize("P,q8,chunk,gw", [(1, 0, 1, 0), (3, 256, 1, 50), (7, 100, 5, 1024), (2000, 200, 2, 7)])
+def test_schedule_variants(H, oracle, P, q8, chunk, gw):
     """y does not depend on how blocks are split into fixed and competitive parts."""
     m = random_csr(3000, 3000, 0.01, 21, empty_row_frac=0.1)
     info = check_against_oracle(H, oracle, m, rows_per_block=64, cols_per_block=128, num_workers=P,
-                                fixed_fraction_q8=q8, claim_chunk=chunk)
+                                fixed_fraction_q8=q8, claim_chunk=chunk, group_weight=gw)
     assert info.num_workers == P and info.claim_chunk == chunk
 
 
@@ -180,3 +183,66 @@ def test_csr_baselines(H, oracle, kind):
         torch.cuda.synchronize()
         y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
         assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs)
+
+
+def _mixed_matrix(seed=5):
+    """Rows of equal length in bulk (full equal groups -> aligned wide loads), a band of short
+    rows (packs of several groups), and a few very long rows (deep batches, whole-wavefront
+    spans), all inside one block column so that they share groups."""
+    from workloads import CsrMatrix
+    rng = np.random.default_rng(seed)
+    n_cols = 6000
+    lens = np.r_[np.full(1500, 12), rng.integers(1, 4, 2000), np.full(700, 5), [5000, 3000, 2999, 800, 799, 300, 64, 63],
+                 rng.integers(0, 40, 600), np.full(640, 9)]
+    rng.shuffle(lens)
+    col = np.concatenate([np.sort(rng.choice(n_cols, n, replace=False)) for n in lens]).astype(np.int32)
+    ptr = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    return CsrMatrix("mixed", len(lens), n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32),
+                     rng.uniform(-1, 1, n_cols).astype(np.float32))
+
+
+@pytest.mark.parametrize("rounds", [2, 4, 8, 9, 16])
+@pytest.mark.parametrize("threads", [256, 512, 1024])
+def test_kernel_variants(H, oracle, rounds, threads):
+    """Every instantiation of the SpMV-part kernel (rounds per batch x workgroup size), on a
+    matrix that reaches all three walking modes, with and without a competitive part."""
+    m = _mixed_matrix()
+    for q8, workers in ((256, 7), (160, 5)):
+        check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=1024, cols_per_block=8192,
+                             rounds_per_batch=rounds, threads_per_worker=threads, fixed_fraction_q8=q8,
+                             num_workers=workers, slot_weight=3)
+
+
+def test_many_columns_competition(H, oracle):
+    """More block columns than a wavefront has lanes (the scan for the fullest column loops), tiny
+    tickets, more workers than groups."""
+    m = random_csr(1500, 9000, 0.01, 31, empty_row_frac=0.2)
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=64, claim_chunk=1,
+                         num_workers=300, threads_per_worker=256)
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=0, claim_chunk=3,
+                         num_workers=32, threads_per_worker=512, rounds_per_batch=4)
+
+
+@pytest.mark.parametrize("unit_slots", [64, 300, 5000])
+def test_split_row_blocks(H, oracle, unit_slots):
+    """Row blocks cut into several combine units (their sums meet in y through atomic adds), next
+    to row blocks with one unit and empty row blocks; R both below and above the 128/256-thread
+    switch of the combine kernel."""
+    m = _mixed_matrix(seed=41)
+    for R in (256, 2048):
+        info = check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=512, combine_unit_slots=unit_slots)
+        if unit_slots == 64:
+            assert info.split_row_blocks > 0
+
+
+@pytest.mark.parametrize("heavy", [1, 300, 2000, 20000])
+@pytest.mark.parametrize("rounds,threads", [(2, 256), (4, 512), (8, 1024), (9, 1024), (16, 512)])
+def test_heavy_groups_shared_by_a_worker(H, oracle, heavy, rounds, threads):
+    """Groups at or above heavy_group_nnz are walked by all wavefronts of a worker, each taking
+    an equal share of the group's rounds.  heavy = 1 makes every group heavy (the worker's list
+    overflows and the rest is walked the ordinary way); the larger values leave a mix."""
+    m = _mixed_matrix(seed=7)
+    for q8, workers in ((256, 3), (128, 6)):
+        check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=2048, cols_per_block=8192,
+                             rounds_per_batch=rounds, threads_per_worker=threads, fixed_fraction_q8=q8,
+                             num_workers=workers, heavy_group_nnz=heavy)

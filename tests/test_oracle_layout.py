@@ -225,10 +225,10 @@ def test_schedule_split(oracle):
     every group exactly once; ranges have equal weight up to one group; every column keeps the
     stated share of its weight fixed, up to one group."""
     m = random_csr(300, 300, 0.05, 3)
-    for P, q8, sw in [(1, 128, 1), (4, 192, 4), (7, 255, 1), (64, 256, 6), (5, 0, 2), (1000, 100, 1)]:
-        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw)
+    for P, q8, sw, gw in [(1, 128, 1, 0), (4, 192, 4, 0), (7, 255, 1, 9), (64, 256, 6, 100), (5, 0, 2, 1), (1000, 100, 1, 0)]:
+        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, group_weight=gw)
         assert h.P == P and h.fixed_q8 == q8
-        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64)
+        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64) + gw * np.arange(h.G + 1)
         cgp, comp_lo = h.array("col_group_ptr"), h.array("comp_lo")
         fs, fc = h.array("fixed_start"), h.array("fixed_col")
         assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
@@ -254,6 +254,40 @@ def test_schedule_split(oracle):
             assert np.array_equal(comp_lo, cgp[1:])                # nothing left to competition
         if q8 == 0:
             assert np.array_equal(comp_lo, cgp[:-1])               # everything competitive
+
+
+def test_combine_units(oracle):
+    """Combine units: every row block owns max(1, ceil(slots / unit_slots)) consecutive units that
+    tile its stripe_blk range in order; a unit starts at the first entry that reaches its share of
+    the row block's slots (brute force), so none holds more than that share plus one block."""
+    m = random_csr(400, 900, 0.08, 11)
+    for unit_slots in (64, 100, 1000, 1 << 20):
+        h = build(oracle, m, R=32, C=16, W=8, unit_slots=unit_slots)
+        sp, sb, slot_ptr = h.array("stripe_ptr"), h.array("stripe_blk"), h.array("slot_ptr")
+        up, us, uk, ms = h.array("unit_ptr"), h.array("unit_stripe"), h.array("unit_k"), h.array("multi_stripes")
+        size = (slot_ptr[1:] - slot_ptr[:-1])[sb].astype(np.int64)
+        assert h.U == up[-1] == len(us) and len(uk) == h.U + 1 and uk[-1] == h.B and up[0] == 0
+        multi = []
+        for bm in range(h.NBR):
+            k0, k1 = sp[bm], sp[bm + 1]
+            slots = int(size[k0:k1].sum())
+            u = max(1, -(-slots // unit_slots))
+            assert up[bm + 1] - up[bm] == u
+            assert np.all(us[up[bm]:up[bm + 1]] == bm)
+            assert uk[up[bm]] == k0 and uk[up[bm + 1]] == k1          # units tile the stripe
+            for i in range(u):
+                k = uk[up[bm] + i]
+                assert int(size[k0:k].sum()) * u >= i * slots          # the unit starts at its share ...
+                assert k == k0 or int(size[k0:k - 1].sum()) * u < i * slots   # ... and not one entry later
+                got = int(size[k:uk[up[bm] + i + 1]].sum())
+                assert got <= slots / u + (size[k0:k1].max() if k1 > k0 else 0)
+            if u > 1:
+                multi.append(bm)
+        assert np.array_equal(ms, np.array(multi, dtype=np.int32)) and h.NM == len(multi)
+        if unit_slots == 64:
+            assert h.NM > 0          # the case does split row blocks
+        if unit_slots == 1 << 20:
+            assert h.NM == 0 and h.U == h.NBR
 
 
 def test_hash_groups_similar_rows(oracle):
