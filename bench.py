@@ -48,14 +48,13 @@ def main() -> int:
     ap.add_argument("--cols-per-block", type=int, default=0)
     ap.add_argument("--num-workers", type=int, default=-1)
     ap.add_argument("--fixed-q8", type=int, default=-2)
-    ap.add_argument("--claim-chunk", type=int, default=-1)
+    ap.add_argument("--tickets-per-worker", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--rounds", type=int, default=0)
     ap.add_argument("--slot-weight", type=int, default=0)
     ap.add_argument("--combine-unit-slots", type=int, default=0)
     ap.add_argument("--hash-shift", type=int, default=-1)
-    ap.add_argument("--heavy-group-nnz", type=int, default=0)
-    ap.add_argument("--group-weight", type=int, default=-1)
+    ap.add_argument("--round-weight", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-csr", action="store_true")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
@@ -83,14 +82,13 @@ def main() -> int:
     if args.cols_per_block: params["cols_per_block"] = args.cols_per_block
     if args.num_workers >= 0: params["num_workers"] = args.num_workers
     if args.fixed_q8 >= -1: params["fixed_fraction_q8"] = args.fixed_q8
-    if args.claim_chunk >= 0: params["claim_chunk"] = args.claim_chunk
+    if args.tickets_per_worker: params["tickets_per_worker"] = args.tickets_per_worker
     if args.threads: params["threads_per_worker"] = args.threads
     if args.rounds: params["rounds_per_batch"] = args.rounds
     if args.slot_weight: params["slot_weight"] = args.slot_weight
     if args.combine_unit_slots: params["combine_unit_slots"] = args.combine_unit_slots
     if args.hash_shift >= 0: params["hash_shift"] = args.hash_shift
-    if args.heavy_group_nnz: params["heavy_group_nnz"] = args.heavy_group_nnz
-    if args.group_weight >= 0: params["group_weight"] = args.group_weight
+    if args.round_weight >= 0: params["round_weight"] = args.round_weight
     overridden = params != preset(args.config)
 
     dev = lambda a: torch.from_numpy(a).cuda()
@@ -152,10 +150,10 @@ def main() -> int:
                    "rows_per_block": info.rows_per_block, "cols_per_block": info.cols_per_block,
                    "group_width": info.group_width, "hash_shift": info.hash_shift, "blocks": info.blocks,
                    "slots": info.slots, "groups": info.groups, "workers": info.num_workers,
-                   "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
+                   "fixed_fraction_q8": info.fixed_fraction_q8, "tickets_per_worker": info.tickets_per_worker,
                    "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight,
                    "combine_unit_slots": info.combine_unit_slots, "combine_units": info.combine_units,
-                   "heavy_group_nnz": info.heavy_group_nnz, "group_weight": info.group_weight},
+                   "round_weight": info.round_weight},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic("k_spmv_part", m.name) if args.scale == 1.0 and not overridden else None,

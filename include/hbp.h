@@ -31,14 +31,22 @@
  *     stripe_blk          [B]      blocks of one row block, bn ascending (combine index)
  *     group_ptr           [G+1]    position of a group's first nonzero   (begin_ptr)
  *     group_slot          [G+1]    first slot of a group
+ *     group_rounds        [G+1]    rounds of all groups before (prefix sums of the longest row)
  *   Schedule (Section 3.3; the unit handed to a wavefront is a group, whose weight is its
- *   nonzeros plus slot_weight times its slots plus group_weight):
+ *   nonzeros plus slot_weight times its slots plus round_weight times its rounds, the
+ *   length of its longest row):
  *     col_group_ptr       [NBC+1]  first group of each block column
  *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
  *                                  the leading fixed_fraction of its weight as fixed part
  *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
  *                                  weight; worker w runs the fixed groups of range w
  *     fixed_col           [P]      block column that holds a worker's first group
+ *     ticket_ptr          [NBC+1]  per block column, range into ticket_group
+ *     ticket_group        [TE]     per block column: the first group of each of its competitive
+ *                                  tickets, then the column's end.  A ticket is worth
+ *                                  ticket_weight = max(1, total weight / (P * tickets_per_worker));
+ *                                  ticket t of a column starts at the first group whose preceding
+ *                                  competitive weight in the column reaches t * ticket_weight
  *   Combine units (Section 3.3, combine part: one workgroup per unit instead of one per row
  *   block, so that a row block with very many slots does not hold up the rest):
  *     unit_ptr            [NBR+1]  first unit of each row block; a row block has
@@ -89,21 +97,20 @@ typedef struct {
     int32_t rows_per_block;    /* R, 1..8192; 0 = default 512                                   */
     int32_t cols_per_block;    /* C, 1..32768; 0 = default 4096                                 */
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
-    int32_t num_workers;       /* P, persistent workgroups the schedule is built for; 0 = device default */
+    int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = device default */
     int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
-    int32_t claim_chunk;       /* groups per wavefront in one competitive ticket; 0 = sized so that a
-                                  worker draws about six tickets                                   */
+    int32_t tickets_per_worker;/* a competitive ticket is worth the whole schedule weight divided by
+                                  (P * tickets_per_worker): 1..64; 0 = default 8                      */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
     int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 1..64; 0 = default     */
     int32_t combine_unit_slots;/* slots one workgroup of the combine part should get at most: a row block
-                                  with more is cut into several units; >= 64; 0 = default 16384      */
-    int32_t group_weight;      /* schedule weight of a group on top of its nonzeros and slots, in
-                                  nonzeros: 0..1024; -1 = default                                    */
-    int32_t heavy_group_nnz;   /* a group with at least this many nonzeros is walked by all wavefronts of
-                                  its worker together instead of one; >= 1; 0 = default 32768        */
+                                  with more is cut into several units; >= 64; 0 = default: twice the
+                                  mean number of slots per row block, at least 16384                 */
+    int32_t round_weight;      /* schedule weight of one round of a group (its rounds = the length of
+                                  its longest row), in nonzeros: 0..1024; -1 = default 8             */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;
 
@@ -116,14 +123,16 @@ typedef struct {
     int64_t blocks, slots, groups;        /* B, S, G                                            */
     int32_t num_workers;         /* P                                                           */
     int32_t fixed_fraction_q8;   /* share of the work that is pre-assigned, in 1/256            */
-    int32_t claim_chunk;
+    int32_t tickets_per_worker;
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
     int32_t combine_unit_slots;  /* slots per combine unit the row blocks were cut for          */
-    int32_t heavy_group_nnz;     /* nonzeros from which a group is shared by a worker's wavefronts */
-    int32_t group_weight;        /* schedule weight of a group, in nonzeros                     */
+    int32_t reserved;
+    int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
+    int64_t ticket_weight;       /* schedule weight of one competitive ticket                   */
+    int64_t ticket_entries;      /* length of ticket_group                                      */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
@@ -140,7 +149,8 @@ typedef enum {
     HBP_ARRAY_ADD_SIGN = 13, /* int32 [nnz], derived on the device from seg_len when exported   */
     HBP_ARRAY_PARTIAL = 14,  /* float [S], per-slot partial sums left by the last hbp_spmv      */
     HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
-    HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22
+    HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22,
+    HBP_ARRAY_TICKET_PTR = 23, HBP_ARRAY_TICKET_GROUP = 24, HBP_ARRAY_GROUP_ROUNDS = 25
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */

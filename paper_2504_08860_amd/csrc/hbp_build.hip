@@ -228,6 +228,18 @@ __global__ __launch_bounds__(256) void k_iota_units(int32_t *unit_ptr, int32_t *
     if (i < NBR) unit_stripe[i] = (int32_t)i;
 }
 
+__global__ __launch_bounds__(256) void k_iota_ptr(int32_t *p, int32_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i <= n) p[i] = (int32_t)i;
+}
+
+__global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int32_t v, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 __global__ void k_set_i32(int32_t *p, int32_t v)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
@@ -433,7 +445,7 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
                                                      const int32_t *__restrict__ seg_j, const int32_t *__restrict__ slot_ptr,
                                                      const int32_t *__restrict__ blk_group_ptr, int32_t W,
                                                      uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
-                                                     int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz,
+                                                     int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz, uint32_t *__restrict__ group_longest,
                                                      int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk)
 {
     extern __shared__ uint64_t keys[];
@@ -467,10 +479,14 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
     __syncthreads();
     const int g0 = blk_group_ptr[b], ng = (m + W - 1) / W;
     for (int gi = threadIdx.x; gi < ng; gi += 256) {
-        uint32_t sum = 0;
+        uint32_t sum = 0, longest = 0;
         const int e1 = min(m, (gi + 1) * W);
-        for (int i = gi * W; i < e1; i++) sum += (uint32_t)keys[i];
+        for (int i = gi * W; i < e1; i++) {
+            sum += (uint32_t)keys[i];
+            longest = max(longest, (uint32_t)keys[i]);
+        }
         group_nnz[g0 + gi] = sum;
+        group_longest[g0 + gi] = longest;
         group_slot[g0 + gi] = s0 + gi * W;
         group_blk[g0 + gi] = b;
     }
@@ -588,13 +604,18 @@ __global__ __launch_bounds__(256) void k_unit_fill(const int32_t *__restrict__ s
 
 // ------------------------------------------------------------------ Section 3.3: schedule
 //
-// Weight of a group = its nonzeros + SW times its slots + GW (SW = slot_weight, GW = group_weight:
-// the per-row and per-group costs of a group measured in nonzeros);
-// Wt(g) = group_ptr[g] + SW * group_slot[g] + GW * g is the weight of all groups before g.
+// Weight of a group = its nonzeros + SW times its slots + RW times its rounds (SW = slot_weight,
+// RW = round_weight: the costs of a row and of a round of a group measured in nonzeros; a group
+// has as many rounds as its longest row has nonzeros);
+// Wt(g) = group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g] is the weight of all groups
+// before g.
 struct Weights {
-    const int32_t *group_ptr, *group_slot;
-    int64_t SW, GW;
-    __device__ __forceinline__ int64_t before(int32_t g) const { return (int64_t)group_ptr[g] + SW * group_slot[g] + GW * g; }
+    const int32_t *group_ptr, *group_slot, *group_rounds;
+    int64_t SW, RW;
+    __device__ __forceinline__ int64_t before(int32_t g) const
+    {
+        return (int64_t)group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g];
+    }
 };
 
 __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict__ col_blk_ptr, const int32_t *__restrict__ blk_group_ptr,
@@ -643,6 +664,44 @@ __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__
         if (col_group_ptr[mid] <= lo) c_lo = mid; else c_hi = mid - 1;
     }
     fixed_col[w] = c_lo;
+}
+
+// Competitive tickets: a ticket is worth Wq.  The competitive groups of column c, [comp_lo, end),
+// of weight cw, make ceil(cw / Wq) tickets; a column takes that many entries of ticket_group plus
+// one for its end.
+__global__ __launch_bounds__(256) void k_ticket_count(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ comp_lo,
+                                                      Weights wt, int32_t NBC, int64_t Wq, uint32_t *__restrict__ count)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= NBC) return;
+    const int64_t cw = wt.before(col_group_ptr[c + 1]) - wt.before(comp_lo[c]);
+    count[c] = (uint32_t)((cw + Wq - 1) / Wq + 1);
+}
+
+// Entry e belongs to the column c with ticket_ptr[c] <= e < ticket_ptr[c + 1]; it is ticket
+// t = e - ticket_ptr[c] of that column and starts at the first group whose preceding competitive
+// weight in the column reaches t Wq, or, for the last entry of the column, the column's end.
+__global__ __launch_bounds__(256) void k_ticket_fill(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ comp_lo,
+                                                     Weights wt, int32_t NBC, int64_t Wq, const int32_t *__restrict__ ticket_ptr,
+                                                     int64_t capacity, int32_t *__restrict__ ticket_group)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= ticket_ptr[NBC] || e >= capacity) return;
+    int32_t c_lo = 0, c_hi = NBC - 1;  // largest c with ticket_ptr[c] <= e
+    while (c_lo < c_hi) {
+        const int32_t mid = c_lo + ((c_hi - c_lo + 1) >> 1);
+        if (ticket_ptr[mid] <= e) c_lo = mid; else c_hi = mid - 1;
+    }
+    const int32_t c = c_lo, t = (int32_t)(e - ticket_ptr[c]);
+    const int32_t g0 = comp_lo[c], g1 = col_group_ptr[c + 1];
+    if (t == ticket_ptr[c + 1] - ticket_ptr[c] - 1) { ticket_group[e] = g1; return; }
+    const int64_t w0 = wt.before(g0), need = (int64_t)t * Wq;
+    int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with Wt(g) - w0 >= need
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (wt.before(mid) - w0 >= need) hi = mid; else lo = mid + 1;
+    }
+    ticket_group[e] = lo;
 }
 
 // One device allocation carved into 256-byte aligned arrays: reserve() every array first,
@@ -708,6 +767,10 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
     own0.reserve(&h->fixed_col, (int64_t)h->P);
     own0.reserve(&h->unit_ptr, NBR + 1);
+    own0.reserve(&h->ticket_ptr, NBC + 2);  // one spare entry: the counts are scanned in place
+    own0.reserve(&h->ticket_scan_tmp, NBC / kScanTile + 2);
+    // at most Wt(G) / ticket_weight + 2 NBC <= 2 P tickets_per_worker + 2 NBC entries
+    own0.reserve(&h->ticket_group, 2 * (int64_t)h->P * h->tickets_per_worker + 2 * NBC + 2);
     HBP_TRY(own0.commit());
     h->arena[0] = own0.base();
     HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
@@ -717,6 +780,9 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipMemsetAsync(h->col_group_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_start, 0, sizeof(int32_t) * (size_t)(h->P + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_col, 0, sizeof(int32_t) * (size_t)h->P, st));
+    k_iota_ptr<<<blocks_for(NBC + 1, 256), 256, 0, st>>>(h->ticket_ptr, (int32_t)NBC);  // no tickets yet
+    k_fill_i32<<<blocks_for(NBC, 256), 256, 0, st>>>(h->ticket_group, 0, NBC);
+    h->ticket_entries = NBC; h->ticket_weight = 1;
 
     if (nnz == 0) {  // empty matrix: no blocks; the combine part alone writes y = 0
         h->B = h->S = h->G = 0;
@@ -724,15 +790,17 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         Arena own1(true);
         own1.reserve(&h->blk_bm, 1); own1.reserve(&h->blk_bn, 1); own1.reserve(&h->slot_ptr, 1);
         own1.reserve(&h->blk_group_ptr, 1); own1.reserve(&h->stripe_blk, 1); own1.reserve(&h->group_ptr, 1);
-        own1.reserve(&h->group_slot, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
+        own1.reserve(&h->group_slot, 1); own1.reserve(&h->group_rounds, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
         own1.reserve(&h->col_local, 1); own1.reserve(&h->data, 1); own1.reserve(&h->partial, 1);
         own1.reserve(&h->unit_stripe, NBR + 1); own1.reserve(&h->unit_k, NBR + 2); own1.reserve(&h->multi_stripes, 1);
         HBP_TRY(own1.commit());
         h->arena[1] = own1.base();
         h->U = NBR; h->NM = 0;
+        if (h->unit_slots == 0) h->unit_slots = 16384;
         k_iota_units<<<blocks_for(NBR + 1, 256), 256, 0, st>>>(h->unit_ptr, h->unit_stripe, h->unit_k, (int32_t)NBR);
         HBP_HIP(hipMemsetAsync(h->slot_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->blk_group_ptr, 0, 4, st));
         HBP_HIP(hipMemsetAsync(h->group_ptr, 0, 4, st)); HBP_HIP(hipMemsetAsync(h->group_slot, 0, 4, st));
+        HBP_HIP(hipMemsetAsync(h->group_rounds, 0, 4, st));
         HBP_HIP(hipStreamSynchronize(st));
         return HBP_OK;
     }
@@ -810,11 +878,16 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own1.reserve(&h->blk_bm, B + 1); own1.reserve(&h->blk_bn, B + 1);
     own1.reserve(&h->slot_ptr, B + 1); own1.reserve(&h->blk_group_ptr, B + 1);
     own1.reserve(&h->stripe_blk, B + 1);
-    own1.reserve(&h->group_ptr, G + 1); own1.reserve(&h->group_slot, G + 1);
+    own1.reserve(&h->group_ptr, G + 1); own1.reserve(&h->group_slot, G + 1); own1.reserve(&h->group_rounds, G + 1);
     own1.reserve(&h->row_local, S + 1); own1.reserve(&h->seg_len, S + 1);
     // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
     own1.reserve(&h->col_local, nnz + 256); own1.reserve(&h->data, nnz + 256);
     own1.reserve(&h->partial, S + 1);
+    if (h->unit_slots == 0) {
+        // default: only row blocks with more than twice the average number of slots are cut
+        const int64_t twice_mean = 2 * ((S + NBR - 1) / NBR);
+        h->unit_slots = (int32_t)std::min<int64_t>(std::max<int64_t>(16384, twice_mean), INT32_MAX);
+    }
     const int64_t max_units = NBR + S / h->unit_slots + 2;
     own1.reserve(&h->unit_stripe, max_units); own1.reserve(&h->unit_k, max_units + 1);
     own1.reserve(&h->multi_stripes, NBR);
@@ -823,10 +896,10 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     Arena tmp2(false);
     uint32_t *stripe_cum, *unit_cnt, *multi_idx;
     tmp2.reserve(&stripe_cum, B + 1); tmp2.reserve(&unit_cnt, NBR + 1); tmp2.reserve(&multi_idx, NBR + 1);
-    uint32_t *bucket_key, *bucket_seg, *group_nnz;
+    uint32_t *bucket_key, *bucket_seg, *group_nnz, *group_longest;
     int32_t *slot_j, *group_blk;
     tmp2.reserve(&bucket_key, S); tmp2.reserve(&bucket_seg, S);
-    tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_blk, G + 1);
+    tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_longest, G + 1); tmp2.reserve(&group_blk, G + 1);
     HBP_TRY(tmp2.commit());
 
     k_compact_blocks<<<blocks_for(std::max<int64_t>(D, NBC) + 1, 256), 256, 0, st>>>(
@@ -851,19 +924,21 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     const size_t order_lds = sizeof(uint64_t) * (size_t)n2;
     HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
-                                                            h->row_local, h->seg_len, slot_j, group_nnz, h->group_slot,
+                                                            h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
                                                             group_blk);
     HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
+    HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
     // step 7
     k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
                                              slot_j, (int32_t)G, C, h->col_local, h->data);
     HBP_HIP(hipGetLastError());
-    uint32_t n_units = 0, n_multi = 0;
+    uint32_t n_units = 0, n_multi = 0, n_rounds = 0;
+    HBP_HIP(hipMemcpyAsync(&n_rounds, h->group_rounds + G, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&n_units, h->unit_ptr + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&n_multi, multi_idx + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipStreamSynchronize(st));
-    h->U = n_units; h->NM = n_multi;
+    h->U = n_units; h->NM = n_multi; h->total_rounds = n_rounds;
     return HBP_OK;
 }
 
@@ -873,10 +948,24 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
     if (h->G > 0) {
         const int32_t NBC = (int32_t)h->NBC;
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
-        const Weights wt{h->group_ptr, h->group_slot, (int64_t)h->slot_weight, (int64_t)h->group_weight};
+        const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight};
         k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
         k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, (int32_t)h->G, h->P,
                                                                           h->fixed_start, h->fixed_col);
+        // ticket weight: the whole weight over P tickets_per_worker tickets (the sizes are on the host)
+        const int64_t total = h->nnz + (int64_t)h->slot_weight * h->S + (int64_t)h->round_weight * h->total_rounds;
+        const int64_t Wq = std::max<int64_t>(1, total / ((int64_t)h->P * h->tickets_per_worker));
+        const int64_t capacity = 2 * (int64_t)h->P * h->tickets_per_worker + 2 * h->NBC + 2;
+        h->ticket_weight = Wq;
+        k_ticket_count<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, h->comp_lo, wt, NBC, Wq, (uint32_t *)h->ticket_ptr);
+        HBP_TRY(exclusive_scan<kOpIdentity>((uint32_t *)h->ticket_ptr, (uint32_t *)h->ticket_ptr, h->NBC, 1, h->ticket_scan_tmp, st));
+        k_ticket_fill<<<blocks_for(capacity, 256), 256, 0, st>>>(h->col_group_ptr, h->comp_lo, wt, NBC, Wq, h->ticket_ptr, capacity,
+                                                                 h->ticket_group);
+        int32_t entries = 0;
+        HBP_HIP(hipMemcpyAsync(&entries, h->ticket_ptr + h->NBC, 4, hipMemcpyDeviceToHost, st));
+        HBP_HIP(hipStreamSynchronize(st));
+        if (entries < 0 || entries > capacity) return HBP_ERR_INTERNAL;
+        h->ticket_entries = entries;
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

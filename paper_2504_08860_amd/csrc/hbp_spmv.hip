@@ -147,7 +147,7 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float
 }
 
 template <int THREADS, int U, int GP>
-__global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
+__global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                                                        const float *__restrict__ x, float *__restrict__ partial,
                                                        float *__restrict__ y, uint32_t *__restrict__ col_ticket,
                                                        uint64_t *__restrict__ dbg)
@@ -158,12 +158,6 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
     __shared__ int32_t sh_grp;   // next group of the current range, drawn by the wavefronts
     __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
-    constexpr int kHeavyCap = 64;
-    __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
-    __shared__ int32_t sh_heavy_n;
-    __shared__ int32_t sh_lens[THREADS];  // per wavefront: segment lengths of the heavy group being cut
-    __shared__ int32_t sh_cut_k[THREADS / 64 + 1];   // heavy group: first round of every wavefront's share
-    __shared__ uint32_t sh_cut_pos[THREADS / 64 + 1];  // and the nonzeros before that round
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -175,12 +169,6 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     // matrix.
     const int32_t n_workers = (int32_t)gridDim.x;
     int32_t worker = (int32_t)blockIdx.x;
-    // Row blocks that the combine part cuts into several units are summed into y with atomic
-    // adds: their rows of y start at zero.
-    for (int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x; i < (int64_t)L.NM * L.R; i += (int64_t)n_workers * THREADS) {
-        const int64_t row = (int64_t)L.multi_stripes[i / L.R] * L.R + i % L.R;
-        if (row < L.n_rows) y[row] = 0.f;
-    }
     if ((n_workers & 31) == 0) {
         const int32_t xcd = worker & 7, i = worker >> 3;
         worker = (((i >> 2) << 3) + xcd) * 4 + (i & 3);
@@ -278,46 +266,32 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
             k = k_end;
         }
     };
-    // A group with at least heavy_nnz nonzeros would keep one wavefront busy long after the rest
-    // of the worker has run dry.  The wavefront that draws one puts it on the worker's list
-    // instead (true), unless the list is full (then it walks the group alone).
-    auto defer_heavy = [&](int32_t group, uint32_t count) __attribute__((always_inline)) {
-        if (count < (uint32_t)L.heavy_nnz) return false;
-        int32_t idx = 0;
-        if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
-        idx = __builtin_amdgcn_readfirstlane(idx);
-        if (idx >= kHeavyCap) return false;
-        if (lane == 0) sh_heavy[idx] = group;
-        return true;
-    };
     // Runs the groups [g_begin, g_end) of block column bn with all wavefronts of the worker.
     auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
         const uint64_t t_in = dbg ? wall_clock64() : 0;
         __syncthreads();  // every wavefront has left the previous range (and its slice of x)
-        if (threadIdx.x == 0) { sh_grp = g_begin; sh_heavy_n = 0; }
+        if (threadIdx.x == 0) sh_grp = g_begin;
         __syncthreads();
         int32_t g = draw_pack(), g1 = draw_pack(), g2 = draw_pack();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
-        uint32_t base[GP], basen[GP], cntn[GP];  // positions stay 32-bit: nnz < 2^31
+        uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
         float done_acc[GP];
 #pragma unroll
         for (int q = 0; q < GP; q++) {
             s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
-            base[q] = basen[q] = cntn[q] = 0;
+            base[q] = basen[q] = 0;
             done_slot[q] = -1;
             done_acc[q] = 0.f;
             if (g + q < g_end) {
                 s0[q] = uniform_load(L.group_slot, g + q);
                 s1[q] = uniform_load(L.group_slot, g + q + 1);
                 base[q] = (uint32_t)uniform_load(L.group_ptr, g + q);
-                if (defer_heavy(g + q, (uint32_t)uniform_load(L.group_ptr, g + q + 1) - base[q])) s1[q] = s0[q];
                 n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
             }
             if (g1 + q < g_end) {
                 s0n[q] = uniform_load(L.group_slot, g1 + q);
                 s1n[q] = uniform_load(L.group_slot, g1 + q + 1);
                 basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
-                cntn[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q + 1) - basen[q];
             }
         }
         // the first packs' metadata is on its way while the slice of x is staged
@@ -330,21 +304,17 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         while (g < g_end) {
             const int32_t g3 = draw_pack();  // before the scalar loads: its wait would cover them too
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
-            uint32_t basenn[GP], cntnn[GP];
+            uint32_t basenn[GP];
             float acc[GP];
 #pragma unroll
             for (int q = 0; q < GP; q++) {
                 s0nn[q] = s1nn[q] = nn[q] = 0;
-                basenn[q] = cntnn[q] = 0;
+                basenn[q] = 0;
                 if (g2 + q < g_end) {
                     s0nn[q] = uniform_load(L.group_slot, g2 + q);
                     s1nn[q] = uniform_load(L.group_slot, g2 + q + 1);
                     basenn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q);
-                    cntnn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q + 1) - basenn[q];
                 }
-                // the next pack's metadata has arrived an iteration ago: heavy groups among them go
-                // to the worker's list and look empty to this wavefront
-                if (defer_heavy(g1 + q, cntn[q])) s1n[q] = s0n[q];
             }
             bool wide = false;
             if constexpr (GP == 1) {
@@ -402,7 +372,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                 done_acc[q] = acc[q];
                 done_slot[q] = slot[q];
                 s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
-                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q]; cntn[q] = cntnn[q];
+                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
             }
             g = g1; g1 = g2; g2 = g3;
         }
@@ -410,65 +380,6 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         for (int q = 0; q < GP; q++)
             if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
 
-        // Heavy groups of this range: all wavefronts of the worker walk each of them together.
-        // Wavefront w takes the rounds [k_w, k_{w+1}), where k_w is the first round that has
-        // w / kWaves of the group's nonzeros before it, and the per-lane sums of the wavefronts
-        // are added in LDS in wavefront order.
-        __syncthreads();
-        const int32_t n_heavy = min(sh_heavy_n, kHeavyCap);
-        for (int32_t i = 0; i < n_heavy; i++) {
-            const int32_t gh = sh_heavy[i];
-            const int32_t hs0 = uniform_load(L.group_slot, gh), hs1 = uniform_load(L.group_slot, gh + 1);
-            const uint32_t b0 = (uint32_t)uniform_load(L.group_ptr, gh);
-            const uint32_t total = (uint32_t)uniform_load(L.group_ptr, gh + 1) - b0;
-            const int32_t len = hs0 + lane < hs1 ? (int32_t)L.seg_len[hs0 + lane] : 0;
-            int32_t *lens = sh_lens + wave * 64;
-            lens[lane] = len;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            // nonzeros of the group in rounds 0 .. k-1; every lane may ask for another k
-            auto before = [&](int32_t k) __attribute__((always_inline)) {
-                uint32_t sum = 0;
-#pragma unroll 16
-                for (int t = 0; t < 64; t++) sum += (uint32_t)min(lens[t], k);
-                return sum;
-            };
-            // smallest k with before(k) >= target, by three 64-way splits of (0, 65536]: a segment
-            // has fewer than 65536 nonzeros, so before(65536) = total >= target
-            const uint32_t target = (uint32_t)(((uint64_t)total * (uint32_t)wave) / (uint32_t)kWaves);
-            int32_t cut_k = 0;
-            uint32_t cut_pos = 0;
-            if (target > 0) {
-                int32_t lo = 0;
-                auto split = [&](int32_t step) __attribute__((always_inline)) {
-                    // candidates lo + step, lo + 2 step, ...: the last one is known to reach the target
-                    const uint32_t got = before(lo + (lane + 1) * step);
-                    const int first = __builtin_ctzll(__ballot(got >= target));
-                    lo += first * step;
-                    return (uint32_t)__shfl(got, first);
-                };
-                split(1024);
-                split(16);
-                cut_pos = split(1);
-                cut_k = lo + 1;
-            }
-            if (lane == 0) { sh_cut_k[wave] = cut_k; sh_cut_pos[wave] = cut_pos; }
-            if (threadIdx.x == 0) sh_cut_k[kWaves] = 0x10000;
-            __syncthreads();
-            const int32_t k_lo = sh_cut_k[wave], k_hi = sh_cut_k[wave + 1];
-            uint32_t pos = b0 + sh_cut_pos[wave];
-            float sum = 0.f;
-            walk_rounds(pos, b0, min(len, k_hi), k_lo, sum);
-            sh_hand[threadIdx.x] = sum;
-            __syncthreads();
-            if (wave == 0 && hs0 + lane < hs1) {
-                float total_sum = sh_hand[lane];
-#pragma unroll
-                for (int w = 1; w < kWaves; w++) total_sum += sh_hand[w * 64 + lane];
-                partial[hs0 + lane] = total_sum;
-            }
-            __syncthreads();  // sh_hand and the cuts are reused by the next heavy group
-        }
     };
 
     // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
@@ -498,16 +409,15 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
     // dry it moves to the column with the most groups left, and stages that segment only once
     // a ticket there has actually given it work.
     if (dbg) dbg_fixed_end = wall_clock64();
-    const int32_t per_ticket = kWaves * chunk;
     int32_t bn = home;
     while (L.competitive) {
-        if (threadIdx.x == 0) sh_next = (int32_t)atomicAdd(&col_ticket[bn], 1u);
+        if (threadIdx.x == 0) sh_next = (int32_t)min(atomicAdd(&col_ticket[bn], 1u), 0x7fffffffu);
         __syncthreads();
-        const int64_t g0 = L.comp_lo[bn] + (int64_t)sh_next * per_ticket;
-        const int32_t hi = L.col_group_ptr[bn + 1];
+        const int32_t t = sh_next, t0 = L.ticket_ptr[bn], n_tickets = L.ticket_ptr[bn + 1] - t0 - 1;
         __syncthreads();  // sh_next is rewritten below
-        if (g0 < hi) {
-            run_range(bn, (int32_t)g0, (int32_t)min((int64_t)hi, g0 + per_ticket));
+        if (t < n_tickets) {
+            const int32_t g0 = L.ticket_group[t0 + t], g1 = L.ticket_group[t0 + t + 1];
+            if (g0 < g1) run_range(bn, g0, g1);  // a ticket behind a group heavier than a ticket is empty
             continue;
         }
         if (wave == 0) {  // this column is dry: look for the one with the most groups left
@@ -517,8 +427,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
                 int32_t c = c0 + lane;
                 uint32_t left = 0;
                 if (c < L.NBC) {
-                    const int64_t total = L.col_group_ptr[c + 1] - L.comp_lo[c];
-                    const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * per_ticket;
+                    const int64_t total = L.ticket_ptr[c + 1] - L.ticket_ptr[c] - 1;  // tickets weigh the same
+                    const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     left = used < total ? (uint32_t)(total - used) : 0u;
                 }
 #pragma unroll
@@ -535,6 +445,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L, int32_t chunk,
         bn = sh_next;
         __syncthreads();
         if (bn < 0) break;
+    }
+    // Row blocks that the combine part cuts into several units are summed into y with atomic
+    // adds: their rows of y start at zero.  (Done last: in front of the first range it delays
+    // every worker's start.)
+    for (int32_t ms = (int32_t)blockIdx.x; ms < L.NM; ms += n_workers) {
+        const int64_t r0 = (int64_t)L.multi_stripes[ms] * L.R;
+        const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
+        for (int32_t r = threadIdx.x; r < rows; r += THREADS) y[r0 + r] = 0.f;
     }
     if (dbg && lane == 0) {
         uint64_t *o = dbg + ((size_t)blockIdx.x * kWaves + wave) * 4;
@@ -655,9 +573,9 @@ Layout hbp_view(const hbp_handle_s *h)
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
     L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
     L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
+    L.ticket_ptr = h->ticket_ptr; L.ticket_group = h->ticket_group;
     L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
     L.NM = (int32_t)h->NM;
-    L.heavy_nnz = h->heavy_nnz;
     return L;
 }
 
@@ -689,7 +607,7 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, f
                                     kMaxC * (int)sizeof(float)));
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, h->claim_chunk, x, h->partial, y, h->ticket, dbg);
+    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, h->partial, y, h->ticket, dbg);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }

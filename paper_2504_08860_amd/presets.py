@@ -1,5 +1,5 @@
 """Block-parameter presets for the five benchmark workloads (R rows x C columns per block,
-fixed share of the schedule, claim chunk).  Chosen by measurement on MI355X; the library's
+fixed share of the schedule).  Chosen by measurement on MI355X; the library's
 own defaults are the paper's 512 x 4096."""
 from __future__ import annotations
 
@@ -7,7 +7,7 @@ PRESETS = {
     1: dict(rows_per_block=512, cols_per_block=4096),
     2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4),
     3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
-    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=224),
+    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=192, round_weight=12),
     5: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
 }
 
