@@ -97,7 +97,8 @@ typedef struct {
     int32_t rows_per_block;    /* R, 1..8192; 0 = default 512                                   */
     int32_t cols_per_block;    /* C, 1..32768; 0 = default 4096                                 */
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
-    int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = device default */
+    int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = as many as
+                                  fit on the device at once, but no more than one per threads_per_worker / 64 groups */
     int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
     int32_t tickets_per_worker;/* a competitive ticket is worth the whole schedule weight divided by

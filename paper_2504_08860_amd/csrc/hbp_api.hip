@@ -1,6 +1,7 @@
 // C ABI of libhbp: argument checking, handle lifetime, export and timing hooks.
 #include "hbp_internal.h"
 
+#include <algorithm>
 #include <chrono>
 #include <cstring>
 #include <new>
@@ -107,6 +108,12 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         free_arrays(h);
         delete h;
         return rc;
+    }
+    if (p.num_workers == 0) {
+        // device default: no more workers than the groups can keep busy, one group per wavefront
+        const int64_t waves = h->threads / hbp::kWave;
+        const int64_t useful = std::max<int64_t>(1, (h->G + waves - 1) / waves);
+        if (useful < h->P) h->P = (int32_t)useful;
     }
     rc = hbp::build_schedule(h, (hipStream_t)stream);
     if (rc != HBP_OK) {

@@ -4,7 +4,7 @@ own defaults are the paper's 512 x 4096."""
 from __future__ import annotations
 
 PRESETS = {
-    1: dict(rows_per_block=512, cols_per_block=4096),
+    1: dict(rows_per_block=512, cols_per_block=4096, fixed_fraction_q8=256),
     2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4),
     3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
     4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=192, round_weight=12),
