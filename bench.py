@@ -48,7 +48,7 @@ def main() -> int:
     ap.add_argument("--cols-per-block", type=int, default=0)
     ap.add_argument("--num-workers", type=int, default=-1)
     ap.add_argument("--fixed-q8", type=int, default=-2)
-    ap.add_argument("--tickets-per-worker", type=int, default=0)
+    ap.add_argument("--claim-chunk", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--rounds", type=int, default=0)
     ap.add_argument("--slot-weight", type=int, default=0)
@@ -82,7 +82,7 @@ def main() -> int:
     if args.cols_per_block: params["cols_per_block"] = args.cols_per_block
     if args.num_workers >= 0: params["num_workers"] = args.num_workers
     if args.fixed_q8 >= -1: params["fixed_fraction_q8"] = args.fixed_q8
-    if args.tickets_per_worker: params["tickets_per_worker"] = args.tickets_per_worker
+    if args.claim_chunk: params["claim_chunk"] = args.claim_chunk
     if args.threads: params["threads_per_worker"] = args.threads
     if args.rounds: params["rounds_per_batch"] = args.rounds
     if args.slot_weight: params["slot_weight"] = args.slot_weight
@@ -150,7 +150,7 @@ def main() -> int:
                    "rows_per_block": info.rows_per_block, "cols_per_block": info.cols_per_block,
                    "group_width": info.group_width, "hash_shift": info.hash_shift, "blocks": info.blocks,
                    "slots": info.slots, "groups": info.groups, "workers": info.num_workers,
-                   "fixed_fraction_q8": info.fixed_fraction_q8, "tickets_per_worker": info.tickets_per_worker,
+                   "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
                    "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight,
                    "combine_unit_slots": info.combine_unit_slots, "combine_units": info.combine_units,
                    "round_weight": info.round_weight},

@@ -41,12 +41,6 @@
  *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
  *                                  weight; worker w runs the fixed groups of range w
  *     fixed_col           [P]      block column that holds a worker's first group
- *     ticket_ptr          [NBC+1]  per block column, range into ticket_group
- *     ticket_group        [TE]     per block column: the first group of each of its competitive
- *                                  tickets, then the column's end.  A ticket is worth
- *                                  ticket_weight = max(1, total weight / (P * tickets_per_worker));
- *                                  ticket t of a column starts at the first group whose preceding
- *                                  competitive weight in the column reaches t * ticket_weight
  *   Combine units (Section 3.3, combine part: one workgroup per unit instead of one per row
  *   block, so that a row block with very many slots does not hold up the rest):
  *     unit_ptr            [NBR+1]  first unit of each row block; a row block has
@@ -101,8 +95,8 @@ typedef struct {
                                   fit on the device at once, but no more than one per threads_per_worker / 64 groups */
     int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
-    int32_t tickets_per_worker;/* a competitive ticket is worth the whole schedule weight divided by
-                                  (P * tickets_per_worker): 1..64; 0 = default 8                      */
+    int32_t claim_chunk;       /* competitive part: groups per wavefront that a worker claims from a
+                                  block column at a time, 1..65536; 0 = default (two draws per wavefront) */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
@@ -124,7 +118,7 @@ typedef struct {
     int64_t blocks, slots, groups;        /* B, S, G                                            */
     int32_t num_workers;         /* P                                                           */
     int32_t fixed_fraction_q8;   /* share of the work that is pre-assigned, in 1/256            */
-    int32_t tickets_per_worker;
+    int32_t claim_chunk;
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
@@ -132,8 +126,6 @@ typedef struct {
     int32_t reserved;
     int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
-    int64_t ticket_weight;       /* schedule weight of one competitive ticket                   */
-    int64_t ticket_entries;      /* length of ticket_group                                      */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
@@ -151,7 +143,7 @@ typedef enum {
     HBP_ARRAY_PARTIAL = 14,  /* float [S], per-slot partial sums left by the last hbp_spmv      */
     HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
     HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22,
-    HBP_ARRAY_TICKET_PTR = 23, HBP_ARRAY_TICKET_GROUP = 24, HBP_ARRAY_GROUP_ROUNDS = 25
+    HBP_ARRAY_GROUP_ROUNDS = 23
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */

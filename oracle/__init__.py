@@ -27,9 +27,9 @@ ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
     "data": (12, np.float32), "add_sign": (13, np.int32), "col_group_ptr": (14, np.int32),
     "comp_lo": (15, np.int32), "fixed_start": (16, np.int32), "fixed_col": (17, np.int32),
     "unit_ptr": (18, np.int32), "unit_stripe": (19, np.int32), "unit_k": (20, np.int32), "multi_stripes": (21, np.int32),
-    "ticket_ptr": (22, np.int32), "ticket_group": (23, np.int32), "group_rounds": (24, np.int32),
+    "group_rounds": (22, np.int32),
 }
-DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8", "U", "NM", "TE", "ticket_weight")
+DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8", "U", "NM")
 
 
 def build(force: bool = False) -> str:
@@ -53,7 +53,7 @@ def _load():
         lib.oracle_hash_key.restype = ctypes.c_uint32
         lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
         lib.oracle_sample_shift.restype = i32
-        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32]
+        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32]
         lib.oracle_hbp_build.restype = vp
         lib.oracle_hbp_free.argtypes = [vp]
         lib.oracle_hbp_free.restype = None
@@ -96,11 +96,10 @@ class OracleHbp:
     """The compact HBP layout built by the C oracle; arrays are numpy copies."""
 
     def __init__(self, ptr, col, val, n_rows, n_cols, R=512, C=4096, W=64, hash_shift=-1,
-                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, tickets_per_worker=8):
+                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0):
         lib = _load()
         self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(n_rows), int(n_cols), int(R), int(C), int(W),
-                                       int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(unit_slots),
-                                       int(tickets_per_worker))
+                                       int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(unit_slots))
         if not self._h:
             raise ValueError("oracle_hbp_build rejected the parameters")
         dims = np.zeros(len(DIMS), dtype=np.int64)

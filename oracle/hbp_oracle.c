@@ -145,9 +145,6 @@ typedef struct {
     int32_t *comp_lo;             /* NBC : first competitive group of a block column          */
     int32_t *fixed_start;         /* P+1 : group ranges of the workers                        */
     int32_t *fixed_col;           /* P   : block column holding a worker's first group        */
-    int64_t TE, ticket_weight;    /* entries of ticket_group; weight of one competitive ticket */
-    int32_t *ticket_ptr;          /* NBC+1 : first ticket_group entry of each block column    */
-    int32_t *ticket_group;        /* TE  : first group of every ticket, then the column's end */
     int64_t U, NM;                /* combine units, row blocks cut into more than one unit    */
     int32_t *unit_ptr;            /* NBR+1 : units of each row block                          */
     int32_t *unit_stripe;         /* U   : row block of a unit                                */
@@ -179,7 +176,6 @@ void oracle_hbp_free(oracle_hbp *h)
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_rounds); free(h->group_slot);
     free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
-    free(h->ticket_ptr); free(h->ticket_group);
     free(h->unit_ptr); free(h->unit_stripe); free(h->unit_k); free(h->multi_stripes);
     free(h);
 }
@@ -189,9 +185,9 @@ void oracle_hbp_free(oracle_hbp *h)
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
-                             int32_t slot_weight, int32_t round_weight, int32_t unit_slots, int32_t tickets_per_worker)
+                             int32_t slot_weight, int32_t round_weight, int32_t unit_slots)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1 || round_weight < 0 || unit_slots < 1 || tickets_per_worker < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1 || round_weight < 0 || unit_slots < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -343,35 +339,6 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
             h->fixed_col[w] = (int32_t)c;
         }
     }
-    /* Competitive tickets.  A ticket is worth ticket_weight = max(1, Wt(G) / (P * tickets_per_worker))
-     * (integer division).  The competitive groups of a column, [comp_lo, end of column), of weight
-     * cw, make ceil(cw / ticket_weight) tickets; ticket t starts at the first group whose preceding
-     * competitive weight in the column reaches t * ticket_weight.  ticket_group lists, column after
-     * column, the first group of every ticket followed by the column's end. */
-    {
-        int64_t Wq = WT(G) / (num_workers * (int64_t)tickets_per_worker);
-        if (Wq < 1) Wq = 1;
-        h->ticket_weight = Wq;
-        h->ticket_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
-        int64_t te = 0;
-        for (int64_t c = 0; c < NBC; c++) {
-            int64_t cw = WT(h->col_group_ptr[c + 1]) - WT(h->comp_lo[c]);
-            h->ticket_ptr[c] = (int32_t)te;
-            te += (cw + Wq - 1) / Wq + 1;
-        }
-        h->ticket_ptr[NBC] = (int32_t)te;
-        h->TE = te;
-        h->ticket_group = (int32_t *)malloc(sizeof(int32_t) * (size_t)(te + 1));
-        for (int64_t c = 0; c < NBC; c++) {
-            int64_t lo = h->comp_lo[c], hi = h->col_group_ptr[c + 1], g = lo;
-            int64_t n = h->ticket_ptr[c + 1] - h->ticket_ptr[c] - 1;
-            for (int64_t t = 0; t < n; t++) {
-                while (g < hi && WT(g) - WT(lo) < t * Wq) g++;
-                h->ticket_group[h->ticket_ptr[c] + t] = (int32_t)g;
-            }
-            h->ticket_group[h->ticket_ptr[c] + n] = (int32_t)hi;
-        }
-    }
     #undef WT
 
     /* Work units of the combine part.  A row block with many slots is cut into
@@ -419,19 +386,18 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     return h;
 }
 
-/* dims[0..17] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 U NM TE ticket_weight */
+/* dims[0..15] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 U NM */
 void oracle_hbp_dims(const oracle_hbp *h, int64_t *dims)
 {
-    int64_t v[18] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8,
-                      h->U, h->NM, h->TE, h->ticket_weight };
+    int64_t v[16] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8,
+                      h->U, h->NM };
     memcpy(dims, v, sizeof v);
 }
 
 /* which: 0 blk_bm 1 blk_bn 2 slot_ptr 3 blk_group_ptr 4 col_blk_ptr 5 stripe_ptr 6 stripe_blk
  *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign
  *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col
- *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 ticket_ptr 23 ticket_group
- *        24 group_rounds.
+ *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 group_rounds.
  * Copies the array into dst and returns its size in bytes (0 for an unknown id). */
 int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
 {
@@ -459,9 +425,7 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 19: src = h->unit_stripe; bytes = 4 * h->U; break;
     case 20: src = h->unit_k; bytes = 4 * (h->U + 1); break;
     case 21: src = h->multi_stripes; bytes = 4 * h->NM; break;
-    case 22: src = h->ticket_ptr; bytes = 4 * (h->NBC + 1); break;
-    case 23: src = h->ticket_group; bytes = 4 * h->TE; break;
-    case 24: src = h->group_rounds; bytes = 4 * (h->G + 1); break;
+    case 22: src = h->group_rounds; bytes = 4 * (h->G + 1); break;
     default: return 0;
     }
     if (dst && bytes) memcpy(dst, src, (size_t)bytes);

@@ -20,7 +20,7 @@ ARRAY_IDS = {
     "stripe_blk": 6, "group_ptr": 7, "group_slot": 8, "row_local": 9, "seg_len": 10, "col_local": 11,
     "data": 12, "add_sign": 13, "partial": 14, "col_group_ptr": 15, "comp_lo": 16,
     "fixed_start": 17, "fixed_col": 18, "unit_ptr": 19, "unit_stripe": 20, "unit_k": 21, "multi_stripes": 22,
-    "ticket_ptr": 23, "ticket_group": 24, "group_rounds": 25,
+    "group_rounds": 23,
 }
 ARRAY_DTYPES = {
     "blk_bm": "int32", "blk_bn": "int32", "slot_ptr": "int32", "blk_group_ptr": "int32", "col_blk_ptr": "int32",
@@ -29,7 +29,7 @@ ARRAY_DTYPES = {
     "partial": "float32", "col_group_ptr": "int32", "comp_lo": "int32",
     "fixed_start": "int32", "fixed_col": "int32",
     "unit_ptr": "int32", "unit_stripe": "int32", "unit_k": "int32", "multi_stripes": "int32",
-    "ticket_ptr": "int32", "ticket_group": "int32", "group_rounds": "int32",
+    "group_rounds": "int32",
 }
 # every symbol include/hbp.h declares
 EXPORTED_SYMBOLS = (
@@ -41,7 +41,7 @@ EXPORTED_SYMBOLS = (
 class hbp_params_t(ctypes.Structure):
     _fields_ = [("rows_per_block", ctypes.c_int32), ("cols_per_block", ctypes.c_int32), ("group_width", ctypes.c_int32),
                 ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("hash_shift", ctypes.c_int32),
-                ("tickets_per_worker", ctypes.c_int32), ("threads_per_worker", ctypes.c_int32),
+                ("claim_chunk", ctypes.c_int32), ("threads_per_worker", ctypes.c_int32),
                 ("rounds_per_batch", ctypes.c_int32), ("slot_weight", ctypes.c_int32),
                 ("combine_unit_slots", ctypes.c_int32), ("round_weight", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
@@ -52,12 +52,11 @@ class hbp_info_t(ctypes.Structure):
                 ("hash_shift", ctypes.c_int32), ("hash_b", ctypes.c_int32),
                 ("row_blocks", ctypes.c_int64), ("col_blocks", ctypes.c_int64),
                 ("blocks", ctypes.c_int64), ("slots", ctypes.c_int64), ("groups", ctypes.c_int64),
-                ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("tickets_per_worker", ctypes.c_int32),
+                ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("claim_chunk", ctypes.c_int32),
                 ("threads_per_worker", ctypes.c_int32), ("rounds_per_batch", ctypes.c_int32),
                 ("slot_weight", ctypes.c_int32), ("combine_unit_slots", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("round_weight", ctypes.c_int32),
-                ("combine_units", ctypes.c_int64), ("ticket_weight", ctypes.c_int64), ("ticket_entries", ctypes.c_int64),
-                ("split_row_blocks", ctypes.c_int64),
+                ("combine_units", ctypes.c_int64), ("split_row_blocks", ctypes.c_int64),
                 ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
                 ("build_ms", ctypes.c_double)]
 

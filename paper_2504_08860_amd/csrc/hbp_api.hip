@@ -43,7 +43,7 @@ int hbp_default_params(hbp_params_t *p)
     p->num_workers = 0;
     p->fixed_fraction_q8 = -1;
     p->hash_shift = -1;
-    p->tickets_per_worker = 0;
+    p->claim_chunk = 0;
     p->threads_per_worker = 0;
     p->rounds_per_batch = 0;
     p->slot_weight = 0;
@@ -71,7 +71,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.round_weight < 0) p.round_weight = 8;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.tickets_per_worker < 0 || p.tickets_per_worker > 64 || p.slot_weight < 1 || p.slot_weight > 64 ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 65536 || p.slot_weight < 1 || p.slot_weight > 64 ||
         (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
@@ -88,7 +88,9 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     h->R = p.rows_per_block; h->C = p.cols_per_block; h->W = p.group_width;
     h->NBR = (n_rows + h->R - 1) / h->R;
     h->NBC = (n_cols + h->C - 1) / h->C;
-    h->tickets_per_worker = p.tickets_per_worker ? p.tickets_per_worker : 8;
+    h->claim_chunk = p.claim_chunk;
+    if (h->claim_chunk == 0)  // two draws per wavefront; a draw is 8 / 4 / 1 groups for 2 / 4 / more rounds per batch
+        h->claim_chunk = p.rounds_per_batch == 2 ? 16 : p.rounds_per_batch == 4 ? 8 : 2;
     int rc = HBP_OK;
     if (h->NBR * h->NBC > hbp::kMaxDense) rc = HBP_ERR_TOO_LARGE;
     int32_t threads = 0, workers = 0;
@@ -207,8 +209,7 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->hash_b = h->R / 9 > 0 ? h->R / 9 : 1;
     info->row_blocks = h->NBR; info->col_blocks = h->NBC;
     info->blocks = h->B; info->slots = h->S; info->groups = h->G;
-    info->num_workers = h->P; info->fixed_fraction_q8 = h->fixed_q8; info->tickets_per_worker = h->tickets_per_worker;
-    info->ticket_weight = h->ticket_weight; info->ticket_entries = h->ticket_entries;
+    info->num_workers = h->P; info->fixed_fraction_q8 = h->fixed_q8; info->claim_chunk = h->claim_chunk;
     info->threads_per_worker = h->threads;
     info->rounds_per_batch = h->unroll;
     info->slot_weight = h->slot_weight;
@@ -259,8 +260,6 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_UNIT_STRIPE: src = h->unit_stripe; bytes = 4 * (size_t)h->U; break;
     case HBP_ARRAY_UNIT_K: src = h->unit_k; bytes = 4 * (size_t)(h->U + 1); break;
     case HBP_ARRAY_MULTI_STRIPES: src = h->multi_stripes; bytes = 4 * (size_t)h->NM; break;
-    case HBP_ARRAY_TICKET_PTR: src = h->ticket_ptr; bytes = 4 * (size_t)(h->NBC + 1); break;
-    case HBP_ARRAY_TICKET_GROUP: src = h->ticket_group; bytes = 4 * (size_t)h->ticket_entries; break;
     case HBP_ARRAY_GROUP_ROUNDS: src = h->group_rounds; bytes = 4 * (size_t)(h->G + 1); break;
     default: return HBP_ERR_INVALID_ARGUMENT;
     }

@@ -228,18 +228,6 @@ __global__ __launch_bounds__(256) void k_iota_units(int32_t *unit_ptr, int32_t *
     if (i < NBR) unit_stripe[i] = (int32_t)i;
 }
 
-__global__ __launch_bounds__(256) void k_iota_ptr(int32_t *p, int32_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i <= n) p[i] = (int32_t)i;
-}
-
-__global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int32_t v, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
 __global__ void k_set_i32(int32_t *p, int32_t v)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
@@ -666,44 +654,6 @@ __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__
     fixed_col[w] = c_lo;
 }
 
-// Competitive tickets: a ticket is worth Wq.  The competitive groups of column c, [comp_lo, end),
-// of weight cw, make ceil(cw / Wq) tickets; a column takes that many entries of ticket_group plus
-// one for its end.
-__global__ __launch_bounds__(256) void k_ticket_count(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ comp_lo,
-                                                      Weights wt, int32_t NBC, int64_t Wq, uint32_t *__restrict__ count)
-{
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= NBC) return;
-    const int64_t cw = wt.before(col_group_ptr[c + 1]) - wt.before(comp_lo[c]);
-    count[c] = (uint32_t)((cw + Wq - 1) / Wq + 1);
-}
-
-// Entry e belongs to the column c with ticket_ptr[c] <= e < ticket_ptr[c + 1]; it is ticket
-// t = e - ticket_ptr[c] of that column and starts at the first group whose preceding competitive
-// weight in the column reaches t Wq, or, for the last entry of the column, the column's end.
-__global__ __launch_bounds__(256) void k_ticket_fill(const int32_t *__restrict__ col_group_ptr, const int32_t *__restrict__ comp_lo,
-                                                     Weights wt, int32_t NBC, int64_t Wq, const int32_t *__restrict__ ticket_ptr,
-                                                     int64_t capacity, int32_t *__restrict__ ticket_group)
-{
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= ticket_ptr[NBC] || e >= capacity) return;
-    int32_t c_lo = 0, c_hi = NBC - 1;  // largest c with ticket_ptr[c] <= e
-    while (c_lo < c_hi) {
-        const int32_t mid = c_lo + ((c_hi - c_lo + 1) >> 1);
-        if (ticket_ptr[mid] <= e) c_lo = mid; else c_hi = mid - 1;
-    }
-    const int32_t c = c_lo, t = (int32_t)(e - ticket_ptr[c]);
-    const int32_t g0 = comp_lo[c], g1 = col_group_ptr[c + 1];
-    if (t == ticket_ptr[c + 1] - ticket_ptr[c] - 1) { ticket_group[e] = g1; return; }
-    const int64_t w0 = wt.before(g0), need = (int64_t)t * Wq;
-    int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with Wt(g) - w0 >= need
-    while (lo < hi) {
-        const int32_t mid = lo + ((hi - lo) >> 1);
-        if (wt.before(mid) - w0 >= need) hi = mid; else lo = mid + 1;
-    }
-    ticket_group[e] = lo;
-}
-
 // One device allocation carved into 256-byte aligned arrays: reserve() every array first,
 // commit() allocates once and hands out the pointers.  hipMalloc/hipFree calls are a large part
 // of the preprocessing time otherwise (each hipFree synchronises the device).
@@ -767,10 +717,6 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
     own0.reserve(&h->fixed_col, (int64_t)h->P);
     own0.reserve(&h->unit_ptr, NBR + 1);
-    own0.reserve(&h->ticket_ptr, NBC + 2);  // one spare entry: the counts are scanned in place
-    own0.reserve(&h->ticket_scan_tmp, NBC / kScanTile + 2);
-    // at most Wt(G) / ticket_weight + 2 NBC <= 2 P tickets_per_worker + 2 NBC entries
-    own0.reserve(&h->ticket_group, 2 * (int64_t)h->P * h->tickets_per_worker + 2 * NBC + 2);
     HBP_TRY(own0.commit());
     h->arena[0] = own0.base();
     HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
@@ -780,9 +726,6 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipMemsetAsync(h->col_group_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_start, 0, sizeof(int32_t) * (size_t)(h->P + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_col, 0, sizeof(int32_t) * (size_t)h->P, st));
-    k_iota_ptr<<<blocks_for(NBC + 1, 256), 256, 0, st>>>(h->ticket_ptr, (int32_t)NBC);  // no tickets yet
-    k_fill_i32<<<blocks_for(NBC, 256), 256, 0, st>>>(h->ticket_group, 0, NBC);
-    h->ticket_entries = NBC; h->ticket_weight = 1;
 
     if (nnz == 0) {  // empty matrix: no blocks; the combine part alone writes y = 0
         h->B = h->S = h->G = 0;
@@ -933,12 +876,11 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
                                              slot_j, (int32_t)G, C, h->col_local, h->data);
     HBP_HIP(hipGetLastError());
-    uint32_t n_units = 0, n_multi = 0, n_rounds = 0;
-    HBP_HIP(hipMemcpyAsync(&n_rounds, h->group_rounds + G, 4, hipMemcpyDeviceToHost, st));
+    uint32_t n_units = 0, n_multi = 0;
     HBP_HIP(hipMemcpyAsync(&n_units, h->unit_ptr + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&n_multi, multi_idx + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipStreamSynchronize(st));
-    h->U = n_units; h->NM = n_multi; h->total_rounds = n_rounds;
+    h->U = n_units; h->NM = n_multi;
     return HBP_OK;
 }
 
@@ -952,20 +894,6 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
         k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
         k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, (int32_t)h->G, h->P,
                                                                           h->fixed_start, h->fixed_col);
-        // ticket weight: the whole weight over P tickets_per_worker tickets (the sizes are on the host)
-        const int64_t total = h->nnz + (int64_t)h->slot_weight * h->S + (int64_t)h->round_weight * h->total_rounds;
-        const int64_t Wq = std::max<int64_t>(1, total / ((int64_t)h->P * h->tickets_per_worker));
-        const int64_t capacity = 2 * (int64_t)h->P * h->tickets_per_worker + 2 * h->NBC + 2;
-        h->ticket_weight = Wq;
-        k_ticket_count<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, h->comp_lo, wt, NBC, Wq, (uint32_t *)h->ticket_ptr);
-        HBP_TRY(exclusive_scan<kOpIdentity>((uint32_t *)h->ticket_ptr, (uint32_t *)h->ticket_ptr, h->NBC, 1, h->ticket_scan_tmp, st));
-        k_ticket_fill<<<blocks_for(capacity, 256), 256, 0, st>>>(h->col_group_ptr, h->comp_lo, wt, NBC, Wq, h->ticket_ptr, capacity,
-                                                                 h->ticket_group);
-        int32_t entries = 0;
-        HBP_HIP(hipMemcpyAsync(&entries, h->ticket_ptr + h->NBC, 4, hipMemcpyDeviceToHost, st));
-        HBP_HIP(hipStreamSynchronize(st));
-        if (entries < 0 || entries > capacity) return HBP_ERR_INTERNAL;
-        h->ticket_entries = entries;
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

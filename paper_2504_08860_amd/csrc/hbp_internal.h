@@ -23,9 +23,9 @@ struct Layout {
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot;
     const int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;  // schedule (Section 3.3)
-    const int32_t *ticket_ptr, *ticket_group;                          // competitive tickets (Section 3.3)
     const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
     int32_t NM;                                                        // row blocks with several units
+    int32_t claim;  // competitive groups a worker claims from a column's counter at a time
     const uint16_t *row_local, *seg_len, *col_local;
     const float *data;
 };
@@ -37,7 +37,7 @@ struct hbp_handle_s {
     int64_t n_rows, n_cols, nnz;
     int32_t R, C, W, a;
     int64_t NBR, NBC, B, S, G;
-    int32_t P, fixed_q8, slot_weight, tickets_per_worker, threads;
+    int32_t P, fixed_q8, slot_weight, claim_chunk, threads;
     int32_t unroll;      // rounds taken per batch by the SpMV-part kernel
     double build_ms;
     // device arrays (owned): views into two allocations, arena[0] sized before the matrix is
@@ -46,11 +46,7 @@ struct hbp_handle_s {
     int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     int32_t *group_ptr, *group_slot;
     int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;
-    int32_t *ticket_ptr, *ticket_group;  // competitive tickets of every block column
     int32_t *group_rounds;               // [G+1] prefix sums of the groups' longest rows
-    uint32_t *ticket_scan_tmp;
-    int64_t ticket_entries, ticket_weight;
-    int64_t total_rounds;                // group_rounds[G]
     int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;
     int64_t U, NM;       // combine work units, row blocks cut into several units
     int32_t unit_slots;  // target slots per combine unit
@@ -58,7 +54,7 @@ struct hbp_handle_s {
     uint16_t *row_local, *seg_len, *col_local;
     float *data;
     float *partial;      // [S] per-slot partial sums of the SpMV part
-    uint32_t *ticket;    // [NBC] competitive-part ticket counters, zero between calls
+    uint32_t *ticket;    // [NBC] competitive groups of every block column claimed so far, zero between calls
 };
 
 namespace hbp {

@@ -156,7 +156,10 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     uint64_t dbg_stage = 0, dbg_fixed_end = 0;
     extern __shared__ float xs[];  // the staged vector segment, C floats
     __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
-    __shared__ int32_t sh_grp;   // next group of the current range, drawn by the wavefronts
+    __shared__ unsigned long long sh_rng;  // groups of the worker still to draw: end << 32 | next
+    __shared__ int32_t sh_dry;   // nothing more to claim from the current block column
+    __shared__ int32_t sh_lock;  // end of the last range reported as used up
+    __shared__ int32_t sh_col[3];  // the current block column, its first competitive group, its end
     __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
@@ -206,10 +209,79 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     // behind the current pack's loads.  GP > 1 is for matrices whose groups hold few nonzeros:
     // the first batches of all GP groups are issued before any is consumed.  A group index at
     // or beyond g_end gives an idle lane set (n = 0, position 0).
-    auto draw_pack = [&]() __attribute__((always_inline)) {
-        int32_t v = 0;
-        if (lane == 0) v = atomicAdd(&sh_grp, GP);
-        return (int32_t)__builtin_amdgcn_readfirstlane(v);
+    //
+    // Draws.  sh_rng holds the worker's current range of groups; a draw takes GP groups off its
+    // front with one LDS atomic (draw_issue) whose result is looked at an iteration later
+    // (draw_resolve), so that its latency is never waited for.  A draw that finds the range
+    // used up, in a worker that competes for this block column (Section 3.3), leads to a claim:
+    // the first wavefront to report the range that ended at `end` as used up (atomic max on
+    // sh_lock; the ends of successive ranges grow) takes the column's next `claim` competitive
+    // groups from the column's counter in global memory and publishes them as the new range;
+    // the other wavefronts wait for the range to move (a bounded wait: a wavefront that gives
+    // up just stops drawing, the claimed groups are walked by those that go on).  So the
+    // wavefronts of a worker pass from fixed to competitive groups and from claim to claim
+    // without a barrier.  Once the column has nothing left (or in a worker that does not
+    // compete) a used-up range makes the draw, and every later draw of the wavefront in this
+    // range, return kNone.
+    constexpr int32_t kNone = 0x7fffffff;
+    constexpr int kSpinLimit = 1 << 16;
+    bool stop = false;  // this wavefront draws no more in the current range
+    // does group g + q of the pack (g, its end e) exist?
+    auto in_pack = [&](int32_t g, int32_t e, int q) __attribute__((always_inline)) {
+        return GP == 1 ? g != kNone : q < e - g;
+    };
+    auto draw_issue = [&]() __attribute__((always_inline)) {
+        unsigned long long old = 0;  // reads as a used-up range
+        if (lane == 0 && !stop) old = atomicAdd(&sh_rng, (unsigned long long)GP);
+        return old;
+    };
+    auto draw_resolve = [&](unsigned long long old, int32_t &pack_end) __attribute__((always_inline)) {
+        int32_t v = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)old);
+        int32_t end = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)(old >> 32));
+        int spins = 0;
+        while (v >= end) {
+            if (stop || __hip_atomic_load(&sh_dry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
+                stop = true;
+                pack_end = 0;
+                return kNone;
+            }
+            int32_t reported = 0;
+            if (lane == 0) reported = atomicMax(&sh_lock, end);
+            reported = __builtin_amdgcn_readfirstlane(reported);
+            if (reported < end) {
+                // first to report this range as used up: claim the column's next groups
+                // (the column's numbers sit in LDS: this path is rare, registers are not)
+                const int32_t claim = L.claim, col_end = sh_col[2];
+                uint32_t t = 0;
+                if (lane == 0) t = atomicAdd(&col_ticket[sh_col[0]], (uint32_t)claim);
+                t = __builtin_amdgcn_readfirstlane(t);
+                const int64_t c0 = (int64_t)sh_col[1] + t;
+                if (c0 >= col_end) {
+                    if (lane == 0) __hip_atomic_store(&sh_dry, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    continue;  // leaves through the test above
+                }
+                const unsigned long long c1 = (unsigned long long)min(c0 + claim, (int64_t)col_end);
+                if (lane == 0) atomicExch(&sh_rng, (c1 << 32) | (unsigned long long)c0);
+            } else {
+                // another wavefront claims: wait until the range's end moves or the column is dry
+                bool moved = false;
+                while (spins < kSpinLimit) {
+                    const unsigned long long now = __hip_atomic_load(&sh_rng, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    const int dry = __hip_atomic_load(&sh_dry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    spins++;
+                    if ((int32_t)(uint32_t)(now >> 32) != end || dry) { moved = true; break; }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                if (!moved) stop = true;  // gave up: leaves through the test above
+            }
+            if (stop) continue;
+            unsigned long long again = 0;
+            if (lane == 0) again = atomicAdd(&sh_rng, (unsigned long long)GP);
+            v = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)again);
+            end = __builtin_amdgcn_readfirstlane((int32_t)(uint32_t)(again >> 32));
+        }
+        pack_end = GP == 1 ? v + 1 : min(v + GP, end);
+        return v;
     };
     // Rounds k, k+1, ... of one group until no lane has a nonzero left (lane q has n; `base` is
     // the position of round k, `first` any valid position of the group), added into acc.
@@ -267,12 +339,22 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         }
     };
     // Runs the groups [g_begin, g_end) of block column bn with all wavefronts of the worker.
-    auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end) __attribute__((always_inline)) {
+    auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end, bool compete) __attribute__((always_inline)) {
         const uint64_t t_in = dbg ? wall_clock64() : 0;
         __syncthreads();  // every wavefront has left the previous range (and its slice of x)
-        if (threadIdx.x == 0) sh_grp = g_begin;
+        if (threadIdx.x == 0) {
+            sh_rng = ((unsigned long long)(uint32_t)g_end << 32) | (uint32_t)g_begin;
+            sh_dry = compete ? 0 : 1;
+            sh_lock = -1;
+            sh_col[0] = bn;
+            sh_col[1] = L.comp_lo[bn];
+            sh_col[2] = L.col_group_ptr[bn + 1];
+        }
+        stop = false;
         __syncthreads();
-        int32_t g = draw_pack(), g1 = draw_pack(), g2 = draw_pack();
+        int32_t e = 0, e1 = 0, e2 = 0;  // ends of the packs g, g1, g2: group g + q exists if it is below e
+        int32_t g = draw_resolve(draw_issue(), e), g1 = draw_resolve(draw_issue(), e1), g2 = kNone;
+        unsigned long long raw2 = draw_issue();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
         uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
         float done_acc[GP];
@@ -282,13 +364,13 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             base[q] = basen[q] = 0;
             done_slot[q] = -1;
             done_acc[q] = 0.f;
-            if (g + q < g_end) {
+            if (in_pack(g, e, q)) {
                 s0[q] = uniform_load(L.group_slot, g + q);
                 s1[q] = uniform_load(L.group_slot, g + q + 1);
                 base[q] = (uint32_t)uniform_load(L.group_ptr, g + q);
                 n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
             }
-            if (g1 + q < g_end) {
+            if (in_pack(g1, e1, q)) {
                 s0n[q] = uniform_load(L.group_slot, g1 + q);
                 s1n[q] = uniform_load(L.group_slot, g1 + q + 1);
                 basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
@@ -301,8 +383,10 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             staged_bn = bn;
         }
         if (dbg) dbg_stage += wall_clock64() - t_in;
-        while (g < g_end) {
-            const int32_t g3 = draw_pack();  // before the scalar loads: its wait would cover them too
+        for (;;) {
+            g2 = draw_resolve(raw2, e2);  // drawn an iteration ago
+            if (g == kNone && g1 == kNone && g2 == kNone) break;  // and this wavefront has stopped drawing
+            raw2 = draw_issue();
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
             uint32_t basenn[GP];
             float acc[GP];
@@ -310,7 +394,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             for (int q = 0; q < GP; q++) {
                 s0nn[q] = s1nn[q] = nn[q] = 0;
                 basenn[q] = 0;
-                if (g2 + q < g_end) {
+                if (in_pack(g2, e2, q)) {
                     s0nn[q] = uniform_load(L.group_slot, g2 + q);
                     s1nn[q] = uniform_load(L.group_slot, g2 + q + 1);
                     basenn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q);
@@ -374,7 +458,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
                 s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
             }
-            g = g1; g1 = g2; g2 = g3;
+            g = g1; g1 = g2;
+            e = e1; e1 = e2;
         }
 #pragma unroll
         for (int q = 0; q < GP; q++)
@@ -382,69 +467,83 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 
     };
 
-    // Fixed part (Section 3.3).  The group list is cut into P contiguous ranges of equal weight;
-    // worker w runs, column by column, the groups of its range that lie in the fixed part of
-    // their column (below comp_lo).
-    int32_t home = 0;
-    {
-        int32_t g = L.fixed_start[worker];
-        const int32_t g_end = L.fixed_start[worker + 1];
-        int32_t c = L.fixed_col[worker];
-        home = c;
-        while (g < g_end) {
-            const int32_t c_end = L.col_group_ptr[c + 1];
-            if (g >= c_end) { c++; continue; }  // columns without groups
-            const int32_t ge = min(g_end, c_end), fe = min(ge, L.comp_lo[c]);
-            if (g < fe) {
-                run_range(c, g, fe);
-            }
-            home = c;
-            g = ge;
-        }
-    }
-
-    // Competitive part.  Every block column has a ticket counter over its competitive groups,
-    // [comp_lo, end of column); a ticket is worth `chunk` groups per wavefront.  A worker keeps
-    // drawing from the column it is on (its segment is staged already); when that column runs
-    // dry it moves to the column with the most groups left, and stages that segment only once
-    // a ticket there has actually given it work.
-    if (dbg) dbg_fixed_end = wall_clock64();
-    int32_t bn = home;
-    while (L.competitive) {
-        if (threadIdx.x == 0) sh_next = (int32_t)min(atomicAdd(&col_ticket[bn], 1u), 0x7fffffffu);
-        __syncthreads();
-        const int32_t t = sh_next, t0 = L.ticket_ptr[bn], n_tickets = L.ticket_ptr[bn + 1] - t0 - 1;
-        __syncthreads();  // sh_next is rewritten below
-        if (t < n_tickets) {
-            const int32_t g0 = L.ticket_group[t0 + t], g1 = L.ticket_group[t0 + t + 1];
-            if (g0 < g1) run_range(bn, g0, g1);  // a ticket behind a group heavier than a ticket is empty
-            continue;
-        }
-        if (wave == 0) {  // this column is dry: look for the one with the most groups left
-            int32_t best = -1;
-            uint32_t best_left = 0;
-            for (int32_t c0 = 0; c0 < L.NBC; c0 += 64) {
-                int32_t c = c0 + lane;
-                uint32_t left = 0;
-                if (c < L.NBC) {
-                    const int64_t total = L.ticket_ptr[c + 1] - L.ticket_ptr[c] - 1;  // tickets weigh the same
-                    const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    left = used < total ? (uint32_t)(total - used) : 0u;
+    // The worker's ranges, one after the other (run_range is expanded once, here):
+    //   phase 0, fixed part (Section 3.3): the group list is cut into P contiguous ranges of
+    //     equal weight; worker w runs, column by column, the groups of its range that lie in
+    //     the fixed part of their column (below comp_lo).  In the last column of its range the
+    //     worker goes on, without a break, to claim that column's competitive groups (its
+    //     segment of x is staged already);
+    //   phase 1: a worker without fixed groups competes in the column its range starts in;
+    //   phase 2, competitive part: the counter of a block column holds how many of its
+    //     competitive groups, [comp_lo, end of column), have been claimed; a worker whose
+    //     column has run dry moves to the column with the most groups left (and stages that
+    //     segment of x), until no column has any.
+    const bool competitive = L.competitive != 0;
+    int32_t home = L.fixed_col[worker], col = home;
+    int32_t g_next = L.fixed_start[worker];
+    const int32_t g_stop = L.fixed_start[worker + 1];
+    bool competed_at_home = false;
+    for (int phase = 0;;) {
+        int32_t r_bn = 0, r_g0 = 0, r_g1 = 0;
+        bool r_compete = true;
+        if (phase == 0) {
+            bool found = false;
+            while (g_next < g_stop && !found) {
+                const int32_t c_end = L.col_group_ptr[col + 1];
+                if (g_next >= c_end) { col++; continue; }  // columns without groups
+                const int32_t ge = min(g_stop, c_end), fe = max(g_next, min(ge, L.comp_lo[col]));
+                const bool last = ge == g_stop;
+                home = col;
+                if (g_next < fe || (last && competitive)) {
+                    r_bn = col;
+                    // (an empty fixed part is handed over as [0, 0): the ends of a worker's
+                    // successive ranges must grow, and claimed ranges start at comp_lo)
+                    r_g0 = g_next < fe ? g_next : 0;
+                    r_g1 = g_next < fe ? fe : 0;
+                    r_compete = last && competitive;
+                    competed_at_home = r_compete;
+                    found = true;
                 }
+                g_next = ge;
+            }
+            if (!found) {
+                if (dbg) dbg_fixed_end = wall_clock64();
+                phase = 1;
+                continue;
+            }
+        } else if (phase == 1) {
+            phase = 2;
+            if (!competitive) break;
+            if (competed_at_home) continue;
+            r_bn = home;
+        } else {
+            if (wave == 0) {
+                int32_t best = -1;
+                uint32_t best_left = 0;
+                for (int32_t c0 = 0; c0 < L.NBC; c0 += 64) {
+                    int32_t c = c0 + lane;
+                    uint32_t left = 0;
+                    if (c < L.NBC) {
+                        const int64_t total = L.col_group_ptr[c + 1] - L.comp_lo[c];
+                        const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        left = used < total ? (uint32_t)(total - used) : 0u;
+                    }
 #pragma unroll
-                for (int d = 32; d > 0; d >>= 1) {
-                    const uint32_t o_left = __shfl_xor(left, d);
-                    const int32_t o_c = __shfl_xor(c, d);
-                    if (o_left > left || (o_left == left && o_c < c)) { left = o_left; c = o_c; }
+                    for (int d = 32; d > 0; d >>= 1) {
+                        const uint32_t o_left = __shfl_xor(left, d);
+                        const int32_t o_c = __shfl_xor(c, d);
+                        if (o_left > left || (o_left == left && o_c < c)) { left = o_left; c = o_c; }
+                    }
+                    if (left > best_left) { best_left = left; best = c; }
                 }
-                if (left > best_left) { best_left = left; best = c; }
+                if (lane == 0) sh_next = best;
             }
-            if (lane == 0) sh_next = best;
+            __syncthreads();
+            r_bn = sh_next;
+            __syncthreads();  // sh_next is rewritten in the next turn
+            if (r_bn < 0) break;
         }
-        __syncthreads();
-        bn = sh_next;
-        __syncthreads();
-        if (bn < 0) break;
+        run_range(r_bn, r_g0, r_g1, r_compete);
     }
     // Row blocks that the combine part cuts into several units are summed into y with atomic
     // adds: their rows of y start at zero.  (Done last: in front of the first range it delays
@@ -573,9 +672,9 @@ Layout hbp_view(const hbp_handle_s *h)
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
     L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
     L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
-    L.ticket_ptr = h->ticket_ptr; L.ticket_group = h->ticket_group;
     L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
     L.NM = (int32_t)h->NM;
+    L.claim = h->claim_chunk * (h->threads / kWave);
     return L;
 }
 

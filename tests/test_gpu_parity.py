@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-5
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
                  "group_ptr", "group_slot", "group_rounds", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col",
-                 "ticket_ptr", "ticket_group", "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
+                 "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
 
 
 @pytest.fixture(scope="module")
@@ -40,11 +40,10 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
                              W=info.group_width, hash_shift=params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
-                             round_weight=info.round_weight, tickets_per_worker=info.tickets_per_worker)
+                             round_weight=info.round_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a
         assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
-        assert (info.ticket_weight, info.ticket_entries) == (o.ticket_weight, o.TE)
         assert info.hash_b == max(1, info.rows_per_block // 9)
         for name in LAYOUT_ARRAYS:
             if name == "add_sign" and not check_add_sign:
@@ -102,13 +101,13 @@ def test_small_random(H, oracle, case):
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, group_width=W, hash_shift=shift)
 
 
-@pytest.mark.parametrize("P,q8,tpw,gw", [(1, 0, 1, 0), (3, 256, 1, 50), (7, 100, 5, 1024), (2000, 200, 2, 7), (5, 30, 64, 0)])
-def test_schedule_variants(H, oracle, P, q8, tpw, gw):
+@pytest.mark.parametrize("P,q8,chunk,gw", [(1, 0, 1, 0), (3, 256, 1, 50), (7, 100, 5, 1024), (2000, 200, 2, 7), (5, 30, 64, 0)])
+def test_schedule_variants(H, oracle, P, q8, chunk, gw):
     """y does not depend on how blocks are split into fixed and competitive parts."""
     m = random_csr(3000, 3000, 0.01, 21, empty_row_frac=0.1)
     info = check_against_oracle(H, oracle, m, rows_per_block=64, cols_per_block=128, num_workers=P,
-                                fixed_fraction_q8=q8, tickets_per_worker=tpw, round_weight=gw)
-    assert info.num_workers == P and info.tickets_per_worker == tpw
+                                fixed_fraction_q8=q8, claim_chunk=chunk, round_weight=gw)
+    assert info.num_workers == P and info.claim_chunk == chunk
 
 
 @pytest.mark.parametrize("number,scale,R,C", [(1, 1.0, 512, 4096), (2, 0.02, 512, 4096), (2, 0.02, 256, 32768),
@@ -218,9 +217,9 @@ def test_many_columns_competition(H, oracle):
     """More block columns than a wavefront has lanes (the scan for the fullest column loops), tiny
     tickets, more workers than groups."""
     m = random_csr(1500, 9000, 0.01, 31, empty_row_frac=0.2)
-    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=64, tickets_per_worker=64,
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=64, claim_chunk=1,
                          num_workers=300, threads_per_worker=256)
-    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=0, tickets_per_worker=3,
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=64, fixed_fraction_q8=0, claim_chunk=3,
                          num_workers=32, threads_per_worker=512, rounds_per_batch=4)
 
 

@@ -52,11 +52,9 @@ def test_worked_example_compact(oracle):
     assert y.tolist() == g["y"]
     assert partial.tolist() == g["compact"]["partial"]
     sch = g["schedule"]
-    h2 = build(oracle, m, R=g["R"], C=g["C"], W=g["W"], hash_shift=g["a"], num_workers=sch["P"], fixed_q8=sch["fixed_q8"],
-               tickets_per_worker=sch["tickets_per_worker"])
-    for name in ("col_group_ptr", "comp_lo", "fixed_start", "fixed_col", "ticket_ptr", "ticket_group"):
+    h2 = build(oracle, m, R=g["R"], C=g["C"], W=g["W"], hash_shift=g["a"], num_workers=sch["P"], fixed_q8=sch["fixed_q8"])
+    for name in ("col_group_ptr", "comp_lo", "fixed_start", "fixed_col"):
         assert h2.array(name).tolist() == sch[name], name
-    assert h2.ticket_weight == sch["ticket_weight"]
 
 
 # ---------------------------------------------------------------- brute force helpers
@@ -266,36 +264,6 @@ def test_group_rounds(oracle):
     assert gr[0] == 0 and len(gr) == h.G + 1
     for g in range(h.G):
         assert gr[g + 1] - gr[g] == seg_len[gs[g]:gs[g + 1]].max()
-
-
-def test_competitive_tickets(oracle):
-    """Section 3.3, competitive part: the tickets of a column tile [comp_lo, end of column) in
-    order, there are ceil(weight / ticket_weight) of them, each starts at the first group that
-    reaches its share (brute force over the prefix weights), and a ticket without its last group
-    weighs less than ticket_weight."""
-    m = random_csr(300, 500, 0.06, 5)
-    for P, q8, sw, gw, tpw in [(1, 0, 1, 0, 1), (3, 128, 4, 0, 8), (16, 200, 2, 5, 3), (50, 256, 1, 0, 8), (2, 64, 1, 0, 64)]:
-        h = build(oracle, m, R=16, C=32, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, round_weight=gw,
-                  tickets_per_worker=tpw)
-        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64) + gw * h.array("group_rounds").astype(np.int64)
-        assert h.ticket_weight == max(1, int(wt[-1]) // (P * tpw))
-        cgp, comp_lo, tp, tg = h.array("col_group_ptr"), h.array("comp_lo"), h.array("ticket_ptr"), h.array("ticket_group")
-        assert tp[0] == 0 and tp[-1] == len(tg) == h.TE
-        for c in range(h.NBC):
-            lo, hi = comp_lo[c], cgp[c + 1]
-            cw = int(wt[hi] - wt[lo])
-            n = tp[c + 1] - tp[c] - 1
-            assert n == -(-cw // h.ticket_weight)
-            t_g = tg[tp[c]:tp[c + 1]]
-            assert t_g[-1] == hi and (n == 0 or t_g[0] == lo) and np.all(np.diff(t_g) >= 0)
-            for t in range(n):
-                g = t_g[t]
-                assert wt[g] - wt[lo] >= t * h.ticket_weight
-                assert g == lo or wt[g - 1] - wt[lo] < t * h.ticket_weight
-                if t_g[t + 1] > g:
-                    assert wt[t_g[t + 1] - 1] - wt[g] < h.ticket_weight      # all but its last group fit
-        if q8 == 256:
-            assert h.TE == h.NBC            # nothing competitive: only the end markers
 
 
 def test_combine_units(oracle):
