@@ -14,7 +14,9 @@
  *   - oracle_hbp_build         2D partition (Section 3.1), per-(row, column block) segment
  *                              discovery (Algorithm 2), hash reorder, warp-group
  *                              column-major fill with add_sign (Section 3.2, last
- *                              paragraph), block schedule split (Section 3.3).
+ *                              paragraph), block schedule split (Section 3.3), work
+ *                              units of the combine part (Fig. 1: which partial sums
+ *                              one task of the combine adds up).
  *   - oracle_hbp_spmv          the two-step SpMV through the layout: per-block walk via
  *                              add_sign (Algorithm 3, with the do-while reading of its
  *                              loop) then the combine of partial sums (Fig. 1), fp64.
@@ -30,9 +32,10 @@
  *
  * Parity status: y, segments, permutation, fill, add_sign and schedule are pinned by
  * the tests under tests/ (definitions, brute force, round trip, closed forms, a
- * hand-worked 8x8 example).  The hash formula itself, the sampling quantile and the
- * fixed/competitive split ratio are NOT given by the paper: "parity unpinned" against
- * the authors' implementation; they are pinned only to this build's stated reading.
+ * hand-worked 8x8 example).  The hash formula itself, the sampling quantile, the
+ * fixed/competitive split (its ratio and the weights of a group) and the work units of
+ * the combine part are NOT given by the paper: "parity unpinned" against the authors'
+ * implementation; they are pinned only to this build's stated reading.
  */
 #include <stdint.h>
 #include <stdlib.h>
