@@ -394,37 +394,121 @@ __device__ __forceinline__ uint32_t aggregated_add(uint32_t *counters, int64_t k
     return result;
 }
 
+// Tiles for the two passes that touch a per-block counter for every segment.  A workgroup takes
+// kTileSegs consecutive segments.  They are in CSR order, so their rows ascend and the tile
+// touches the blocks of a few neighbouring row blocks only: (bm_hi - bm_lo + 1) * NBC counters.
+// When those fit in LDS the tile counts there (LDS integer atomics are two orders of magnitude
+// faster than scattered global ones) and goes to global memory once per counter it has
+// touched; otherwise every segment goes to global memory with wave-aggregated atomics.
+constexpr int kTileSegs = 2048;      // 256 threads x 8 segments
+constexpr int kTileCounters = 8192;  // 32 KB of LDS
+
+struct Tile {
+    int64_t base, S;
+    int32_t bm_lo, span;  // span = 0: the counters do not fit
+};
+
+__device__ __forceinline__ Tile tile_of(const int32_t *__restrict__ seg_row, int64_t S, int32_t R, int32_t NBC)
+{
+    Tile t;
+    t.S = S;
+    t.base = (int64_t)blockIdx.x * kTileSegs;
+    t.bm_lo = 0;
+    t.span = 0;
+    if (t.base < S) {
+        const int64_t last = min(t.base + kTileSegs, S) - 1;
+        t.bm_lo = seg_row[t.base] / R;
+        const int64_t span = (int64_t)(seg_row[last] / R - t.bm_lo + 1) * NBC;
+        t.span = span <= kTileCounters ? (int32_t)span : 0;
+    }
+    return t;
+}
+
 // Segments per block of the (column block, row block) table.
 // The segment count is still on the device (last entry of the scan) and the records of a
 // malformed matrix are incomplete, hence S_ptr and err.
 __global__ __launch_bounds__(256) void k_count_blocks(const int32_t *__restrict__ seg_row, const int32_t *__restrict__ seg_bn,
                                                       const uint32_t *__restrict__ S_ptr, const int32_t *__restrict__ err,
-                                                      int32_t R, int32_t NBR, uint32_t *__restrict__ dense_cnt)
+                                                      int32_t R, int32_t NBR, int32_t NBC, uint32_t *__restrict__ dense_cnt)
 {
+    __shared__ uint32_t cnt[kTileCounters];
     if (*err) return;
-    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool active = s < (int64_t)*S_ptr;
-    const int64_t d = active ? (int64_t)seg_bn[s] * NBR + seg_row[s] / R : 0;
-    aggregated_add(dense_cnt, d, active);
+    const Tile t = tile_of(seg_row, (int64_t)*S_ptr, R, NBC);
+    if (t.base >= t.S) return;
+    if (t.span == 0) {
+        for (int i = 0; i < kTileSegs / 256; i++) {
+            const int64_t s = t.base + i * 256 + threadIdx.x;
+            const bool active = s < t.S;
+            const int64_t d = active ? (int64_t)seg_bn[s] * NBR + seg_row[s] / R : 0;
+            aggregated_add(dense_cnt, d, active);
+        }
+        return;
+    }
+    for (int i = threadIdx.x; i < t.span; i += 256) cnt[i] = 0u;
+    __syncthreads();
+    for (int i = 0; i < kTileSegs / 256; i++) {
+        const int64_t s = t.base + i * 256 + threadIdx.x;
+        if (s < t.S) atomicAdd(&cnt[(seg_row[s] / R - t.bm_lo) * NBC + seg_bn[s]], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < t.span; i += 256) {
+        const uint32_t c = cnt[i];
+        if (c) atomicAdd(&dense_cnt[(int64_t)(i % NBC) * NBR + t.bm_lo + i / NBC], c);
+    }
 }
 
-// Bucketed scatter: (key << 16 | local row, segment id) into the block's slot range.
+// Bucketed scatter: (key << 16 | local row, segment id) into the block's slot range.  The order
+// in which the segments of a block arrive is arbitrary (k_order_block sorts them).
 __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_j, const int32_t *__restrict__ seg_row,
-                                                const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR,
+                                                const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR, int32_t NBC,
                                                 const int32_t *__restrict__ a_ptr, uint32_t *__restrict__ cursor,
                                                 uint32_t *__restrict__ bucket_key, uint32_t *__restrict__ bucket_seg)
 {
-    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool active = s < S;
-    const int32_t row = active ? seg_row[s] : 0;
-    const int64_t d = active ? (int64_t)seg_bn[s] * NBR + row / R : 0;
-    const uint32_t pos = aggregated_add(cursor, d, active);
-    if (!active) return;
-    const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-    const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u;
-    const uint32_t key = hash_key(n, (uint32_t)*a_ptr, b, R_u);
-    bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
-    bucket_seg[pos] = (uint32_t)s;
+    __shared__ uint32_t cnt[kTileCounters];  // per counter of the tile: segments seen, then their first position
+    const Tile t = tile_of(seg_row, S, R, NBC);
+    if (t.base >= t.S) return;
+    const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u, a = (uint32_t)*a_ptr;
+    auto emit = [&](int64_t s, int32_t row, uint32_t pos) {
+        const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
+        bucket_key[pos] = (hash_key(n, a, b, R_u) << 16) | (uint32_t)(row % R);
+        bucket_seg[pos] = (uint32_t)s;
+    };
+    if (t.span == 0) {
+        for (int i = 0; i < kTileSegs / 256; i++) {
+            const int64_t s = t.base + i * 256 + threadIdx.x;
+            const bool active = s < t.S;
+            const int32_t row = active ? seg_row[s] : 0;
+            const int64_t d = active ? (int64_t)seg_bn[s] * NBR + row / R : 0;
+            const uint32_t pos = aggregated_add(cursor, d, active);
+            if (active) emit(s, row, pos);
+        }
+        return;
+    }
+    for (int i = threadIdx.x; i < t.span; i += 256) cnt[i] = 0u;
+    __syncthreads();
+    int32_t row[kTileSegs / 256], local[kTileSegs / 256];
+    uint32_t rank[kTileSegs / 256];
+#pragma unroll
+    for (int i = 0; i < kTileSegs / 256; i++) {
+        const int64_t s = t.base + i * 256 + threadIdx.x;
+        row[i] = 0; local[i] = 0; rank[i] = 0;
+        if (s < t.S) {
+            row[i] = seg_row[s];
+            local[i] = (row[i] / R - t.bm_lo) * NBC + seg_bn[s];
+            rank[i] = atomicAdd(&cnt[local[i]], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < t.span; i += 256) {
+        const uint32_t c = cnt[i];
+        if (c) cnt[i] = atomicAdd(&cursor[(int64_t)(i % NBC) * NBR + t.bm_lo + i / NBC], c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kTileSegs / 256; i++) {
+        const int64_t s = t.base + i * 256 + threadIdx.x;
+        if (s < t.S) emit(s, row[i], cnt[local[i]] + rank[i]);
+    }
 }
 
 // One workgroup per non-empty block: order its slots by (key, local row) with a bitonic
@@ -794,7 +878,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_TRY(exclusive_scan<kOpIdentity>(seg_cnt, word_off, n_words, 1, scan_tmp, st));
     k_seg_emit<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_ptr, csr_col, seg_bits, word_off, word_row, nnz, n_cols, R, C,
                                                       (int32_t)NBR, n_words, seg_j, seg_row, seg_bn);
-    k_count_blocks<<<blocks_for(nnz, 256), 256, 0, st>>>(seg_row, seg_bn, word_off + n_words, d_err, R, (int32_t)NBR, dense_cnt);
+    k_count_blocks<<<blocks_for(nnz, kTileSegs), 256, 0, st>>>(seg_row, seg_bn, word_off + n_words, d_err, R, (int32_t)NBR, (int32_t)NBC,
+                                                               dense_cnt);
     // step 4: scans over the block table
     HBP_TRY(exclusive_scan<kOpIdentity>(dense_cnt, slot_off, D, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpCeilDivW>(dense_cnt, group_off, D, (uint32_t)W, scan_tmp, st));
@@ -860,8 +945,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_unit_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(h->stripe_ptr, stripe_cum, h->unit_ptr, multi_idx, (int32_t)NBR, (int32_t)B,
                                                      h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
-    k_bucket<<<blocks_for(S, 256), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, d_a, slot_off, bucket_key,
-                                                 bucket_seg);
+    k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a, slot_off,
+                                                       bucket_key, bucket_seg);
     int n2 = 2;
     while (n2 < R) n2 <<= 1;
     const size_t order_lds = sizeof(uint64_t) * (size_t)n2;
