@@ -176,10 +176,23 @@ __global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__
         if (j0 < 0 || j1 > nnz || j1 < j0) j1 = j0;  // malformed ptr is reported by the row-bit pass
         int64_t open = -1;                            // start of the segment whose end is not yet seen
         int bn_left = -1;                             // column block of the nonzero left of this chunk
-        for (int64_t base = j0; base < j1; base += 64) {
+        // eight chunks of 64 columns are fetched at a time: a row can have 10^5 nonzeros and
+        // one wavefront walks it
+        constexpr int kAhead = 8;
+        for (int64_t base0 = j0; base0 < j1; base0 += 64 * kAhead) {
+            int32_t cols[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; u++) {
+                const int64_t j = base0 + 64 * u + lane;
+                cols[u] = j < j1 ? col[j] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < kAhead; u++) {
+            const int64_t base = base0 + 64 * u;
+            if (base >= j1) break;
             const int64_t j = base + lane;
             const bool valid = j < j1;
-            const int bn = valid ? col[j] / C : -2;
+            const int bn = valid ? cols[u] / C : -2;
             int bn_prev = __shfl_up(bn, 1);
             if (lane == 0) bn_prev = bn_left;
             const bool start = valid && bn != bn_prev;
@@ -194,6 +207,7 @@ __global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__
                 open = base + (63 - __clzll((long long)mask));
             }
             bn_left = __shfl(bn, 63);
+            }
         }
         if (open >= 0 && lane == 0) tally((int)(j1 - open));
     }
@@ -582,15 +596,30 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
     const int n = lane < cnt ? seg_len[s0 + lane] : 0;
     const int64_t j = lane < cnt ? slot_j[s0 + lane] : 0;
     int64_t base = group_ptr[g];
-    for (int k = 0;; k++) {
-        const uint64_t live = __ballot(k < n);
-        if (!live) break;
-        if (k < n) {
-            const int64_t dst = base + lanes_below(live);
-            col_local[dst] = (uint16_t)(csr_col[j + k] - col0);
-            data[dst] = csr_val[j + k];
+    // eight rounds at a time: the sixteen loads are independent of each other and of the stores
+    constexpr int kRounds = 8;
+    for (int k = 0; __ballot(k < n); k += kRounds) {
+        int32_t c[kRounds];
+        float v[kRounds];
+#pragma unroll
+        for (int u = 0; u < kRounds; u++) {
+            c[u] = 0;
+            v[u] = 0.f;
+            if (k + u < n) {
+                c[u] = csr_col[j + k + u];
+                v[u] = csr_val[j + k + u];
+            }
         }
-        base += __popcll(live);
+#pragma unroll
+        for (int u = 0; u < kRounds; u++) {
+            const uint64_t live = __ballot(k + u < n);
+            if (k + u < n) {
+                const int64_t dst = base + lanes_below(live);
+                col_local[dst] = (uint16_t)(c[u] - col0);
+                data[dst] = v[u];
+            }
+            base += __popcll(live);
+        }
     }
 }
 
