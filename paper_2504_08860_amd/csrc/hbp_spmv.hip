@@ -40,40 +40,64 @@ template <int U>
 struct Batch {
     uint32_t c[U];
     float v[U];
+    int rounds;  // rounds of the batch in which some lane has a nonzero (they are the leading ones)
 };
 
-// Issues the loads of rounds k .. k+U-1 and advances base past them.  `first` is a position
-// that is always valid: lanes without an element in a round read it (and discard the
-// product), so no load is predicated.
+// Issues the loads of rounds k .. k+U-1 and advances base past them.  No load is predicated: a
+// lane without an element in a round reads a neighbour's (or the position just behind the
+// round: inside the group, or inside the padding behind the last group) and drops the product.
 template <int U>
 __device__ __forceinline__ void issue_batch(Batch<U> &b, const uint16_t *__restrict__ col_local,
-                                            const float *__restrict__ data, uint32_t &base, uint32_t first, int32_t n,
-                                            int32_t k)
+                                            const float *__restrict__ data, uint32_t &base, int32_t n, int32_t k)
 {
+    b.rounds = 0;
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const uint64_t live = __ballot(k + u < n);
         b.c[u] = 0;
         b.v[u] = 0.f;
         if (live) {  // wave-uniform: rounds past every row's end issue nothing
-            const uint32_t j = k + u < n ? base + (uint32_t)lanes_below(live) : first;
+            const uint32_t j = (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)live, base));
             b.c[u] = __builtin_nontemporal_load(col_local + j);
             b.v[u] = __builtin_nontemporal_load(data + j);
             base += (uint32_t)__popcll(live);
+            b.rounds = u + 1;
         }
     }
 }
 
-template <int U>
+// Products of the batch, summed per lane.  QUARTERS: the batch is taken in four quarters and a
+// quarter without a nonzero is skipped (deep batches behind a group's first one are mostly
+// empty when the rows are only a little longer than the first batch).
+template <int U, bool QUARTERS = false>
 __device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *xs, int32_t n, int32_t k)
 {
-    float xv[U], acc = 0.f;
+    float acc = 0.f;
+    if constexpr (QUARTERS) {
+        constexpr int Q = U / 4;
 #pragma unroll
-    for (int u = 0; u < U; u++) xv[u] = xs[b.c[u]];
+        for (int q0 = 0; q0 < U; q0 += Q) {
+            if (q0 < b.rounds) {  // wave-uniform
+                float xv[Q];
 #pragma unroll
-    for (int u = 0; u < U; u++) {
-        const float p = b.v[u] * xv[u];
-        acc += k + u < n ? p : 0.f;
+                for (int u = 0; u < Q; u++) xv[u] = xs[b.c[q0 + u]];
+#pragma unroll
+                for (int u = 0; u < Q; u++) {
+                    const float p = b.v[q0 + u] * xv[u];
+                    acc += k + q0 + u < n ? p : 0.f;
+                }
+            }
+        }
+    } else {
+        float xv[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) xv[u] = xs[b.c[u]];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const float p = b.v[u] * xv[u];
+            acc += k + u < n ? p : 0.f;
+        }
     }
     return acc;
 }
@@ -284,8 +308,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         return v;
     };
     // Rounds k, k+1, ... of one group until no lane has a nonzero left (lane q has n; `base` is
-    // the position of round k, `first` any valid position of the group), added into acc.
-    auto walk_rounds = [&](uint32_t &base, uint32_t first, int32_t n, int32_t k, float &acc) __attribute__((always_inline)) {
+    // the position of round k), added into acc.
+    auto walk_rounds = [&](uint32_t &base, int32_t n, int32_t k, float &acc) __attribute__((always_inline)) {
         for (;;) {
             const uint64_t live = __ballot(k < n);
             if (!live) break;
@@ -294,8 +318,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 // many rows still going, or one of them ends soon: a deep batch of rounds
                 constexpr int UL = 16;
                 Batch<UL> deep;
-                issue_batch<UL>(deep, L.col_local, L.data, base, first, n, k);
-                acc += consume_batch<UL>(deep, xs, n, k);
+                issue_batch<UL>(deep, L.col_local, L.data, base, n, k);
+                acc += consume_batch<UL, true>(deep, xs, n, k);
                 k += UL;
                 continue;
             }
@@ -432,12 +456,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             if (!wide) {
                 // general groups: round by round, U rounds per batch
                 Batch<U> bt[GP];
-                uint32_t first[GP];
 #pragma unroll
-                for (int q = 0; q < GP; q++) {
-                    first[q] = base[q];
-                    issue_batch<U>(bt[q], L.col_local, L.data, base[q], first[q], n[q], 0);
-                }
+                for (int q = 0; q < GP; q++) issue_batch<U>(bt[q], L.col_local, L.data, base[q], n[q], 0);
 #pragma unroll
                 for (int q = 0; q < GP; q++) {
                     if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
@@ -447,7 +467,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
 #pragma unroll
                 for (int q = 0; q < GP; q++) {  // rows longer than U, one group at a time
-                    walk_rounds(base[q], first[q], n[q], U, acc[q]);
+                    walk_rounds(base[q], n[q], U, acc[q]);
                     slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
                 }
             }
