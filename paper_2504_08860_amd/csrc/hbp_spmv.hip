@@ -14,6 +14,8 @@
 // block's blocks into an LDS copy of the y slice and writes it out, zeros included.
 #include "hbp_internal.h"
 
+#include <type_traits>
+
 namespace hbp {
 namespace {
 
@@ -589,7 +591,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 // but run an order of magnitude slower on this hardware.)  The copies are summed on the way out.
 // Also re-arms the per-column ticket counters for the next call (the SpMV part of this call
 // has finished: same stream).
-template <int THREADS>
+template <int THREADS, bool DEEP>
 __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__restrict__ partial, float *__restrict__ y,
                                                      uint32_t *__restrict__ ticket)
 {
@@ -621,22 +623,31 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
         __syncthreads();
         for (int32_t i = wave; i < nb; i += kWaves) {
             const int32_t s1 = range[2 * i + 1];
-            for (int32_t s = range[2 * i] + lane; s < s1; s += 256) {
-                uint32_t r[4];
-                float p[4], o[4];
+            // KU slots per lane in flight (the kernel is bound by the bytes it has in flight);
+            // the (up to) 64 KU slots of a step are distinct rows of one block: read all, then
+            // write all
+            auto add_block = [&](auto ku) __attribute__((always_inline)) {
+                constexpr int KU = decltype(ku)::value;
+                for (int32_t s = range[2 * i] + lane; s < s1; s += 64 * KU) {
+                    uint32_t r[KU];
+                    float p[KU], o[KU];
 #pragma unroll
-                for (int u = 0; u < 4; u++) {
-                    const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
-                    r[u] = L.row_local[idx];
-                    p[u] = partial[idx];
+                    for (int u = 0; u < KU; u++) {
+                        const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
+                        r[u] = L.row_local[idx];
+                        p[u] = partial[idx];
+                    }
+#pragma unroll
+                    for (int u = 0; u < KU; u++) o[u] = ys[r[u]];
+#pragma unroll
+                    for (int u = 0; u < KU; u++)
+                        if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
                 }
-                // the (up to) 256 slots are distinct rows of one block: read all, then write all
-#pragma unroll
-                for (int u = 0; u < 4; u++) o[u] = ys[r[u]];
-#pragma unroll
-                for (int u = 0; u < 4; u++)
-                    if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
-            }
+            };
+            const int32_t slots = s1 - range[2 * i];
+            if (DEEP && slots > 512) add_block(std::integral_constant<int, 16>{});
+            else if (DEEP && slots > 256) add_block(std::integral_constant<int, 8>{});
+            else add_block(std::integral_constant<int, 4>{});
         }
     }
     __syncthreads();
@@ -756,14 +767,14 @@ int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
     const Layout L = hbp_view(h);
     static int configured_device = -1;
     if (configured_device != h->device) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_combine<256>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        HBP_HIP(hipFuncSetAttribute((const void *)k_combine<256, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     4 * kMaxR * (int)sizeof(float)));
         configured_device = h->device;
     }
     if (h->R <= 1024)
-        k_combine<128><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<128, false><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     else
-        k_combine<256><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<256, true><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
