@@ -122,7 +122,9 @@ struct WideBatch {
     u32x2 c[CH];
 };
 
-template <int CH>
+// FIRST: the chunks start at the run's first chunk; only that one can hold elements in front of
+// the run, so the other chunks are tested against the run's end alone.
+template <int CH, bool FIRST = true>
 __device__ __forceinline__ void issue_wide(WideBatch<CH> &b, const uint16_t *__restrict__ col_local,
                                            const float *__restrict__ data, uint32_t chunk0, uint32_t i0, uint32_t run_begin,
                                            uint32_t run_end, int lane)
@@ -132,14 +134,14 @@ __device__ __forceinline__ void issue_wide(WideBatch<CH> &b, const uint16_t *__r
         const uint32_t p = chunk0 + 256u * (i0 + u) + 4u * (uint32_t)lane;
         b.v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
         b.c[u] = u32x2{0u, 0u};
-        if (p + 3u >= run_begin && p < run_end) {  // lanes whose four elements miss the run load nothing
+        if ((!(FIRST && u == 0) || p + 3u >= run_begin) && p < run_end) {  // lanes whose four elements miss the run load nothing
             b.v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(data + p));
             b.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(col_local + p));
         }
     }
 }
 
-template <int CH>
+template <int CH, bool FIRST = true>
 __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float *xs, uint32_t chunk0, uint32_t i0,
                                              uint32_t run_begin, uint32_t run_end, int lane, float (&acc)[4])
 {
@@ -153,7 +155,7 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float
         c[u][0] = lo & 0xffffu; c[u][1] = lo >> 16; c[u][2] = hi & 0xffffu; c[u][3] = hi >> 16;
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            ok[u][j] = p + j >= run_begin && p + j < run_end;
+            ok[u][j] = (!(FIRST && u == 0) || p + j >= run_begin) && p + j < run_end;
             c[u][j] = ok[u][j] ? c[u][j] : 0u;  // never index the segment with a foreign column
         }
     }
@@ -442,8 +444,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     nn[0] = s0n[0] + lane < s1n[0] ? L.seg_len[s0n[0] + lane] : 0;
                     consume_wide<CH>(wb, xs, chunk0, 0, base[0], run_end, lane, a4);
                     for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
-                        issue_wide<CH>(wb, L.col_local, L.data, chunk0, i0, base[0], run_end, lane);
-                        consume_wide<CH>(wb, xs, chunk0, i0, base[0], run_end, lane, a4);
+                        issue_wide<CH, false>(wb, L.col_local, L.data, chunk0, i0, base[0], run_end, lane);
+                        consume_wide<CH, false>(wb, xs, chunk0, i0, base[0], run_end, lane, a4);
                     }
 #pragma unroll
                     for (int j = 0; j < 4; j++) {
