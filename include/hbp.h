@@ -106,6 +106,9 @@ typedef struct {
                                   mean number of slots per row block, at least 16384                 */
     int32_t round_weight;      /* schedule weight of one round of a group (its rounds = the length of
                                   its longest row), in nonzeros: 0..1024; -1 = default 8             */
+    int32_t heavy_group_rounds;/* a group with a row of more nonzeros than this (inside the block) is walked
+                                  by all wavefronts of its worker together, each taking an equal share of
+                                  its nonzeros, instead of by one: >= 1; 0 = default 2048              */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
 } hbp_params_t;
 
@@ -123,7 +126,7 @@ typedef struct {
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
     int32_t combine_unit_slots;  /* slots per combine unit the row blocks were cut for          */
-    int32_t reserved;
+    int32_t heavy_group_rounds;  /* row length from which a group is shared by a worker's wavefronts */
     int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */

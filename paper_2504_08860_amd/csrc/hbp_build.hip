@@ -532,7 +532,8 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
                                                      const int32_t *__restrict__ blk_group_ptr, int32_t W,
                                                      uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
                                                      int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz, uint32_t *__restrict__ group_longest,
-                                                     int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk)
+                                                     int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk, uint32_t heavy_rounds,
+                                                     uint32_t *__restrict__ longest_all)
 {
     extern __shared__ uint64_t keys[];
     const int b = blockIdx.x;
@@ -573,6 +574,7 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
         }
         group_nnz[g0 + gi] = sum;
         group_longest[g0 + gi] = longest;
+        if (longest > heavy_rounds) atomicMax(longest_all, longest);  // only that long rows matter to the caller
         group_slot[g0 + gi] = s0 + gi * W;
         group_blk[g0 + gi] = b;
     }
@@ -953,11 +955,12 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     Arena tmp2(false);
     uint32_t *stripe_cum, *unit_cnt, *multi_idx;
     tmp2.reserve(&stripe_cum, B + 1); tmp2.reserve(&unit_cnt, NBR + 1); tmp2.reserve(&multi_idx, NBR + 1);
-    uint32_t *bucket_key, *bucket_seg, *group_nnz, *group_longest;
+    uint32_t *bucket_key, *bucket_seg, *group_nnz, *group_longest, *longest_all;
     int32_t *slot_j, *group_blk;
     tmp2.reserve(&bucket_key, S); tmp2.reserve(&bucket_seg, S);
-    tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_longest, G + 1); tmp2.reserve(&group_blk, G + 1);
+    tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_longest, G + 1); tmp2.reserve(&longest_all, 1); tmp2.reserve(&group_blk, G + 1);
     HBP_TRY(tmp2.commit());
+    HBP_HIP(hipMemsetAsync(longest_all, 0, sizeof(uint32_t), st));
 
     k_compact_blocks<<<blocks_for(std::max<int64_t>(D, NBC) + 1, 256), 256, 0, st>>>(
         dense_cnt, slot_off, group_off, blk_id, D, (int32_t)NBR, (int32_t)NBC, h->blk_bm, h->blk_bn, h->slot_ptr,
@@ -982,7 +985,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
                                                             h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
-                                                            group_blk);
+                                                            group_blk, (uint32_t)h->heavy_rounds, longest_all);
     HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
@@ -990,11 +993,13 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
                                              slot_j, (int32_t)G, C, h->col_local, h->data);
     HBP_HIP(hipGetLastError());
-    uint32_t n_units = 0, n_multi = 0;
+    uint32_t n_units = 0, n_multi = 0, longest = 0;
+    HBP_HIP(hipMemcpyAsync(&longest, longest_all, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&n_units, h->unit_ptr + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&n_multi, multi_idx + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipStreamSynchronize(st));
     h->U = n_units; h->NM = n_multi;
+    h->longest_segment = (int32_t)longest;  // 0 unless above heavy_rounds
     return HBP_OK;
 }
 

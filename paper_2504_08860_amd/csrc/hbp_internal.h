@@ -26,6 +26,7 @@ struct Layout {
     const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
     int32_t NM;                                                        // row blocks with several units
     int32_t claim;  // competitive groups a worker claims from a column's counter at a time
+    int32_t heavy_rounds;  // a group with a longer row is walked by all wavefronts of a worker together
     const uint16_t *row_local, *seg_len, *col_local;
     const float *data;
 };
@@ -50,6 +51,8 @@ struct hbp_handle_s {
     int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;
     int64_t U, NM;       // combine work units, row blocks cut into several units
     int32_t unit_slots;  // target slots per combine unit
+    int32_t heavy_rounds;  // groups with a longer row are shared by a worker's wavefronts
+    int32_t longest_segment;  // longest row segment of the matrix
     int32_t round_weight;  // schedule weight of a group on top of its nonzeros and slots
     uint16_t *row_local, *seg_len, *col_local;
     float *data;

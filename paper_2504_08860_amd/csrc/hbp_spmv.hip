@@ -174,7 +174,7 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float
     }
 }
 
-template <int THREADS, int U, int GP>
+template <int THREADS, int U, int GP, bool HEAVY>
 __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                                                        const float *__restrict__ x, float *__restrict__ partial,
                                                        float *__restrict__ y, uint32_t *__restrict__ col_ticket,
@@ -189,6 +189,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     __shared__ int32_t sh_lock;  // end of the last range reported as used up
     __shared__ int32_t sh_col[3];  // the current block column, its first competitive group, its end
     __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
+    constexpr int kHeavyCap = 64;
+    __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
+    __shared__ int32_t sh_heavy_n;
+    __shared__ int32_t sh_lens[THREADS];  // per wavefront: segment lengths of the heavy group being cut
+    __shared__ int32_t sh_cut_k[THREADS / 64 + 1];   // heavy group: first round of every wavefront's share
+    __shared__ uint32_t sh_cut_pos[THREADS / 64 + 1];  // and the nonzeros before that round
     constexpr int kWaves = THREADS / 64;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -374,6 +380,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             sh_rng = ((unsigned long long)(uint32_t)g_end << 32) | (uint32_t)g_begin;
             sh_dry = compete ? 0 : 1;
             sh_lock = -1;
+            sh_heavy_n = 0;
             sh_col[0] = bn;
             sh_col[1] = L.comp_lo[bn];
             sh_col[2] = L.col_group_ptr[bn + 1];
@@ -415,6 +422,22 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             g2 = draw_resolve(raw2, e2);  // drawn an iteration ago
             if (g == kNone && g1 == kNone && g2 == kNone) break;  // and this wavefront has stopped drawing
             raw2 = draw_issue();
+            // A group with a row of more than heavy_rounds nonzeros would keep this wavefront busy
+            // long after the rest of the worker has run dry: it goes on the worker's list and
+            // looks empty here (unless the list is full: then this wavefront walks it alone).
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                if (HEAVY && __ballot(n[q] > L.heavy_rounds)) {
+                    int32_t idx = 0;
+                    if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
+                    idx = __builtin_amdgcn_readfirstlane(idx);
+                    if (idx < kHeavyCap) {
+                        if (lane == 0) sh_heavy[idx] = g + q;
+                        n[q] = 0;
+                        s1[q] = s0[q];
+                    }
+                }
+            }
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
             uint32_t basenn[GP];
             float acc[GP];
@@ -489,6 +512,66 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         for (int q = 0; q < GP; q++)
             if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
 
+        // Heavy groups of this range: all wavefronts of the worker walk each of them together.
+        // Wavefront w takes the rounds [k_w, k_{w+1}), where k_w is the first round that has
+        // w / kWaves of the group's nonzeros before it, and the per-lane sums of the wavefronts
+        // are added in LDS in wavefront order.
+        if constexpr (!HEAVY) return;
+        __syncthreads();
+        const int32_t n_heavy = min(sh_heavy_n, kHeavyCap);
+        for (int32_t i = 0; i < n_heavy; i++) {
+            const int32_t gh = sh_heavy[i];
+            const int32_t hs0 = uniform_load(L.group_slot, gh), hs1 = uniform_load(L.group_slot, gh + 1);
+            const uint32_t b0 = (uint32_t)uniform_load(L.group_ptr, gh);
+            const uint32_t total = (uint32_t)uniform_load(L.group_ptr, gh + 1) - b0;
+            const int32_t len = hs0 + lane < hs1 ? (int32_t)L.seg_len[hs0 + lane] : 0;
+            int32_t *lens = sh_lens + wave * 64;
+            lens[lane] = len;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // nonzeros of the group in rounds 0 .. k-1; every lane may ask for another k
+            auto before = [&](int32_t k) __attribute__((always_inline)) {
+                uint32_t sum = 0;
+#pragma unroll 16
+                for (int t = 0; t < 64; t++) sum += (uint32_t)min(lens[t], k);
+                return sum;
+            };
+            // smallest k with before(k) >= target, by three 64-way splits of (0, 65536]: a segment
+            // has fewer than 65536 nonzeros, so before(65536) = total >= target
+            const uint32_t target = (uint32_t)(((uint64_t)total * (uint32_t)wave) / (uint32_t)kWaves);
+            int32_t cut_k = 0;
+            uint32_t cut_pos = 0;
+            if (target > 0) {
+                int32_t lo = 0;
+                auto split = [&](int32_t step) __attribute__((always_inline)) {
+                    // candidates lo + step, lo + 2 step, ...: the last one is known to reach the target
+                    const uint32_t got = before(lo + (lane + 1) * step);
+                    const int first = __builtin_ctzll(__ballot(got >= target));
+                    lo += first * step;
+                    return (uint32_t)__shfl(got, first);
+                };
+                split(1024);
+                split(16);
+                cut_pos = split(1);
+                cut_k = lo + 1;
+            }
+            if (lane == 0) { sh_cut_k[wave] = cut_k; sh_cut_pos[wave] = cut_pos; }
+            if (threadIdx.x == 0) sh_cut_k[kWaves] = 0x10000;
+            __syncthreads();
+            const int32_t k_lo = sh_cut_k[wave], k_hi = sh_cut_k[wave + 1];
+            uint32_t pos = b0 + sh_cut_pos[wave];
+            float sum = 0.f;
+            walk_rounds(pos, min(len, k_hi), k_lo, sum);
+            sh_hand[threadIdx.x] = sum;
+            __syncthreads();
+            if (wave == 0 && hs0 + lane < hs1) {
+                float total_sum = sh_hand[lane];
+#pragma unroll
+                for (int w = 1; w < kWaves; w++) total_sum += sh_hand[w * 64 + lane];
+                partial[hs0 + lane] = total_sum;
+            }
+            __syncthreads();  // sh_hand and the cuts are reused by the next heavy group
+        }
     };
 
     // The worker's ranges, one after the other (run_range is expanded once, here):
@@ -708,6 +791,7 @@ Layout hbp_view(const hbp_handle_s *h)
     L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
     L.NM = (int32_t)h->NM;
     L.claim = h->claim_chunk * (h->threads / kWave);
+    L.heavy_rounds = h->heavy_rounds;
     return L;
 }
 
@@ -729,39 +813,45 @@ int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *thre
     return HBP_OK;
 }
 
-template <int THREADS, int U, int GP>
+template <int THREADS, int U, int GP, bool HEAVY>
 static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     const size_t lds = (size_t)h->C * sizeof(float);
     static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
     if (configured_device != h->device) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U, GP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U, GP, HEAVY>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     kMaxC * (int)sizeof(float)));
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U, GP><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, h->partial, y, h->ticket, dbg);
+    k_spmv_part<THREADS, U, GP, HEAVY><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, h->partial, y, h->ticket, dbg);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
-template <int THREADS>
+template <int THREADS, bool HEAVY>
 static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
-    case 2: return launch_part<THREADS, 2, 8>(h, L, x, y, st, dbg);
-    case 4: return launch_part<THREADS, 4, 4>(h, L, x, y, st, dbg);
-    case 9: return launch_part<THREADS, 9, 1>(h, L, x, y, st, dbg);
-    case 16: return launch_part<THREADS, 16, 1>(h, L, x, y, st, dbg);
-    default: return launch_part<THREADS, 8, 1>(h, L, x, y, st, dbg);
+    case 2: return launch_part<THREADS, 2, 8, HEAVY>(h, L, x, y, st, dbg);
+    case 4: return launch_part<THREADS, 4, 4, HEAVY>(h, L, x, y, st, dbg);
+    case 9: return launch_part<THREADS, 9, 1, HEAVY>(h, L, x, y, st, dbg);
+    case 16: return launch_part<THREADS, 16, 1, HEAVY>(h, L, x, y, st, dbg);
+    default: return launch_part<THREADS, 8, 1, HEAVY>(h, L, x, y, st, dbg);
     }
 }
 
 int launch_spmv_part(const hbp_handle_s *h, const float *x, float *y, hipStream_t st, uint64_t *dbg)
 {
     const Layout L = hbp_view(h);
-    if (h->threads == 1024) return launch_part_u<1024>(h, L, x, y, st, dbg);
-    if (h->threads == 512) return launch_part_u<512>(h, L, x, y, st, dbg);
-    return launch_part_u<256>(h, L, x, y, st, dbg);
+    // the kernel that can share heavy groups among a worker's wavefronts only where the matrix has one
+    if (h->longest_segment > h->heavy_rounds) {
+        if (h->threads == 1024) return launch_part_u<1024, true>(h, L, x, y, st, dbg);
+        if (h->threads == 512) return launch_part_u<512, true>(h, L, x, y, st, dbg);
+        return launch_part_u<256, true>(h, L, x, y, st, dbg);
+    }
+    if (h->threads == 1024) return launch_part_u<1024, false>(h, L, x, y, st, dbg);
+    if (h->threads == 512) return launch_part_u<512, false>(h, L, x, y, st, dbg);
+    return launch_part_u<256, false>(h, L, x, y, st, dbg);
 }
 
 int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)

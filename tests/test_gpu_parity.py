@@ -233,3 +233,17 @@ def test_split_row_blocks(H, oracle, unit_slots):
         info = check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=512, combine_unit_slots=unit_slots)
         if unit_slots == 64:
             assert info.split_row_blocks > 0
+
+
+@pytest.mark.parametrize("heavy", [1, 5, 60, 700])
+@pytest.mark.parametrize("rounds,threads", [(2, 256), (4, 512), (8, 1024), (9, 1024), (16, 512)])
+def test_heavy_groups_shared_by_a_worker(H, oracle, heavy, rounds, threads):
+    """Groups with a row longer than heavy_group_rounds are walked by all wavefronts of a worker,
+    each taking an equal share of the group's nonzeros.  heavy = 1 makes nearly every group heavy
+    (the worker's list overflows and the rest is walked the ordinary way); the larger values
+    leave a mix; with and without a competitive part."""
+    m = _mixed_matrix(seed=7)
+    for q8, workers in ((256, 3), (128, 6)):
+        check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=2048, cols_per_block=8192,
+                             rounds_per_batch=rounds, threads_per_worker=threads, fixed_fraction_q8=q8,
+                             num_workers=workers, heavy_group_rounds=heavy)
