@@ -51,7 +51,8 @@ def main() -> int:
     ap.add_argument("--claim-chunk", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--rounds", type=int, default=0)
-    ap.add_argument("--slot-weight", type=int, default=0)
+    ap.add_argument("--slot-weight", type=int, default=-1)
+    ap.add_argument("--group-weight", type=int, default=-1)
     ap.add_argument("--combine-unit-slots", type=int, default=0)
     ap.add_argument("--hash-shift", type=int, default=-1)
     ap.add_argument("--round-weight", type=int, default=-1)
@@ -86,7 +87,8 @@ def main() -> int:
     if args.claim_chunk: params["claim_chunk"] = args.claim_chunk
     if args.threads: params["threads_per_worker"] = args.threads
     if args.rounds: params["rounds_per_batch"] = args.rounds
-    if args.slot_weight: params["slot_weight"] = args.slot_weight
+    if args.slot_weight >= 0: params["slot_weight"] = args.slot_weight
+    if args.group_weight >= 0: params["group_weight"] = args.group_weight
     if args.combine_unit_slots: params["combine_unit_slots"] = args.combine_unit_slots
     if args.hash_shift >= 0: params["hash_shift"] = args.hash_shift
     if args.round_weight >= 0: params["round_weight"] = args.round_weight
@@ -153,7 +155,7 @@ def main() -> int:
                    "group_width": info.group_width, "hash_shift": info.hash_shift, "blocks": info.blocks,
                    "slots": info.slots, "groups": info.groups, "workers": info.num_workers,
                    "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
-                   "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight,
+                   "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight, "group_weight": info.group_weight,
                    "combine_unit_slots": info.combine_unit_slots, "combine_units": info.combine_units,
                    "round_weight": info.round_weight, "heavy_group_rounds": info.heavy_group_rounds},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,

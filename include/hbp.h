@@ -34,7 +34,7 @@
  *     group_rounds        [G+1]    rounds of all groups before (prefix sums of the longest row)
  *   Schedule (Section 3.3; the unit handed to a wavefront is a group, whose weight is its
  *   nonzeros plus slot_weight times its slots plus round_weight times its rounds, the
- *   length of its longest row):
+ *   length of its longest row, plus group_weight):
  *     col_group_ptr       [NBC+1]  first group of each block column
  *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
  *                                  the leading fixed_fraction of its weight as fixed part
@@ -100,7 +100,8 @@ typedef struct {
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
-    int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 1..64; 0 = default     */
+    int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 0..64; -1 = default 4  */
+    int32_t group_weight;      /* schedule weight of a group as such, in nonzeros: 0..4096; -1 = default 0 */
     int32_t combine_unit_slots;/* slots one workgroup of the combine part should get at most: a row block
                                   with more is cut into several units; >= 64; 0 = default: twice the
                                   mean number of slots per row block, at least 16384                 */
@@ -125,13 +126,14 @@ typedef struct {
     int32_t threads_per_worker;  /* workgroup size of the SpMV-part kernel                      */
     int32_t rounds_per_batch;    /* rounds loaded per batch by the SpMV-part kernel             */
     int32_t slot_weight;         /* schedule weight of a slot, in nonzeros                      */
+    int32_t group_weight;        /* schedule weight of a group as such, in nonzeros             */
     int32_t combine_unit_slots;  /* slots per combine unit the row blocks were cut for          */
     int32_t heavy_group_rounds;  /* row length from which a group is shared by a worker's wavefronts */
     int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
-    int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves (see DESIGN)   */
+    int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves                 */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
     double build_ms;             /* wall time of hbp_build, allocation and synchronisation included */
 } hbp_info_t;

@@ -188,9 +188,9 @@ void oracle_hbp_free(oracle_hbp *h)
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
-                             int32_t slot_weight, int32_t round_weight, int32_t unit_slots)
+                             int32_t slot_weight, int32_t round_weight, int32_t group_weight, int32_t unit_slots)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 1 || round_weight < 0 || unit_slots < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || unit_slots < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -303,7 +303,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     }
 
     /* Section 3.3, mixed execution allocation.  The unit handed to a wavefront is a group; the
-     * weight of a group is its nonzeros plus slot_weight times its slots plus round_weight times
+     * weight of a group is group_weight plus its nonzeros plus slot_weight times its slots plus round_weight times
      * its rounds (the length of its longest row: the steps a wavefront takes through it), so
      * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] + round_weight * group_rounds[g] is the
      * weight of all groups before g.
@@ -326,7 +326,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
-    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g] + (int64_t)round_weight * (int64_t)h->group_rounds[g])
+    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g] + (int64_t)round_weight * (int64_t)h->group_rounds[g] + (int64_t)group_weight * (int64_t)(g))
     for (int64_t c = 0; c < NBC; c++) {
         int64_t g0 = h->col_group_ptr[c], g1 = h->col_group_ptr[c + 1], g = g0;
         while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;

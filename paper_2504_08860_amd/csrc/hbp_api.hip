@@ -46,7 +46,8 @@ int hbp_default_params(hbp_params_t *p)
     p->claim_chunk = 0;
     p->threads_per_worker = 0;
     p->rounds_per_batch = 0;
-    p->slot_weight = 0;
+    p->slot_weight = -1;
+    p->group_weight = -1;
     p->combine_unit_slots = 0;
     p->round_weight = -1;
     p->heavy_group_rounds = 0;
@@ -68,12 +69,13 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.cols_per_block == 0) p.cols_per_block = 4096;
     if (p.group_width == 0) p.group_width = 64;
     if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
-    if (p.slot_weight == 0) p.slot_weight = 4;
+    if (p.slot_weight < 0) p.slot_weight = 4;
+    if (p.group_weight < 0) p.group_weight = 0;
     if (p.round_weight < 0) p.round_weight = 8;
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 65536 || p.slot_weight < 1 || p.slot_weight > 64 ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 65536 || p.slot_weight > 64 || p.group_weight > 4096 ||
         (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 || p.heavy_group_rounds < 1 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
@@ -102,6 +104,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
         h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
         h->fixed_q8 = p.fixed_fraction_q8;
         h->slot_weight = p.slot_weight;
+        h->group_weight = p.group_weight;
         h->unit_slots = p.combine_unit_slots;
         h->round_weight = p.round_weight;
         h->heavy_rounds = p.heavy_group_rounds;
@@ -216,6 +219,7 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->threads_per_worker = h->threads;
     info->rounds_per_batch = h->unroll;
     info->slot_weight = h->slot_weight;
+    info->group_weight = h->group_weight;
     info->combine_unit_slots = h->unit_slots;
     info->round_weight = h->round_weight;
     info->heavy_group_rounds = h->heavy_rounds;

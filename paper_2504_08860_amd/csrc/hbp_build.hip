@@ -707,17 +707,18 @@ __global__ __launch_bounds__(256) void k_unit_fill(const int32_t *__restrict__ s
 
 // ------------------------------------------------------------------ Section 3.3: schedule
 //
-// Weight of a group = its nonzeros + SW times its slots + RW times its rounds (SW = slot_weight,
-// RW = round_weight: the costs of a row and of a round of a group measured in nonzeros; a group
-// has as many rounds as its longest row has nonzeros);
-// Wt(g) = group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g] is the weight of all groups
-// before g.
+// Weight of a group = GW + its nonzeros + SW times its slots + RW times its rounds (GW =
+// group_weight, SW = slot_weight, RW = round_weight: the costs of a group as such, of a row and
+// of a round of a group, measured in nonzeros; a group has as many rounds as its longest row
+// has nonzeros);
+// Wt(g) = group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g] + GW * g is the weight of all
+// groups before g.
 struct Weights {
     const int32_t *group_ptr, *group_slot, *group_rounds;
-    int64_t SW, RW;
+    int64_t SW, RW, GW;
     __device__ __forceinline__ int64_t before(int32_t g) const
     {
-        return (int64_t)group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g];
+        return (int64_t)group_ptr[g] + SW * group_slot[g] + RW * group_rounds[g] + GW * g;
     }
 };
 
@@ -1009,7 +1010,8 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
     if (h->G > 0) {
         const int32_t NBC = (int32_t)h->NBC;
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
-        const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight};
+        const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight,
+                         (int64_t)h->group_weight};
         k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
         k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, (int32_t)h->G, h->P,
                                                                           h->fixed_start, h->fixed_col);

@@ -52,6 +52,7 @@ struct hbp_handle_s {
     int64_t U, NM;       // combine work units, row blocks cut into several units
     int32_t unit_slots;  // target slots per combine unit
     int32_t heavy_rounds;  // groups with a longer row are shared by a worker's wavefronts
+    int32_t group_weight;  // schedule weight of a group as such
     int32_t longest_segment;  // longest row segment of the matrix
     int32_t round_weight;  // schedule weight of a group on top of its nonzeros and slots
     uint16_t *row_local, *seg_len, *col_local;

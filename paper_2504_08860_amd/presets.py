@@ -7,7 +7,9 @@ PRESETS = {
     1: dict(rows_per_block=512, cols_per_block=4096, fixed_fraction_q8=256),
     2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4),
     3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
-    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=192, round_weight=12),
+    # weights from a least-squares fit of the workers' times: a range costs per group and per round, not per nonzero
+    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=224, slot_weight=0,
+            group_weight=100, round_weight=35),
     5: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
 }
 

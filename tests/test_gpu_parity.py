@@ -40,7 +40,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
                              W=info.group_width, hash_shift=params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
-                             round_weight=info.round_weight)
+                             round_weight=info.round_weight, group_weight=info.group_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a
         assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
@@ -101,12 +101,14 @@ def test_small_random(H, oracle, case):
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, group_width=W, hash_shift=shift)
 
 
-@pytest.mark.parametrize("P,q8,chunk,gw", [(1, 0, 1, 0), (3, 256, 1, 50), (7, 100, 5, 1024), (2000, 200, 2, 7), (5, 30, 64, 0)])
-def test_schedule_variants(H, oracle, P, q8, chunk, gw):
+@pytest.mark.parametrize("P,q8,chunk,gw,cw", [(1, 0, 1, 0, 0), (3, 256, 1, 50, 400), (7, 100, 5, 1024, 4096), (2000, 200, 2, 7, 0),
+                                               (5, 30, 64, 0, 33)])
+def test_schedule_variants(H, oracle, P, q8, chunk, gw, cw):
     """y does not depend on how blocks are split into fixed and competitive parts."""
     m = random_csr(3000, 3000, 0.01, 21, empty_row_frac=0.1)
     info = check_against_oracle(H, oracle, m, rows_per_block=64, cols_per_block=128, num_workers=P,
-                                fixed_fraction_q8=q8, claim_chunk=chunk, round_weight=gw)
+                                fixed_fraction_q8=q8, claim_chunk=chunk, round_weight=gw, group_weight=cw,
+                                slot_weight=0 if cw == 33 else -1)
     assert info.num_workers == P and info.claim_chunk == chunk
 
 

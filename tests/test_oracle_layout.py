@@ -225,10 +225,11 @@ def test_schedule_split(oracle):
     every group exactly once; ranges have equal weight up to one group; every column keeps the
     stated share of its weight fixed, up to one group."""
     m = random_csr(300, 300, 0.05, 3)
-    for P, q8, sw, gw in [(1, 128, 1, 0), (4, 192, 4, 0), (7, 255, 1, 9), (64, 256, 6, 100), (5, 0, 2, 1), (1000, 100, 1, 0)]:
-        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, round_weight=gw)
+    for P, q8, sw, gw, cw in [(1, 128, 1, 0, 0), (4, 192, 4, 0, 7), (7, 255, 1, 9, 0), (64, 256, 6, 100, 300), (5, 0, 0, 1, 50),
+                              (1000, 100, 1, 0, 0)]:
+        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, round_weight=gw, group_weight=cw)
         assert h.P == P and h.fixed_q8 == q8
-        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64) + gw * h.array("group_rounds").astype(np.int64)
+        wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64) + gw * h.array("group_rounds").astype(np.int64) + cw * np.arange(h.G + 1)
         cgp, comp_lo = h.array("col_group_ptr"), h.array("comp_lo")
         fs, fc = h.array("fixed_start"), h.array("fixed_col")
         assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
