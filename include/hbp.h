@@ -96,7 +96,7 @@ typedef struct {
     int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
     int32_t claim_chunk;       /* competitive part: groups per wavefront that a worker claims from a
-                                  block column at a time, 1..65536; 0 = default (two draws per wavefront) */
+                                  block column at a time, 1..1024; 0 = default (two draws per wavefront) */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once); 0 = default                 */

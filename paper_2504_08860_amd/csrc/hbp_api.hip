@@ -75,7 +75,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
     if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
-        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 65536 || p.slot_weight > 64 || p.group_weight > 4096 ||
+        p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 1024 || p.slot_weight > 64 || p.group_weight > 4096 ||
         (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 || p.heavy_group_rounds < 1 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||

@@ -249,3 +249,51 @@ def test_heavy_groups_shared_by_a_worker(H, oracle, heavy, rounds, threads):
         check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=2048, cols_per_block=8192,
                              rounds_per_batch=rounds, threads_per_worker=threads, fixed_fraction_q8=q8,
                              num_workers=workers, heavy_group_rounds=heavy)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_parameters(H, oracle, seed):
+    """Seeded random draws over matrix shape and every build parameter (block sizes, group
+    width, workers, fixed share, claim size, weights, kernel variant, combine units, heavy
+    threshold): layout bit-exact, y and partial sums within tolerance, twice in a row."""
+    rng = np.random.default_rng(1000 + seed)
+    n_rows = int(rng.integers(1, 6000))
+    n_cols = int(rng.integers(1, 9000))
+    density = float(rng.choice([0.002, 0.01, 0.05, 0.2]))
+    m = random_csr(n_rows, n_cols, density, 500 + seed, empty_row_frac=float(rng.choice([0.0, 0.3])))
+    if seed % 4 == 0:   # a few long rows on top, so that deep batches, spans and heavy groups occur
+        m = _with_long_rows(m, rng)
+    threads = int(rng.choice([256, 512, 1024]))
+    params = dict(
+        rows_per_block=int(rng.choice([1, 7, 64, 512, 2048, 8192])),
+        cols_per_block=int(rng.choice([1, 33, 256, 4096, 32768])),
+        group_width=int(rng.choice([1, 5, 32, 64])),
+        num_workers=int(rng.choice([0, 1, 3, 17, 300])),
+        fixed_fraction_q8=int(rng.choice([0, 77, 192, 255, 256])),
+        claim_chunk=int(rng.choice([0, 1, 3, 50])),
+        threads_per_worker=threads,
+        rounds_per_batch=int(rng.choice([2, 4, 8, 9, 16])),
+        slot_weight=int(rng.choice([0, 1, 4, 64])),
+        group_weight=int(rng.choice([0, 10, 4096])),
+        round_weight=int(rng.choice([0, 8, 1024])),
+        combine_unit_slots=int(rng.choice([0, 64, 1000])),
+        heavy_group_rounds=int(rng.choice([0, 1, 20, 300])),
+        hash_shift=int(rng.choice([-1, 0, 3, 12])),
+    )
+    if params["rows_per_block"] * params["cols_per_block"] < 64 and n_rows * n_cols > 4_000_000:
+        params["rows_per_block"] = 64   # keep the block table of the tiny-block cases small
+    check_against_oracle(H, oracle, m, check_add_sign=seed % 3 == 0, **params)
+
+
+def _with_long_rows(m, rng):
+    """m with a handful of rows replaced by rows that fill 10 to 90 % of the columns."""
+    from workloads import CsrMatrix
+    lens = np.diff(m.ptr).astype(np.int64)
+    rows = [m.col[m.ptr[i]:m.ptr[i + 1]] for i in range(m.n_rows)]
+    for i in rng.choice(m.n_rows, size=min(m.n_rows, 6), replace=False):
+        k = max(1, int(m.n_cols * rng.uniform(0.1, 0.9)))
+        rows[i] = np.sort(rng.choice(m.n_cols, k, replace=False)).astype(np.int32)
+        lens[i] = k
+    col = np.concatenate(rows).astype(np.int32) if lens.sum() else np.zeros(0, np.int32)
+    ptr = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    return CsrMatrix(m.name + "+long", m.n_rows, m.n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32), m.x)
