@@ -184,6 +184,31 @@ def main() -> int:
             out[name] = {"ms": round(ms, 5), "GFLOPs": round(2.0 * m.nnz / (ms * 1e-3) / 1e9, 2),
                          "hbp_speedup": round(ms / ms_per_step, 3)}
 
+    if not args.no_csr:
+        # Section 4's second baseline: the same 2D partition without the hash reorder and with an
+        # all-fixed schedule, and the diagnostic of Section 4.1 for both layouts (mean over the
+        # groups of the standard deviation of their rows' lengths)
+        def group_len_std(handle):
+            seg_len = H.hbp_export(handle, "seg_len").astype(np.float64)
+            gs = H.hbp_export(handle, "group_slot").astype(np.int64)
+            cnt = np.diff(gs).astype(np.float64)
+            s1 = np.add.reduceat(seg_len, gs[:-1])
+            s2 = np.add.reduceat(seg_len * seg_len, gs[:-1])
+            var = np.maximum(s2 / cnt - (s1 / cnt) ** 2, 0.0)
+            return float(np.sqrt(var).mean())
+        plain_params = dict(params, fixed_fraction_q8=256)
+        hp = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, no_reorder=True, **plain_params)
+        for _ in range(5):
+            H.hbp_spmv(hp, x, y)
+        torch.cuda.synchronize()
+        p_part, p_comb, p_call = H.hbp_spmv_timed(hp, x, y, max(5, min(50, args.steps)))
+        ms = p_part + p_comb
+        out["plain_2d"] = {"ms": round(ms, 5), "ms_spmv_part": round(p_part, 5), "ms_combine": round(p_comb, 5),
+                           "GFLOPs": round(2.0 * m.nnz / (ms * 1e-3) / 1e9, 2),
+                           "hbp_speedup": round(ms / (ms_part + ms_comb), 3),
+                           "group_len_std": {"hbp": round(group_len_std(h), 4), "plain_2d": round(group_len_std(hp), 4)}}
+        H.hbp_free(hp)
+
     if not args.no_cpu_baseline:
         import oracle
         reps, times = 5, []

@@ -83,6 +83,8 @@ typedef enum {
 
 /* flags for hbp_params_t.flags */
 #define HBP_FLAG_VALIDATE 1u /* check column order/range of the CSR input during the build */
+#define HBP_FLAG_NO_REORDER 2u /* plain 2D partitioning, the method Section 4 compares HBP with: no hash
+                                  reorder, the slots of a block stay in ascending row order */
 
 /* Build parameters.  Block sizes follow Section 3.1 (the paper derives 4096 columns from
  * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is

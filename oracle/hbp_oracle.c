@@ -183,8 +183,9 @@ void oracle_hbp_free(oracle_hbp *h)
     free(h);
 }
 
-/* Build the compact layout.  hash_shift < 0 samples a.  num_workers P and fixed_q8
- * (share of the work pre-assigned, in 1/256) define the schedule arrays.
+/* Build the compact layout.  hash_shift = -1 samples a; hash_shift = -2 also switches the reorder off (the plain
+ * 2D-partitioning method the paper compares with in Section 4: slots of a block in ascending row order).
+ * num_workers P and fixed_q8 (share of the work pre-assigned, in 1/256) define the schedule arrays.
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
@@ -195,6 +196,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
     h->a = hash_shift >= 0 ? hash_shift : oracle_sample_shift(ptr, col, n_rows, C);
+    const int plain = hash_shift == -2;  /* plain 2D partition: no reorder, every row gets key 0 */
     int64_t NBR = (n_rows + R - 1) / R, NBC = (n_cols + C - 1) / C;
     h->NBR = NBR; h->NBC = NBC;
 
@@ -249,10 +251,10 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     for (int64_t b = 0; b < B; b++) {
         int64_t s0 = h->slot_ptr[b], s1 = h->slot_ptr[b + 1];
         memset(table, 0, sizeof(int64_t) * (size_t)(R + 1));
-        for (int64_t s = s0; s < s1; s++) table[oracle_hash_key((uint32_t)tn[s], h->a, R) + 1]++;
+        for (int64_t s = s0; s < s1; s++) table[(plain ? 0 : oracle_hash_key((uint32_t)tn[s], h->a, R)) + 1]++;
         for (int64_t k = 0; k < R; k++) table[k + 1] += table[k];
         for (int64_t s = s0; s < s1; s++) {   /* ascending local row */
-            int64_t slot = s0 + table[oracle_hash_key((uint32_t)tn[s], h->a, R)]++;
+            int64_t slot = s0 + table[plain ? 0 : oracle_hash_key((uint32_t)tn[s], h->a, R)]++;
             h->row_local[slot] = (uint16_t)tq[s];
             h->seg_len[slot] = (uint16_t)tn[s];
             slot_j[slot] = tj[s];

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libhbp.so")
 
 HBP_OK = 0
 HBP_FLAG_VALIDATE = 1
+HBP_FLAG_NO_REORDER = 2
 
 ARRAY_IDS = {
     "blk_bm": 0, "blk_bn": 1, "slot_ptr": 2, "blk_group_ptr": 3, "col_blk_ptr": 4, "stripe_ptr": 5,
@@ -139,11 +140,13 @@ def hbp_default_params() -> hbp_params_t:
 def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
               **overrides) -> int:
     """CSR (device tensors) -> handle.  ``overrides`` set fields of hbp_params_t by name
-    (``validate=True/False`` sets the flag)."""
+    (``validate=True/False`` and ``no_reorder=True/False`` set the flags)."""
     p = params if params is not None else hbp_default_params()
     for k, v in overrides.items():
         if k == "validate":
             p.flags = (p.flags | HBP_FLAG_VALIDATE) if v else (p.flags & ~HBP_FLAG_VALIDATE)
+        elif k == "no_reorder":
+            p.flags = (p.flags | HBP_FLAG_NO_REORDER) if v else (p.flags & ~HBP_FLAG_NO_REORDER)
         else:
             if not hasattr(p, k):
                 raise TypeError(f"hbp_params_t has no field {k}")

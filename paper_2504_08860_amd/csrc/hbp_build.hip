@@ -475,7 +475,7 @@ __global__ __launch_bounds__(256) void k_count_blocks(const int32_t *__restrict_
 // in which the segments of a block arrive is arbitrary (k_order_block sorts them).
 __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_j, const int32_t *__restrict__ seg_row,
                                                 const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR, int32_t NBC,
-                                                const int32_t *__restrict__ a_ptr, uint32_t *__restrict__ cursor,
+                                                const int32_t *__restrict__ a_ptr, int32_t reorder, uint32_t *__restrict__ cursor,
                                                 uint32_t *__restrict__ bucket_key, uint32_t *__restrict__ bucket_seg)
 {
     __shared__ uint32_t cnt[kTileCounters];  // per counter of the tile: segments seen, then their first position
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_
     const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u, a = (uint32_t)*a_ptr;
     auto emit = [&](int64_t s, int32_t row, uint32_t pos) {
         const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-        bucket_key[pos] = (hash_key(n, a, b, R_u) << 16) | (uint32_t)(row % R);
+        bucket_key[pos] = ((reorder ? hash_key(n, a, b, R_u) : 0u) << 16) | (uint32_t)(row % R);
         bucket_seg[pos] = (uint32_t)s;
     };
     if (t.span == 0) {
@@ -978,7 +978,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_unit_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(h->stripe_ptr, stripe_cum, h->unit_ptr, multi_idx, (int32_t)NBR, (int32_t)B,
                                                      h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
-    k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a, slot_off,
+    k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a,
+                                                       (p.flags & HBP_FLAG_NO_REORDER) ? 0 : 1, slot_off,
                                                        bucket_key, bucket_seg);
     int n2 = 2;
     while (n2 < R) n2 <<= 1;

@@ -37,7 +37,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
     try:
         info = H.hbp_get_info(h)
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
-                             W=info.group_width, hash_shift=params.get("hash_shift", -1),
+                             W=info.group_width, hash_shift=-2 if params.get("no_reorder") else params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
                              round_weight=info.round_weight, group_weight=info.group_weight)
@@ -297,3 +297,10 @@ def _with_long_rows(m, rng):
     col = np.concatenate(rows).astype(np.int32) if lens.sum() else np.zeros(0, np.int32)
     ptr = np.r_[0, np.cumsum(lens)].astype(np.int32)
     return CsrMatrix(m.name + "+long", m.n_rows, m.n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32), m.x)
+
+
+@pytest.mark.parametrize("R,C", [(64, 128), (512, 4096)])
+def test_plain_2d_partition(H, oracle, R, C):
+    """HBP_FLAG_NO_REORDER: the plain 2D-partitioning method of Section 4 (no hash reorder)."""
+    m = _mixed_matrix(seed=3)
+    check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, no_reorder=True)

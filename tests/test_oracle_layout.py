@@ -346,3 +346,19 @@ def test_configs_small_scale(oracle, number, scale, R, C):
     bm = np.repeat(h.array("blk_bm"), np.diff(h.array("slot_ptr")))
     np.add.at(tot, bm.astype(np.int64) * R + h.array("row_local"), h.array("seg_len"))
     assert np.array_equal(tot, np.diff(m.ptr))
+
+
+def test_plain_2d_partition_keeps_row_order(oracle):
+    """hash_shift = -2 (the plain 2D partitioning of Section 4): the slots of every block list its
+    rows in ascending order, nothing else changes (same segments, same y)."""
+    m = random_csr(200, 300, 0.08, 9)
+    plain = build(oracle, m, R=32, C=64, W=8, hash_shift=-2)
+    hbp = build(oracle, m, R=32, C=64, W=8)
+    sp, rl = plain.array("slot_ptr"), plain.array("row_local")
+    for b in range(plain.B):
+        assert np.all(np.diff(rl[sp[b]:sp[b + 1]].astype(np.int64)) > 0)
+    assert (plain.B, plain.S) == (hbp.B, hbp.S)
+    assert coo_set(*plain.to_coo()) == coo_set(*hbp.to_coo())
+    y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    y, _ = plain.spmv(m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-12 * np.maximum(s_abs, 1e-300))
