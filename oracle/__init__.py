@@ -49,11 +49,13 @@ def _load():
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         lib.oracle_csr_spmv_f64.argtypes = [vp, vp, vp, vp, i64, vp, vp]
         lib.oracle_csr_spmv_f64.restype = None
+        lib.oracle_csr_spmv_f64_d.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+        lib.oracle_csr_spmv_f64_d.restype = None
         lib.oracle_hash_key.argtypes = [ctypes.c_uint32, i32, i32]
         lib.oracle_hash_key.restype = ctypes.c_uint32
         lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
         lib.oracle_sample_shift.restype = i32
-        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32]
+        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32]
         lib.oracle_hbp_build.restype = vp
         lib.oracle_hbp_free.argtypes = [vp]
         lib.oracle_hbp_free.restype = None
@@ -80,7 +82,9 @@ def csr_spmv_f64(ptr, col, val, x):
     n_rows = len(ptr) - 1
     y = np.empty(n_rows, dtype=np.float64)
     s = np.empty(n_rows, dtype=np.float64)
-    _load().oracle_csr_spmv_f64(_p(ptr), _p(col), _p(val), _p(x), n_rows, _p(y), _p(s))
+    assert val.dtype == x.dtype and val.dtype in (np.float32, np.float64)
+    fn = _load().oracle_csr_spmv_f64 if val.dtype == np.float32 else _load().oracle_csr_spmv_f64_d
+    fn(_p(ptr), _p(col), _p(val), _p(x), n_rows, _p(y), _p(s))
     return y, s
 
 
@@ -98,7 +102,9 @@ class OracleHbp:
     def __init__(self, ptr, col, val, n_rows, n_cols, R=512, C=4096, W=64, hash_shift=-1,
                  num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, group_weight=0):
         lib = _load()
-        self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(n_rows), int(n_cols), int(R), int(C), int(W),
+        assert val.dtype in (np.float32, np.float64)
+        self.value_dtype = val.dtype
+        self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(val.dtype.itemsize), int(n_rows), int(n_cols), int(R), int(C), int(W),
                                        int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(group_weight),
                                        int(unit_slots))
         if not self._h:
@@ -112,6 +118,8 @@ class OracleHbp:
     def array(self, name: str) -> np.ndarray:
         if name not in self._cache:
             which, dt = ARRAYS[name]
+            if name == "data":
+                dt = self.value_dtype
             lib = _load()
             nbytes = lib.oracle_hbp_copy(self._h, which, None)
             out = np.empty(nbytes // np.dtype(dt).itemsize, dtype=dt)
@@ -124,13 +132,14 @@ class OracleHbp:
         """(y, partial) through the layout (Algorithm 3 walk + combine), fp64."""
         partial = np.zeros(max(self.S, 1), dtype=np.float64)
         y = np.zeros(self.n_rows, dtype=np.float64)
+        assert x.dtype == self.value_dtype
         _load().oracle_hbp_spmv(self._h, _p(x), _p(partial), _p(y))
         return y, partial[: self.S]
 
     def to_coo(self):
         rows = np.full(max(self.nnz, 1), -1, dtype=np.int64)
         cols = np.full(max(self.nnz, 1), -1, dtype=np.int64)
-        vals = np.zeros(max(self.nnz, 1), dtype=np.float32)
+        vals = np.zeros(max(self.nnz, 1), dtype=self.value_dtype)
         _load().oracle_hbp_to_coo(self._h, _p(rows), _p(cols), _p(vals))
         return rows[: self.nnz], cols[: self.nnz], vals[: self.nnz]
 

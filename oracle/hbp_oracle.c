@@ -7,6 +7,7 @@
  *
  * What it computes, and the passage of the paper each part follows:
  *   - oracle_csr_spmv_f64      y = A x by the plain definition (Algorithm 1), fp64.
+ *   - oracle_csr_spmv_f64_d    the same with the matrix and vector stored in fp64.
  *   - oracle_hash_key          the nonlinear hash = aggregation + dispersion + linear
  *                              mapping (Section 3.2; its figure with the formula is not
  *                              available, so the formula below is this build's reading).
@@ -21,6 +22,10 @@
  *                              add_sign (Algorithm 3, with the do-while reading of its
  *                              loop) then the combine of partial sums (Fig. 1), fp64.
  *   - oracle_hbp_to_coo        inverse of the format conversion.
+ *
+ * Values are stored as fp32 (value_bytes 4) or fp64 (value_bytes 8, the storage type of
+ * Section 3.1's cost estimate); everything except the data array is the same for both,
+ * and all arithmetic is fp64 either way.
  *
  * Layout produced ("compact" mode): only non-empty blocks and, inside a block, only
  * rows with at least one nonzero in it are stored.  Blocks are listed column-major
@@ -52,6 +57,22 @@ void oracle_csr_spmv_f64(const int32_t *ptr, const int32_t *col, const float *va
         double sum = 0.0, mag = 0.0;
         for (int64_t j = ptr[i]; j < ptr[i + 1]; j++) {
             double p = (double)val[j] * (double)x[col[j]];
+            sum += p;
+            mag += p < 0 ? -p : p;
+        }
+        y_ref[i] = sum;
+        if (s_abs) s_abs[i] = mag;
+    }
+}
+
+/* The same for fp64 storage (the paper's storage type, Section 3.1): val and x are doubles. */
+void oracle_csr_spmv_f64_d(const int32_t *ptr, const int32_t *col, const double *val, const double *x,
+                           int64_t n_rows, double *y_ref, double *s_abs)
+{
+    for (int64_t i = 0; i < n_rows; i++) {
+        double sum = 0.0, mag = 0.0;
+        for (int64_t j = ptr[i]; j < ptr[i + 1]; j++) {
+            double p = val[j] * x[col[j]];
             sum += p;
             mag += p < 0 ? -p : p;
         }
@@ -142,7 +163,9 @@ typedef struct {
     uint16_t *row_local;          /* S   : slot -> row inside its block (output_hash)      */
     uint16_t *seg_len;            /* S   : nonzeros of that row inside the block           */
     uint16_t *col_local;          /* nnz : column inside the block's column range          */
-    float *data;                  /* nnz                                                   */
+    float *data;                  /* nnz (fp32 storage)                                    */
+    double *data64;               /* nnz (fp64 storage); exactly one of data / data64 is set */
+    int32_t value_bytes;          /* 4 or 8                                                */
     int32_t *add_sign;            /* nnz : distance to the row's next nonzero, -1 at its end */
     int32_t *col_group_ptr;       /* NBC+1 : first group of each block column                 */
     int32_t *comp_lo;             /* NBC : first competitive group of a block column          */
@@ -178,7 +201,7 @@ void oracle_hbp_free(oracle_hbp *h)
     if (!h) return;
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_rounds); free(h->group_slot);
-    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
+    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->data64); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
     free(h->unit_ptr); free(h->unit_stripe); free(h->unit_k); free(h->multi_stripes);
     free(h);
 }
@@ -187,11 +210,11 @@ void oracle_hbp_free(oracle_hbp *h)
  * 2D-partitioning method the paper compares with in Section 4: slots of a block in ascending row order).
  * num_workers P and fixed_q8 (share of the work pre-assigned, in 1/256) define the schedule arrays.
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
-oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float *val, int64_t n_rows, int64_t n_cols,
+oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void *val, int32_t value_bytes, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
                              int32_t slot_weight, int32_t round_weight, int32_t group_weight, int32_t unit_slots)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || unit_slots < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || (value_bytes != 4 && value_bytes != 8) || unit_slots < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -265,7 +288,9 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
     h->group_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
     h->group_slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
     h->col_local = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(h->nnz + 1));
-    h->data = (float *)malloc(sizeof(float) * (size_t)(h->nnz + 1));
+    h->value_bytes = value_bytes;
+    if (value_bytes == 4) h->data = (float *)malloc(sizeof(float) * (size_t)(h->nnz + 1));
+    else h->data64 = (double *)malloc(sizeof(double) * (size_t)(h->nnz + 1));
     h->add_sign = (int32_t *)malloc(sizeof(int32_t) * (size_t)(h->nnz + 1));
     {
         int64_t pos = 0, g = 0;
@@ -280,7 +305,8 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const float
                     for (int64_t s = s0; s < s1; s++) {
                         if (k >= h->seg_len[s]) continue;
                         h->col_local[pos] = (uint16_t)(col[slot_j[s] + k] - col0);
-                        h->data[pos] = val[slot_j[s] + k];
+                        if (value_bytes == 4) h->data[pos] = ((const float *)val)[slot_j[s] + k];
+                        else h->data64[pos] = ((const double *)val)[slot_j[s] + k];
                         if (k + 1 == h->seg_len[s]) { h->add_sign[pos] = -1; live--; }
                         else h->add_sign[pos] = (int32_t)live;
                         pos++;
@@ -420,7 +446,7 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 9: src = h->row_local; bytes = 2 * h->S; break;
     case 10: src = h->seg_len; bytes = 2 * h->S; break;
     case 11: src = h->col_local; bytes = 2 * h->nnz; break;
-    case 12: src = h->data; bytes = 4 * h->nnz; break;
+    case 12: src = h->value_bytes == 4 ? (const void *)h->data : (const void *)h->data64; bytes = h->value_bytes * h->nnz; break;
     case 13: src = h->add_sign; bytes = 4 * h->nnz; break;
     case 14: src = h->col_group_ptr; bytes = 4 * (h->NBC + 1); break;
     case 15: src = h->comp_lo; bytes = 4 * h->NBC; break;
@@ -442,17 +468,18 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
  * so the zero_row correction is 0) and walks its row with add_sign, accumulating then
  * stopping once add_sign is negative.  partial[s] is the block's contribution to row
  * bm*R + row_local[s].  Combine part: partial sums of a row are added with bn ascending. */
-void oracle_hbp_spmv(const oracle_hbp *h, const float *x, double *partial, double *y)
+void oracle_hbp_spmv(const oracle_hbp *h, const void *x_any, double *partial, double *y)
 {
     for (int64_t b = 0; b < h->B; b++) {
-        const float *xs = x + (int64_t)h->blk_bn[b] * h->C;   /* the block's vector segment */
+        const int64_t x0 = (int64_t)h->blk_bn[b] * h->C;   /* start of the block's vector segment */
         for (int64_t g = h->blk_group_ptr[b]; g < h->blk_group_ptr[b + 1]; g++) {
             for (int64_t s = h->group_slot[g]; s < h->group_slot[g + 1]; s++) {
                 int64_t j = h->group_ptr[g] + (s - h->group_slot[g]);
                 double sum = 0.0;
                 int32_t step;
                 do {
-                    sum += (double)h->data[j] * (double)xs[h->col_local[j]];
+                    sum += h->value_bytes == 4 ? (double)h->data[j] * (double)((const float *)x_any)[x0 + h->col_local[j]]
+                                               : h->data64[j] * ((const double *)x_any)[x0 + h->col_local[j]];
                     step = h->add_sign[j];
                     j += step;
                 } while (step > 0);
@@ -471,7 +498,7 @@ void oracle_hbp_spmv(const oracle_hbp *h, const float *x, double *partial, doubl
 
 /* Inverse of the conversion: every stored nonzero as (row, global column, value), in
  * storage order. */
-void oracle_hbp_to_coo(const oracle_hbp *h, int64_t *rows, int64_t *cols, float *vals)
+void oracle_hbp_to_coo(const oracle_hbp *h, int64_t *rows, int64_t *cols, void *vals)
 {
     for (int64_t b = 0; b < h->B; b++)
         for (int64_t g = h->blk_group_ptr[b]; g < h->blk_group_ptr[b + 1]; g++)
@@ -480,7 +507,8 @@ void oracle_hbp_to_coo(const oracle_hbp *h, int64_t *rows, int64_t *cols, float 
                 for (;;) {
                     rows[j] = (int64_t)h->blk_bm[b] * h->R + h->row_local[s];
                     cols[j] = (int64_t)h->blk_bn[b] * h->C + h->col_local[j];
-                    vals[j] = h->data[j];
+                    if (h->value_bytes == 4) ((float *)vals)[j] = h->data[j];
+                    else ((double *)vals)[j] = h->data64[j];
                     if (h->add_sign[j] < 0) break;
                     j += h->add_sign[j];
                 }

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle.hbp_literal import LiteralHbp
-from workloads import make_config, random_csr, worked_example_8x8
+from workloads import make_config, random_csr, widen_to_f64, worked_example_8x8
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_8x8.json")
 
@@ -362,3 +362,33 @@ def test_plain_2d_partition_keeps_row_order(oracle):
     y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
     y, _ = plain.spmv(m.x)
     assert np.all(np.abs(y - y_ref) <= 1e-12 * np.maximum(s_abs, 1e-300))
+
+
+def test_fp64_storage(oracle):
+    """fp64 storage (Section 3.1's value type): the structure is that of the fp32 build of the same
+    pattern, the values come back bit for bit (they are not float32-representable), and the SpMV
+    agrees with the plain definition and with an exact rational evaluation on sampled rows."""
+    from fractions import Fraction
+    m32 = random_csr(150, 260, 0.07, 21, empty_row_frac=0.1)
+    m = widen_to_f64(m32, 5)
+    assert np.any(m.val != m.val.astype(np.float32)) and np.any(m.x != m.x.astype(np.float32))
+    h32 = build(oracle, m32, R=32, C=64, W=8, num_workers=3)
+    h = build(oracle, m, R=32, C=64, W=8, num_workers=3)
+    for name in oracle.ARRAYS:
+        if name != "data":
+            assert np.array_equal(h.array(name), h32.array(name)), name
+    assert h.array("data").dtype == np.float64 and h.array("data").shape == (m.nnz,)
+    rows, cols, vals = h.to_coo()
+    got = sorted(zip(rows.tolist(), cols.tolist(), vals.view(np.uint64).tolist()))
+    want = sorted(zip(np.repeat(np.arange(m.n_rows), np.diff(m.ptr)).tolist(), m.col.tolist(), m.val.view(np.uint64).tolist()))
+    assert got == want
+    y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    y, _ = h.spmv(m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-13 * s_abs)
+    for i in range(0, m.n_rows, 7):
+        exact = sum((Fraction(float(m.val[j])) * Fraction(float(m.x[m.col[j]])) for j in range(m.ptr[i], m.ptr[i + 1])), Fraction(0))
+        assert abs(Fraction(float(y_ref[i])) - exact) <= Fraction(1, 10**13) * Fraction(float(s_abs[i])) + Fraction(1, 10**300)
+        assert abs(Fraction(float(y[i])) - exact) <= Fraction(1, 10**13) * Fraction(float(s_abs[i])) + Fraction(1, 10**300)
+    # the float32 result of the same pattern differs by more than the fp64 bound on most rows
+    y32, _ = oracle.csr_spmv_f64(m32.ptr, m32.col, m32.val, m32.x)
+    assert np.mean(np.abs(y32 - y_ref) > 1e-11 * s_abs) > 0.5

@@ -2,7 +2,8 @@
 
 These generators are the only code shared by the CPU oracle's tests and the
 HIP path's tests/bench.  They hold none of the method's arithmetic: they only
-produce CSR matrices (int32 ``ptr``/``col``, float32 ``val``) and dense vectors
+produce CSR matrices (int32 ``ptr``/``col``, float32 ``val``; ``widen_to_f64`` gives the
+float64 variant) and dense vectors
 ``x`` whose shapes and sparsity structure stand in for the SuiteSparse matrices
 of the paper's Table 1, which cannot be obtained here.
 
@@ -20,4 +21,5 @@ from .generators import (  # noqa: F401
     lognormal_rect,
     random_csr,
     worked_example_8x8,
+    widen_to_f64,
 )

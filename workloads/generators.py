@@ -21,8 +21,8 @@ class CsrMatrix:
     n_cols: int
     ptr: np.ndarray  # int32, n_rows + 1
     col: np.ndarray  # int32, nnz, strictly ascending inside each row
-    val: np.ndarray  # float32, nnz
-    x: np.ndarray  # float32, n_cols
+    val: np.ndarray  # float32 (float64 after widen_to_f64), nnz
+    x: np.ndarray  # same type as val, n_cols
 
     @property
     def nnz(self) -> int:
@@ -31,7 +31,7 @@ class CsrMatrix:
     def check(self) -> None:
         """Structural self-check of the generator output (not of the method)."""
         assert self.ptr.dtype == np.int32 and self.col.dtype == np.int32
-        assert self.val.dtype == np.float32 and self.x.dtype == np.float32
+        assert self.val.dtype == self.x.dtype and self.val.dtype in (np.float32, np.float64)
         assert self.ptr.shape == (self.n_rows + 1,) and self.ptr[0] == 0
         assert self.col.shape == (self.nnz,) and self.val.shape == (self.nnz,)
         assert self.x.shape == (self.n_cols,)
@@ -210,6 +210,16 @@ def worked_example_8x8() -> CsrMatrix:
         ptr.append(len(col))
     return CsrMatrix("worked8x8", 8, 8, np.array(ptr, dtype=np.int32), np.array(col, dtype=np.int32),
                      np.array(val, dtype=np.float32), np.arange(1, 9, dtype=np.float32))
+
+
+def widen_to_f64(m: CsrMatrix, seed: int = 64) -> CsrMatrix:
+    """The same matrix and vector stored in float64, with seeded random bits below float32's
+    last place (each value is scaled by 1 + u * 2**-24, u uniform in [0, 1)), so that a
+    path which rounds its values to float32 anywhere is told apart from one that does not."""
+    rng = np.random.default_rng(seed)
+    val = m.val.astype(np.float64) * (1.0 + rng.random(m.val.shape[0]) * 2.0**-24)
+    x = m.x.astype(np.float64) * (1.0 + rng.random(m.x.shape[0]) * 2.0**-24)
+    return CsrMatrix(m.name + "_f64", m.n_rows, m.n_cols, m.ptr, m.col, val, x)
 
 
 CONFIG_NAMES = {
