@@ -54,9 +54,16 @@
  *     seg_len     u16     [S]      nonzeros of that row inside the block (add_sign is
  *                                  derived from these at run time)
  *     col_local   u16     [nnz]    column inside the block               (col)
- *     data        f32     [nnz]    values, bit-for-bit copies            (data)
+ *     data        f32/f64 [nnz]    values, bit-for-bit copies            (data)
  *   begin_nnz of a block is group_ptr[blk_group_ptr[b]]; zero_row is not stored because
  *   empty rows own no slot.
+ *
+ * Value type.  A handle holds fp32 values (hbp_build; x, y and the partial sums are fp32 and
+ *   all products and sums are taken in fp32) or fp64 values, the storage type of Section 3.1's
+ *   cost estimate (hbp_build_f64; x, y, partial sums and arithmetic fp64).  Everything except
+ *   `data` and `partial` is the same for both.  The entry points without suffix take fp32
+ *   handles, those ending in _f64 take fp64 handles; the other kind of handle is refused
+ *   with HBP_ERR_INVALID_ARGUMENT.
  */
 #ifndef HBP_H
 #define HBP_H
@@ -90,8 +97,8 @@ typedef enum {
  * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is
  * staged in the 160 KB LDS of a gfx950 compute unit as fp32. */
 typedef struct {
-    int32_t rows_per_block;    /* R, 1..8192; 0 = default 512                                   */
-    int32_t cols_per_block;    /* C, 1..32768; 0 = default 4096                                 */
+    int32_t rows_per_block;    /* R, 1..8192 (fp64: 1..4096); 0 = default 512                   */
+    int32_t cols_per_block;    /* C, 1..32768 (fp64: 1..16384): 128 KB of x in LDS; 0 = default 4096 */
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = as many as
                                   fit on the device at once, but no more than one per threads_per_worker / 64 groups */
@@ -134,6 +141,7 @@ typedef struct {
     int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
+    int32_t value_bytes;         /* 4: fp32 handle, 8: fp64 handle                              */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves                 */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
@@ -147,7 +155,7 @@ typedef enum {
     HBP_ARRAY_GROUP_SLOT = 8, HBP_ARRAY_ROW_LOCAL = 9, HBP_ARRAY_SEG_LEN = 10, HBP_ARRAY_COL_LOCAL = 11,
     HBP_ARRAY_DATA = 12,
     HBP_ARRAY_ADD_SIGN = 13, /* int32 [nnz], derived on the device from seg_len when exported   */
-    HBP_ARRAY_PARTIAL = 14,  /* float [S], per-slot partial sums left by the last hbp_spmv      */
+    HBP_ARRAY_PARTIAL = 14,  /* float or double [S], per-slot partial sums of the last SpMV      */
     HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
     HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22,
     HBP_ARRAY_GROUP_ROUNDS = 23
@@ -179,6 +187,16 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
  * caller (they share the partial-sum buffer and the ticket counter). */
 int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream);
 
+/* The fp64 variant (Section 3.1 counts 8 bytes per stored value): hbp_build_f64 is hbp_build
+ * with csr_val DEVICE double [nnz], and builds the same layout and schedule as hbp_build
+ * would for the same pattern and parameters, with `data` in fp64 (R at most 4096 and C at
+ * most 16384: the LDS copies of the x and y slices are twice as large).  hbp_spmv_f64 is
+ * hbp_spmv with x DEVICE double [n_cols], y DEVICE double [n_rows]; products, partial sums
+ * and the combine part are fp64. */
+int hbp_build_f64(const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val,
+                  int64_t n_rows, int64_t n_cols, const hbp_params_t *params, void *stream, hbp_handle_t *out);
+int hbp_spmv_f64(hbp_handle_t h, const double *x, double *y, void *stream);
+
 /* Frees the handle and its device arrays (synchronises the device first). NULL is allowed. */
 int hbp_free(hbp_handle_t h);
 
@@ -196,11 +214,15 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
  * after the second).  Synchronises the stream. */
 int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters,
                    float *ms_part, float *ms_combine, float *ms_total);
+int hbp_spmv_timed_f64(hbp_handle_t h, const double *x, double *y, void *stream, int iters,
+                       float *ms_part, float *ms_combine, float *ms_total);
 
 /* In-repo CSR baselines (Algorithm 1).  kind 0: one thread per row; kind 1: one wavefront
  * per row with a cross-lane reduction.  All pointers DEVICE; y overwritten. */
 int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
                  const float *x, float *y, int64_t n_rows, void *stream);
+int hbp_csr_spmv_f64(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val,
+                     const double *x, double *y, int64_t n_rows, void *stream);
 
 const char *hbp_status_string(int status);
 /* hipError_t of the most recent HBP_ERR_HIP on this thread, as int. */

@@ -36,6 +36,7 @@ ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = (
     "hbp_default_params", "hbp_build", "hbp_spmv", "hbp_free", "hbp_get_info", "hbp_export", "hbp_spmv_timed",
     "hbp_csr_spmv", "hbp_status_string", "hbp_last_hip_error",
+    "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64",
 )
 
 
@@ -58,7 +59,7 @@ class hbp_info_t(ctypes.Structure):
                 ("threads_per_worker", ctypes.c_int32), ("rounds_per_batch", ctypes.c_int32),
                 ("slot_weight", ctypes.c_int32), ("group_weight", ctypes.c_int32), ("combine_unit_slots", ctypes.c_int32),
                 ("heavy_group_rounds", ctypes.c_int32), ("round_weight", ctypes.c_int32),
-                ("combine_units", ctypes.c_int64), ("split_row_blocks", ctypes.c_int64),
+                ("combine_units", ctypes.c_int64), ("split_row_blocks", ctypes.c_int64), ("value_bytes", ctypes.c_int32),
                 ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
                 ("build_ms", ctypes.c_double)]
 
@@ -93,6 +94,10 @@ def lib() -> ctypes.CDLL:
         L.hbp_export.argtypes = [vp, ctypes.c_int, vp, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
         L.hbp_spmv_timed.argtypes = [vp, vp, vp, vp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_float)] * 3
         L.hbp_csr_spmv.argtypes = [ctypes.c_int, vp, vp, vp, vp, vp, i64, vp]
+        L.hbp_build_f64.argtypes = L.hbp_build.argtypes
+        L.hbp_spmv_f64.argtypes = L.hbp_spmv.argtypes
+        L.hbp_spmv_timed_f64.argtypes = L.hbp_spmv_timed.argtypes
+        L.hbp_csr_spmv_f64.argtypes = L.hbp_csr_spmv.argtypes
         L.hbp_status_string.argtypes = [ctypes.c_int]
         L.hbp_status_string.restype = ctypes.c_char_p
         L.hbp_last_hip_error.argtypes = []
@@ -127,6 +132,12 @@ def _dev_f32(t, what):
     return t.data_ptr()
 
 
+def _dev_f64(t, what):
+    import torch
+    assert t.is_cuda and t.dtype == torch.float64 and t.is_contiguous(), f"{what}: contiguous float64 CUDA tensor required"
+    return t.data_ptr()
+
+
 def hbp_status_string(status: int) -> str:
     return lib().hbp_status_string(int(status)).decode()
 
@@ -137,10 +148,7 @@ def hbp_default_params() -> hbp_params_t:
     return p
 
 
-def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
-              **overrides) -> int:
-    """CSR (device tensors) -> handle.  ``overrides`` set fields of hbp_params_t by name
-    (``validate=True/False`` and ``no_reorder=True/False`` set the flags)."""
+def _build(f64: bool, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, overrides) -> int:
     p = params if params is not None else hbp_default_params()
     for k, v in overrides.items():
         if k == "validate":
@@ -154,9 +162,23 @@ def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_p
     assert csr_ptr.numel() == n_rows + 1
     assert csr_col.numel() == csr_val.numel()
     out = ctypes.c_void_p()
-    _check(lib().hbp_build(_dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"), _dev_f32(csr_val, "csr_val"),
-                           int(n_rows), int(n_cols), ctypes.byref(p), _stream_ptr(stream), ctypes.byref(out)), "hbp_build")
+    fn, val = (lib().hbp_build_f64, _dev_f64(csr_val, "csr_val")) if f64 else (lib().hbp_build, _dev_f32(csr_val, "csr_val"))
+    _check(fn(_dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"), val,
+              int(n_rows), int(n_cols), ctypes.byref(p), _stream_ptr(stream), ctypes.byref(out)), "hbp_build_f64" if f64 else "hbp_build")
     return out.value
+
+
+def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
+              **overrides) -> int:
+    """CSR (device tensors, float32 values) -> handle.  ``overrides`` set fields of hbp_params_t by name
+    (``validate=True/False`` and ``no_reorder=True/False`` set the flags)."""
+    return _build(False, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, overrides)
+
+
+def hbp_build_f64(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
+                  **overrides) -> int:
+    """hbp_build for float64 values; the handle goes with the ``_f64`` calls."""
+    return _build(True, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, overrides)
 
 
 def hbp_spmv(handle: int, x, y, stream=None) -> None:
@@ -165,11 +187,24 @@ def hbp_spmv(handle: int, x, y, stream=None) -> None:
     _check(lib().hbp_spmv(handle, _dev_f32(x, "x"), _dev_f32(y, "y"), _stream_ptr(stream)), "hbp_spmv")
 
 
+def hbp_spmv_f64(handle: int, x, y, stream=None) -> None:
+    info = hbp_get_info(handle)
+    assert x.numel() == info.n_cols and y.numel() == info.n_rows
+    _check(lib().hbp_spmv_f64(handle, _dev_f64(x, "x"), _dev_f64(y, "y"), _stream_ptr(stream)), "hbp_spmv_f64")
+
+
 def hbp_spmv_timed(handle: int, x, y, iters: int, stream=None):
     """(ms SpMV-part kernel, ms combine kernel, ms whole call), averaged over ``iters`` calls."""
     a, b, c = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
     _check(lib().hbp_spmv_timed(handle, _dev_f32(x, "x"), _dev_f32(y, "y"), _stream_ptr(stream), int(iters),
                                 ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "hbp_spmv_timed")
+    return a.value, b.value, c.value
+
+
+def hbp_spmv_timed_f64(handle: int, x, y, iters: int, stream=None):
+    a, b, c = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    _check(lib().hbp_spmv_timed_f64(handle, _dev_f64(x, "x"), _dev_f64(y, "y"), _stream_ptr(stream), int(iters),
+                                    ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "hbp_spmv_timed_f64")
     return a.value, b.value, c.value
 
 
@@ -190,6 +225,8 @@ def hbp_export(handle: int, name: str):
     nbytes = ctypes.c_size_t()
     _check(lib().hbp_export(handle, which, None, 0, ctypes.byref(nbytes)), "hbp_export")
     dt = np.dtype(ARRAY_DTYPES[name])
+    if name in ("data", "partial") and hbp_get_info(handle).value_bytes == 8:
+        dt = np.dtype("float64")
     out = np.empty(nbytes.value // dt.itemsize, dtype=dt)
     if nbytes.value:
         _check(lib().hbp_export(handle, which, out.ctypes.data, out.nbytes, ctypes.byref(nbytes)), "hbp_export")
@@ -201,3 +238,9 @@ def hbp_csr_spmv(kind: int, csr_ptr, csr_col, csr_val, x, y, stream=None) -> Non
     _check(lib().hbp_csr_spmv(int(kind), _dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"),
                               _dev_f32(csr_val, "csr_val"), _dev_f32(x, "x"), _dev_f32(y, "y"),
                               csr_ptr.numel() - 1, _stream_ptr(stream)), "hbp_csr_spmv")
+
+
+def hbp_csr_spmv_f64(kind: int, csr_ptr, csr_col, csr_val, x, y, stream=None) -> None:
+    _check(lib().hbp_csr_spmv_f64(int(kind), _dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"),
+                                  _dev_f64(csr_val, "csr_val"), _dev_f64(x, "x"), _dev_f64(y, "y"),
+                                  csr_ptr.numel() - 1, _stream_ptr(stream)), "hbp_csr_spmv_f64")

@@ -55,8 +55,8 @@ int hbp_default_params(hbp_params_t *p)
     return HBP_OK;
 }
 
-int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, int64_t n_rows, int64_t n_cols,
-              const hbp_params_t *params, void *stream, hbp_handle_t *out)
+static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val, int64_t n_rows,
+                     int64_t n_cols, const hbp_params_t *params, void *stream, hbp_handle_t *out)
 {
     if (!out) return HBP_ERR_INVALID_ARGUMENT;
     *out = nullptr;
@@ -73,7 +73,8 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     if (p.group_weight < 0) p.group_weight = 0;
     if (p.round_weight < 0) p.round_weight = 8;
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
-    if (p.rows_per_block < 1 || p.rows_per_block > hbp::kMaxR || p.cols_per_block < 1 || p.cols_per_block > hbp::kMaxC ||
+    const int32_t max_r = value_bytes == 8 ? hbp::kMaxR64 : hbp::kMaxR, max_c = value_bytes == 8 ? hbp::kMaxC64 : hbp::kMaxC;
+    if (p.rows_per_block < 1 || p.rows_per_block > max_r || p.cols_per_block < 1 || p.cols_per_block > max_c ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
         p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 1024 || p.slot_weight > 64 || p.group_weight > 4096 ||
         (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 || p.heavy_group_rounds < 1 ||
@@ -89,6 +90,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     std::memset(h, 0, sizeof *h);
     if (hipGetDevice(&h->device) != hipSuccess) { delete h; return HBP_ERR_HIP; }
     h->n_rows = n_rows; h->n_cols = n_cols;
+    h->value_bytes = value_bytes;
     h->R = p.rows_per_block; h->C = p.cols_per_block; h->W = p.group_width;
     h->NBR = (n_rows + h->R - 1) / h->R;
     h->NBC = (n_cols + h->C - 1) / h->C;
@@ -98,7 +100,7 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     int rc = HBP_OK;
     if (h->NBR * h->NBC > hbp::kMaxDense) rc = HBP_ERR_TOO_LARGE;
     int32_t threads = 0, workers = 0;
-    if (rc == HBP_OK) rc = hbp::default_workers(h->device, h->C, p.threads_per_worker, &threads, &workers);
+    if (rc == HBP_OK) rc = hbp::default_workers(h->device, h->C, value_bytes, p.threads_per_worker, &threads, &workers);
     if (rc == HBP_OK) {
         h->threads = threads;
         h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
@@ -134,9 +136,9 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
     return HBP_OK;
 }
 
-int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream)
+static int spmv_any(int32_t value_bytes, hbp_handle_t h, const void *x, void *y, void *stream)
 {
-    if (!h || !x || !y) return HBP_ERR_INVALID_ARGUMENT;
+    if (!h || !x || !y || h->value_bytes != value_bytes) return HBP_ERR_INVALID_ARGUMENT;
     DeviceGuard guard(h->device);
     if (!guard.ok) return HBP_ERR_HIP;
     int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream);
@@ -144,10 +146,10 @@ int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream)
     return hbp::launch_combine(h, y, (hipStream_t)stream);
 }
 
-int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters, float *ms_part, float *ms_combine,
-                   float *ms_total)
+static int spmv_timed_any(int32_t value_bytes, hbp_handle_t h, const void *x, void *y, void *stream, int iters, float *ms_part,
+                          float *ms_combine, float *ms_total)
 {
-    if (!h || !x || !y || iters < 1 || iters > 100000) return HBP_ERR_INVALID_ARGUMENT;
+    if (!h || !x || !y || h->value_bytes != value_bytes || iters < 1 || iters > 100000) return HBP_ERR_INVALID_ARGUMENT;
     DeviceGuard guard(h->device);
     if (!guard.ok) return HBP_ERR_HIP;
     hipStream_t st = (hipStream_t)stream;
@@ -178,7 +180,7 @@ int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int i
 
 // Investigation hook (not part of the public header): per-wavefront timestamps of one SpMV-part
 // launch, 4 x uint64 per wavefront: start, end of fixed part, end, time spent staging (10 ns ticks).
-int hbp_debug_timeline(hbp_handle_t h, const float *x, float *y, void *stream, uint64_t *host_out, size_t capacity)
+int hbp_debug_timeline(hbp_handle_t h, const void *x, void *y, void *stream, uint64_t *host_out, size_t capacity)
 {
     if (!h || !x || !y || !host_out) return HBP_ERR_INVALID_ARGUMENT;
     const size_t n = (size_t)h->P * (h->threads / 64) * 4;
@@ -225,14 +227,16 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->heavy_group_rounds = h->heavy_rounds;
     info->combine_units = h->U;
     info->split_row_blocks = h->NM;
+    info->value_bytes = h->value_bytes;
     const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
     const int64_t grp = 4 * 2 * (h->G + 1);
-    info->bytes_layout = blk + grp + 2 * 2 * h->S + 6 * h->nnz;
+    const int64_t vb = h->value_bytes;
+    info->bytes_layout = blk + grp + 2 * 2 * h->S + (2 + vb) * h->nnz;
     // SpMV part: col + data per nonzero, seg_len per slot, both group arrays, the block arrays it
     // reads (blk_bn, blk_group_ptr, col_blk_ptr), x once, one partial sum written per slot.
-    info->bytes_spmv_part = 6 * h->nnz + 2 * h->S + grp + 4 * (2 * (h->B + 1) + h->NBC + 1) + 4 * h->n_cols + 4 * h->S;
+    info->bytes_spmv_part = (2 + vb) * h->nnz + 2 * h->S + grp + 4 * (2 * (h->B + 1) + h->NBC + 1) + vb * h->n_cols + vb * h->S;
     // combine: partial sum + row_local per slot, stripe index and slot_ptr, y written once.
-    info->bytes_combine = 6 * h->S + 4 * ((h->NBR + 1) + 2 * h->B + 1) + 4 * h->n_rows;
+    info->bytes_combine = (2 + vb) * h->S + 4 * ((h->NBR + 1) + 2 * h->B + 1) + vb * h->n_rows;
     info->build_ms = h->build_ms;
     return HBP_OK;
 }
@@ -257,9 +261,9 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_ROW_LOCAL: src = h->row_local; bytes = 2 * (size_t)h->S; break;
     case HBP_ARRAY_SEG_LEN: src = h->seg_len; bytes = 2 * (size_t)h->S; break;
     case HBP_ARRAY_COL_LOCAL: src = h->col_local; bytes = 2 * (size_t)h->nnz; break;
-    case HBP_ARRAY_DATA: src = h->data; bytes = 4 * (size_t)h->nnz; break;
+    case HBP_ARRAY_DATA: src = h->data; bytes = (size_t)h->value_bytes * (size_t)h->nnz; break;
     case HBP_ARRAY_ADD_SIGN: bytes = 4 * (size_t)h->nnz; break;
-    case HBP_ARRAY_PARTIAL: src = h->partial; bytes = 4 * (size_t)h->S; break;
+    case HBP_ARRAY_PARTIAL: src = h->partial; bytes = (size_t)h->value_bytes * (size_t)h->S; break;
     case HBP_ARRAY_COL_GROUP_PTR: src = h->col_group_ptr; bytes = 4 * (size_t)(h->NBC + 1); break;
     case HBP_ARRAY_COMP_LO: src = h->comp_lo; bytes = 4 * (size_t)h->NBC; break;
     case HBP_ARRAY_FIXED_START: src = h->fixed_start; bytes = 4 * (size_t)(h->P + 1); break;
@@ -290,13 +294,53 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     return HBP_OK;
 }
 
-int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, const float *x, float *y,
-                 int64_t n_rows, void *stream)
+static int csr_any(int32_t value_bytes, int kind, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val, const void *x,
+                   void *y, int64_t n_rows, void *stream)
 {
     if ((kind != 0 && kind != 1) || !csr_ptr || !csr_col || !csr_val || !x || !y || n_rows < 1 ||
         n_rows >= (int64_t(1) << 31) - 1)
         return HBP_ERR_INVALID_ARGUMENT;
-    return hbp::launch_csr(kind, csr_ptr, csr_col, csr_val, x, y, n_rows, (hipStream_t)stream);
+    return hbp::launch_csr(kind, value_bytes, csr_ptr, csr_col, csr_val, x, y, n_rows, (hipStream_t)stream);
+}
+
+int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, int64_t n_rows, int64_t n_cols,
+              const hbp_params_t *params, void *stream, hbp_handle_t *out)
+{
+    return build_any(4, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, out);
+}
+
+int hbp_build_f64(const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val, int64_t n_rows, int64_t n_cols,
+                  const hbp_params_t *params, void *stream, hbp_handle_t *out)
+{
+    return build_any(8, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, out);
+}
+
+int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream) { return spmv_any(4, h, x, y, stream); }
+
+int hbp_spmv_f64(hbp_handle_t h, const double *x, double *y, void *stream) { return spmv_any(8, h, x, y, stream); }
+
+int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters, float *ms_part, float *ms_combine,
+                   float *ms_total)
+{
+    return spmv_timed_any(4, h, x, y, stream, iters, ms_part, ms_combine, ms_total);
+}
+
+int hbp_spmv_timed_f64(hbp_handle_t h, const double *x, double *y, void *stream, int iters, float *ms_part, float *ms_combine,
+                       float *ms_total)
+{
+    return spmv_timed_any(8, h, x, y, stream, iters, ms_part, ms_combine, ms_total);
+}
+
+int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val, const float *x, float *y,
+                 int64_t n_rows, void *stream)
+{
+    return csr_any(4, kind, csr_ptr, csr_col, csr_val, x, y, n_rows, stream);
+}
+
+int hbp_csr_spmv_f64(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val, const double *x, double *y,
+                     int64_t n_rows, void *stream)
+{
+    return csr_any(8, kind, csr_ptr, csr_col, csr_val, x, y, n_rows, stream);
 }
 
 const char *hbp_status_string(int status)

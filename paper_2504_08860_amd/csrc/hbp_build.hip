@@ -584,11 +584,12 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
 
 // One wavefront per group.  Round k stores the k-th nonzero of every lane that still has
 // one, lanes in slot order; rows keep their CSR (ascending column) order.
-__global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_col, const float *__restrict__ csr_val,
+template <typename T>
+__global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_col, const T *__restrict__ csr_val,
                                               const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
                                               const int32_t *__restrict__ group_blk, const int32_t *__restrict__ blk_bn,
                                               const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
-                                              int32_t G, int32_t C, uint16_t *__restrict__ col_local, float *__restrict__ data)
+                                              int32_t G, int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
 {
     const int lane = threadIdx.x & 63;
     const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -602,11 +603,11 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
     constexpr int kRounds = 8;
     for (int k = 0; __ballot(k < n); k += kRounds) {
         int32_t c[kRounds];
-        float v[kRounds];
+        T v[kRounds];
 #pragma unroll
         for (int u = 0; u < kRounds; u++) {
             c[u] = 0;
-            v[u] = 0.f;
+            v[u] = T(0);
             if (k + u < n) {
                 c[u] = csr_col[j + k + u];
                 v[u] = csr_val[j + k + u];
@@ -780,8 +781,12 @@ public:
     template <typename T>
     void reserve(T **out, int64_t count)
     {
-        const size_t bytes = ((size_t)(count > 0 ? count : 1) * sizeof(T) + 255) & ~(size_t)255;
-        slots_.push_back({(void **)out, total_});
+        reserve_bytes((void **)out, (int64_t)sizeof(T) * (count > 0 ? count : 1));
+    }
+    void reserve_bytes(void **out, int64_t n_bytes)
+    {
+        const size_t bytes = ((size_t)(n_bytes > 0 ? n_bytes : 1) + 255) & ~(size_t)255;
+        slots_.push_back({out, total_});
         total_ += bytes;
     }
     int commit()
@@ -806,7 +811,7 @@ inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + pe
 
 }  // namespace
 
-int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t st)
 {
     const int64_t n_rows = h->n_rows, n_cols = h->n_cols;
@@ -850,7 +855,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         own1.reserve(&h->blk_bm, 1); own1.reserve(&h->blk_bn, 1); own1.reserve(&h->slot_ptr, 1);
         own1.reserve(&h->blk_group_ptr, 1); own1.reserve(&h->stripe_blk, 1); own1.reserve(&h->group_ptr, 1);
         own1.reserve(&h->group_slot, 1); own1.reserve(&h->group_rounds, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
-        own1.reserve(&h->col_local, 1); own1.reserve(&h->data, 1); own1.reserve(&h->partial, 1);
+        own1.reserve(&h->col_local, 1); own1.reserve_bytes(&h->data, 8); own1.reserve_bytes(&h->partial, 8);
         own1.reserve(&h->unit_stripe, NBR + 1); own1.reserve(&h->unit_k, NBR + 2); own1.reserve(&h->multi_stripes, 1);
         HBP_TRY(own1.commit());
         h->arena[1] = own1.base();
@@ -941,8 +946,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own1.reserve(&h->group_ptr, G + 1); own1.reserve(&h->group_slot, G + 1); own1.reserve(&h->group_rounds, G + 1);
     own1.reserve(&h->row_local, S + 1); own1.reserve(&h->seg_len, S + 1);
     // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
-    own1.reserve(&h->col_local, nnz + 256); own1.reserve(&h->data, nnz + 256);
-    own1.reserve(&h->partial, S + 1);
+    own1.reserve(&h->col_local, nnz + 256); own1.reserve_bytes(&h->data, (nnz + 256) * h->value_bytes);
+    own1.reserve_bytes(&h->partial, (S + 1) * h->value_bytes);
     if (h->unit_slots == 0) {
         // default: only row blocks with more than twice the average number of slots are cut
         const int64_t twice_mean = 2 * ((S + NBR - 1) / NBR);
@@ -992,8 +997,17 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
     // step 7
-    k_fill<<<blocks_for(G, 4), 256, 0, st>>>(csr_col, csr_val, h->group_ptr, h->group_slot, group_blk, h->blk_bn, h->seg_len,
-                                             slot_j, (int32_t)G, C, h->col_local, h->data);
+    // the padding behind the last group is read (and its products dropped) by lanes without an element
+    HBP_HIP(hipMemsetAsync(h->col_local + nnz, 0, 256 * sizeof(uint16_t), st));
+    HBP_HIP(hipMemsetAsync((char *)h->data + (size_t)nnz * h->value_bytes, 0, 256 * (size_t)h->value_bytes, st));
+    if (h->value_bytes == 8)
+        k_fill<double><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const double *>(csr_val), h->group_ptr, h->group_slot,
+                                                         group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                         static_cast<double *>(h->data));
+    else
+        k_fill<float><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const float *>(csr_val), h->group_ptr, h->group_slot,
+                                                        group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                        static_cast<float *>(h->data));
     HBP_HIP(hipGetLastError());
     uint32_t n_units = 0, n_multi = 0, longest = 0;
     HBP_HIP(hipMemcpyAsync(&longest, longest_all, 4, hipMemcpyDeviceToHost, st));

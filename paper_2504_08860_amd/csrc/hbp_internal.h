@@ -11,6 +11,8 @@ namespace hbp {
 constexpr int kWave = 64;            // gfx950 wavefront width
 constexpr int kMaxR = 8192;          // rows per block: one block's slots are ordered in 64 KB of LDS
 constexpr int kMaxC = 32768;         // columns per block: fp32 vector segment of 128 KB in LDS
+constexpr int kMaxC64 = 16384;       // the same 128 KB with fp64 values
+constexpr int kMaxR64 = 4096;        // fp64: the combine part keeps four copies of a y slice in LDS
 constexpr int64_t kMaxDense = int64_t(1) << 27;  // NBR * NBC table entries
 
 // Device-side view of the layout, passed by value to kernels.
@@ -28,7 +30,7 @@ struct Layout {
     int32_t claim;  // competitive groups a worker claims from a column's counter at a time
     int32_t heavy_rounds;  // a group with a longer row is walked by all wavefronts of a worker together
     const uint16_t *row_local, *seg_len, *col_local;
-    const float *data;
+    const void *data;  // float or double, by the handle's value type
 };
 
 }  // namespace hbp
@@ -56,8 +58,9 @@ struct hbp_handle_s {
     int32_t longest_segment;  // longest row segment of the matrix
     int32_t round_weight;  // schedule weight of a group on top of its nonzeros and slots
     uint16_t *row_local, *seg_len, *col_local;
-    float *data;
-    float *partial;      // [S] per-slot partial sums of the SpMV part
+    int32_t value_bytes; // 4: fp32 values (data, partial, x, y), 8: fp64
+    void *data;
+    void *partial;       // [S] per-slot partial sums of the SpMV part
     uint32_t *ticket;    // [NBC] competitive groups of every block column claimed so far, zero between calls
 };
 
@@ -75,17 +78,18 @@ void set_last_hip_error(hipError_t e);
     } while (0)
 
 // build (hbp_build.hip)
-int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
+int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t stream);
 int build_schedule(hbp_handle_s *h, hipStream_t stream);
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
 
 // spmv (hbp_spmv.hip)
 Layout hbp_view(const hbp_handle_s *h);
-int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
-int launch_spmv_part(const hbp_handle_s *h, const float *x, float *y, hipStream_t stream, uint64_t *timeline = nullptr);
-int launch_combine(const hbp_handle_s *h, float *y, hipStream_t stream);
-int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,
+int default_workers(int device, int32_t C, int32_t value_bytes, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
+// x, y (and val): arrays of the handle's value type (value_bytes for the CSR baselines)
+int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t stream, uint64_t *timeline = nullptr);
+int launch_combine(const hbp_handle_s *h, void *y, hipStream_t stream);
+int launch_csr(int kind, int value_bytes, const int32_t *ptr, const int32_t *col, const void *val, const void *x, void *y,
                int64_t n_rows, hipStream_t stream);
 
 }  // namespace hbp

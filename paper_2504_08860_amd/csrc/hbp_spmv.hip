@@ -38,26 +38,27 @@ __device__ __forceinline__ int32_t uniform_load(const int32_t *p, int32_t i)
 // time ("a batch"): the U ballots give each round's live lanes, a lane's element in a round
 // sits at the round's base plus the number of live lanes below it, all 2U loads are issued,
 // then the products are accumulated through the staged vector segment.
-template <int U>
+// T is the value type, float or double.
+template <int U, typename T>
 struct Batch {
     uint32_t c[U];
-    float v[U];
+    T v[U];
     int rounds;  // rounds of the batch in which some lane has a nonzero (they are the leading ones)
 };
 
 // Issues the loads of rounds k .. k+U-1 and advances base past them.  No load is predicated: a
 // lane without an element in a round reads a neighbour's (or the position just behind the
 // round: inside the group, or inside the padding behind the last group) and drops the product.
-template <int U>
-__device__ __forceinline__ void issue_batch(Batch<U> &b, const uint16_t *__restrict__ col_local,
-                                            const float *__restrict__ data, uint32_t &base, int32_t n, int32_t k)
+template <int U, typename T>
+__device__ __forceinline__ void issue_batch(Batch<U, T> &b, const uint16_t *__restrict__ col_local,
+                                            const T *__restrict__ data, uint32_t &base, int32_t n, int32_t k)
 {
     b.rounds = 0;
 #pragma unroll
     for (int u = 0; u < U; u++) {
         const uint64_t live = __ballot(k + u < n);
         b.c[u] = 0;
-        b.v[u] = 0.f;
+        b.v[u] = T(0);
         if (live) {  // wave-uniform: rounds past every row's end issue nothing
             const uint32_t j = (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)live, base));
@@ -72,33 +73,33 @@ __device__ __forceinline__ void issue_batch(Batch<U> &b, const uint16_t *__restr
 // Products of the batch, summed per lane.  QUARTERS: the batch is taken in four quarters and a
 // quarter without a nonzero is skipped (deep batches behind a group's first one are mostly
 // empty when the rows are only a little longer than the first batch).
-template <int U, bool QUARTERS = false>
-__device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *xs, int32_t n, int32_t k)
+template <int U, bool QUARTERS = false, typename T>
+__device__ __forceinline__ T consume_batch(const Batch<U, T> &b, const T *xs, int32_t n, int32_t k)
 {
-    float acc = 0.f;
+    T acc = T(0);
     if constexpr (QUARTERS) {
         constexpr int Q = U / 4;
 #pragma unroll
         for (int q0 = 0; q0 < U; q0 += Q) {
             if (q0 < b.rounds) {  // wave-uniform
-                float xv[Q];
+                T xv[Q];
 #pragma unroll
                 for (int u = 0; u < Q; u++) xv[u] = xs[b.c[q0 + u]];
 #pragma unroll
                 for (int u = 0; u < Q; u++) {
-                    const float p = b.v[q0 + u] * xv[u];
-                    acc += k + q0 + u < n ? p : 0.f;
+                    const T p = b.v[q0 + u] * xv[u];
+                    acc += k + q0 + u < n ? p : T(0);
                 }
             }
         }
     } else {
-        float xv[U];
+        T xv[U];
 #pragma unroll
         for (int u = 0; u < U; u++) xv[u] = xs[b.c[u]];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const float p = b.v[u] * xv[u];
-            acc += k + u < n ? p : 0.f;
+            const T p = b.v[u] * xv[u];
+            acc += k + u < n ? p : T(0);
         }
     }
     return acc;
@@ -106,48 +107,51 @@ __device__ __forceinline__ float consume_batch(const Batch<U> &b, const float *x
 
 // Fast path for a full group whose 64 rows all have the same length n0 >= 4: its nonzeros are
 // one contiguous run of 64 n0 elements in which element o belongs to the row of lane o mod 64.
-// The run is read in 256-element chunks aligned to 1 KB (data) / 512 B (columns), four
-// consecutive elements per lane with one 16-byte and one 8-byte load.  With d = distance from
+// The run is read in 256-element chunks aligned to 1 KB (fp32 data) / 512 B (columns), four
+// consecutive elements per lane with one 16-byte (fp64: 32-byte) and one 8-byte load.  With d = distance from
 // the first chunk's start to the run, lane l's j-th element of every chunk belongs to the row
 // of lane (4 l + j - d) mod 64, so a lane keeps four running sums and no shuffle is needed
 // until the end, when the four lanes l, l^16, l^32, l^48 that serve the same rows are added.
 // Lanes whose four elements lie outside the run load nothing; elements outside the run that
 // share a 16-byte quad with it are read but contribute nothing.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+struct Vec4 {
+    typedef T type __attribute__((ext_vector_type(4)));
+};
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <int CH>
+template <int CH, typename T>
 struct WideBatch {
-    f32x4 v[CH];
+    typename Vec4<T>::type v[CH];
     u32x2 c[CH];
 };
 
 // FIRST: the chunks start at the run's first chunk; only that one can hold elements in front of
 // the run, so the other chunks are tested against the run's end alone.
-template <int CH, bool FIRST = true>
-__device__ __forceinline__ void issue_wide(WideBatch<CH> &b, const uint16_t *__restrict__ col_local,
-                                           const float *__restrict__ data, uint32_t chunk0, uint32_t i0, uint32_t run_begin,
+template <int CH, bool FIRST = true, typename T>
+__device__ __forceinline__ void issue_wide(WideBatch<CH, T> &b, const uint16_t *__restrict__ col_local,
+                                           const T *__restrict__ data, uint32_t chunk0, uint32_t i0, uint32_t run_begin,
                                            uint32_t run_end, int lane)
 {
 #pragma unroll
     for (int u = 0; u < CH; u++) {
         const uint32_t p = chunk0 + 256u * (i0 + u) + 4u * (uint32_t)lane;
-        b.v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        b.v[u] = typename Vec4<T>::type{T(0), T(0), T(0), T(0)};
         b.c[u] = u32x2{0u, 0u};
         if ((!(FIRST && u == 0) || p + 3u >= run_begin) && p < run_end) {  // lanes whose four elements miss the run load nothing
-            b.v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(data + p));
+            b.v[u] = __builtin_nontemporal_load(reinterpret_cast<const typename Vec4<T>::type *>(data + p));
             b.c[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(col_local + p));
         }
     }
 }
 
-template <int CH, bool FIRST = true>
-__device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float *xs, uint32_t chunk0, uint32_t i0,
-                                             uint32_t run_begin, uint32_t run_end, int lane, float (&acc)[4])
+template <int CH, bool FIRST = true, typename T>
+__device__ __forceinline__ void consume_wide(const WideBatch<CH, T> &b, const T *xs, uint32_t chunk0, uint32_t i0,
+                                             uint32_t run_begin, uint32_t run_end, int lane, T (&acc)[4])
 {
     uint32_t c[CH][4];
     bool ok[CH][4];
-    float xv[CH][4];
+    T xv[CH][4];
 #pragma unroll
     for (int u = 0; u < CH; u++) {
         const uint32_t p = chunk0 + 256u * (i0 + u) + 4u * (uint32_t)lane;
@@ -165,30 +169,32 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH> &b, const float
         for (int j = 0; j < 4; j++) xv[u][j] = xs[c[u][j]];
 #pragma unroll
     for (int u = 0; u < CH; u++) {
-        const float v[4] = {b.v[u].x, b.v[u].y, b.v[u].z, b.v[u].w};
+        const T v[4] = {b.v[u].x, b.v[u].y, b.v[u].z, b.v[u].w};
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            const float prod = v[j] * xv[u][j];
-            acc[j] += ok[u][j] ? prod : 0.f;
+            const T prod = v[j] * xv[u][j];
+            acc[j] += ok[u][j] ? prod : T(0);
         }
     }
 }
 
-template <int THREADS, int U, int GP, bool HEAVY>
+template <int THREADS, int U, int GP, bool HEAVY, typename T>
 __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
-                                                       const float *__restrict__ x, float *__restrict__ partial,
-                                                       float *__restrict__ y, uint32_t *__restrict__ col_ticket,
+                                                       const T *__restrict__ x, T *__restrict__ partial,
+                                                       T *__restrict__ y, uint32_t *__restrict__ col_ticket,
                                                        uint64_t *__restrict__ dbg)
 {
+    const T *__restrict__ const data = static_cast<const T *>(L.data);
     const uint64_t dbg_t0 = dbg ? wall_clock64() : 0;
     uint64_t dbg_stage = 0, dbg_fixed_end = 0;
-    extern __shared__ float xs[];  // the staged vector segment, C floats
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    T *const xs = reinterpret_cast<T *>(dyn_lds);  // the staged vector segment, C values
     __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
     __shared__ unsigned long long sh_rng;  // groups of the worker still to draw: end << 32 | next
     __shared__ int32_t sh_dry;   // nothing more to claim from the current block column
     __shared__ int32_t sh_lock;  // end of the last range reported as used up
     __shared__ int32_t sh_col[3];  // the current block column, its first competitive group, its end
-    __shared__ float sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
+    __shared__ T sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
     constexpr int kHeavyCap = 64;
     __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
     __shared__ int32_t sh_heavy_n;
@@ -216,22 +222,24 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         const int64_t c0 = (int64_t)bn * L.C;
         const int32_t width = (int32_t)min((int64_t)L.C, L.n_cols - c0);
         // 16-byte loads, eight in flight per thread, when the slice is 16-byte aligned
-        const float *src = x + c0;
-        const int32_t n4 = (reinterpret_cast<uintptr_t>(src) & 15u) == 0 ? width >> 2 : 0;
+        typedef T vec16 __attribute__((ext_vector_type(16 / sizeof(T))));
+        constexpr int32_t kPer = 16 / (int32_t)sizeof(T);
+        const T *src = x + c0;
+        const int32_t n4 = (reinterpret_cast<uintptr_t>(src) & 15u) == 0 ? width / kPer : 0;
         for (int32_t i0 = 0; i0 < n4; i0 += THREADS * 8) {
-            f32x4 t[8];
+            vec16 t[8];
 #pragma unroll
             for (int u = 0; u < 8; u++) {
                 const int32_t i = min(i0 + u * THREADS + (int32_t)threadIdx.x, n4 - 1);
-                t[u] = reinterpret_cast<const f32x4 *>(src)[i];
+                t[u] = reinterpret_cast<const vec16 *>(src)[i];
             }
 #pragma unroll
             for (int u = 0; u < 8; u++) {
                 const int32_t i = i0 + u * THREADS + (int32_t)threadIdx.x;
-                if (i < n4) reinterpret_cast<f32x4 *>(xs)[i] = t[u];
+                if (i < n4) reinterpret_cast<vec16 *>(xs)[i] = t[u];
             }
         }
-        for (int32_t i = 4 * n4 + threadIdx.x; i < width; i += THREADS) xs[i] = src[i];
+        for (int32_t i = kPer * n4 + threadIdx.x; i < width; i += THREADS) xs[i] = src[i];
     };
 
     // The wavefronts of the worker share out the groups [*, g_end) of the current range by
@@ -319,7 +327,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     };
     // Rounds k, k+1, ... of one group until no lane has a nonzero left (lane q has n; `base` is
     // the position of round k), added into acc.
-    auto walk_rounds = [&](uint32_t &base, int32_t n, int32_t k, float &acc) __attribute__((always_inline)) {
+    auto walk_rounds = [&](uint32_t &base, int32_t n, int32_t k, T &acc) __attribute__((always_inline)) {
         for (;;) {
             const uint64_t live = __ballot(k < n);
             if (!live) break;
@@ -327,8 +335,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             if (m > 32 || __ballot(k + 2 * U < n) != live) {
                 // many rows still going, or one of them ends soon: a deep batch of rounds
                 constexpr int UL = 16;
-                Batch<UL> deep;
-                issue_batch<UL>(deep, L.col_local, L.data, base, n, k);
+                Batch<UL, T> deep;
+                issue_batch<UL>(deep, L.col_local, data, base, n, k);
                 acc += consume_batch<UL, true>(deep, xs, n, k);
                 k += UL;
                 continue;
@@ -344,23 +352,23 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             for (int d = 32; d > 0; d >>= 1) k_end = min(k_end, __shfl_xor(k_end, d));
             const uint32_t span = (uint32_t)m * (uint32_t)(k_end - k);
             const uint32_t S = (64u / (uint32_t)m) * (uint32_t)m;
-            float sum = 0.f;
+            T sum = T(0);
             if ((uint32_t)lane < S) {
                 uint32_t o = (uint32_t)lane;
                 for (; o + 3u * S < span; o += 4u * S) {
                     uint32_t c4[4];
-                    float v4[4];
+                    T v4[4];
 #pragma unroll
                     for (int u = 0; u < 4; u++) {
                         c4[u] = __builtin_nontemporal_load(L.col_local + base + o + u * S);
-                        v4[u] = __builtin_nontemporal_load(L.data + base + o + u * S);
+                        v4[u] = __builtin_nontemporal_load(data + base + o + u * S);
                     }
 #pragma unroll
                     for (int u = 0; u < 4; u++) sum += v4[u] * xs[c4[u]];
                 }
-                for (; o < span; o += S) sum += L.data[base + o] * xs[L.col_local[base + o]];
+                for (; o < span; o += S) sum += data[base + o] * xs[L.col_local[base + o]];
             }
-            float *hand = sh_hand + wave * 64;
+            T *hand = sh_hand + wave * 64;
             hand[lane] = sum;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -392,13 +400,13 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         unsigned long long raw2 = draw_issue();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
         uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
-        float done_acc[GP];
+        T done_acc[GP];
 #pragma unroll
         for (int q = 0; q < GP; q++) {
             s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
             base[q] = basen[q] = 0;
             done_slot[q] = -1;
-            done_acc[q] = 0.f;
+            done_acc[q] = T(0);
             if (in_pack(g, e, q)) {
                 s0[q] = uniform_load(L.group_slot, g + q);
                 s1[q] = uniform_load(L.group_slot, g + q + 1);
@@ -440,7 +448,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             }
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
             uint32_t basenn[GP];
-            float acc[GP];
+            T acc[GP];
 #pragma unroll
             for (int q = 0; q < GP; q++) {
                 s0nn[q] = s1nn[q] = nn[q] = 0;
@@ -460,14 +468,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     constexpr int CH = 4;
                     const uint32_t chunk0 = base[0] & ~255u, run_end = base[0] + 64u * (uint32_t)n0;
                     const uint32_t n_chunks = (run_end - chunk0 + 255u) >> 8;
-                    float a4[4] = {0.f, 0.f, 0.f, 0.f};
-                    WideBatch<CH> wb;
-                    issue_wide<CH>(wb, L.col_local, L.data, chunk0, 0, base[0], run_end, lane);
+                    T a4[4] = {T(0), T(0), T(0), T(0)};
+                    WideBatch<CH, T> wb;
+                    issue_wide<CH>(wb, L.col_local, data, chunk0, 0, base[0], run_end, lane);
                     if (done_slot[0] >= 0) partial[done_slot[0]] = done_acc[0];
                     nn[0] = s0n[0] + lane < s1n[0] ? L.seg_len[s0n[0] + lane] : 0;
                     consume_wide<CH>(wb, xs, chunk0, 0, base[0], run_end, lane, a4);
                     for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
-                        issue_wide<CH, false>(wb, L.col_local, L.data, chunk0, i0, base[0], run_end, lane);
+                        issue_wide<CH, false>(wb, L.col_local, data, chunk0, i0, base[0], run_end, lane);
                         consume_wide<CH, false>(wb, xs, chunk0, i0, base[0], run_end, lane, a4);
                     }
 #pragma unroll
@@ -482,9 +490,9 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             }
             if (!wide) {
                 // general groups: round by round, U rounds per batch
-                Batch<U> bt[GP];
+                Batch<U, T> bt[GP];
 #pragma unroll
-                for (int q = 0; q < GP; q++) issue_batch<U>(bt[q], L.col_local, L.data, base[q], n[q], 0);
+                for (int q = 0; q < GP; q++) issue_batch<U>(bt[q], L.col_local, data, base[q], n[q], 0);
 #pragma unroll
                 for (int q = 0; q < GP; q++) {
                     if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
@@ -560,12 +568,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             __syncthreads();
             const int32_t k_lo = sh_cut_k[wave], k_hi = sh_cut_k[wave + 1];
             uint32_t pos = b0 + sh_cut_pos[wave];
-            float sum = 0.f;
+            T sum = T(0);
             walk_rounds(pos, min(len, k_hi), k_lo, sum);
             sh_hand[threadIdx.x] = sum;
             __syncthreads();
             if (wave == 0 && hs0 + lane < hs1) {
-                float total_sum = sh_hand[lane];
+                T total_sum = sh_hand[lane];
 #pragma unroll
                 for (int w = 1; w < kWaves; w++) total_sum += sh_hand[w * 64 + lane];
                 partial[hs0 + lane] = total_sum;
@@ -658,7 +666,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     for (int32_t ms = (int32_t)blockIdx.x; ms < L.NM; ms += n_workers) {
         const int64_t r0 = (int64_t)L.multi_stripes[ms] * L.R;
         const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
-        for (int32_t r = threadIdx.x; r < rows; r += THREADS) y[r0 + r] = 0.f;
+        for (int32_t r = threadIdx.x; r < rows; r += THREADS) y[r0 + r] = T(0);
     }
     if (dbg && lane == 0) {
         uint64_t *o = dbg + ((size_t)blockIdx.x * kWaves + wave) * 4;
@@ -676,11 +684,12 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 // but run an order of magnitude slower on this hardware.)  The copies are summed on the way out.
 // Also re-arms the per-column ticket counters for the next call (the SpMV part of this call
 // has finished: same stream).
-template <int THREADS, bool DEEP>
-__global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__restrict__ partial, float *__restrict__ y,
+template <int THREADS, bool DEEP, typename T>
+__global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restrict__ partial, T *__restrict__ y,
                                                      uint32_t *__restrict__ ticket)
 {
-    extern __shared__ float ys_all[];  // kWaves copies of R floats
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    T *const ys_all = reinterpret_cast<T *>(dyn_lds);  // kWaves copies of R values
     constexpr int kPass = 128, kWaves = THREADS / 64;
     __shared__ int32_t range[2 * kPass];
     // One workgroup per combine unit: entries [unit_k[j], unit_k[j + 1]) of stripe_blk, all of row
@@ -692,10 +701,10 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
     for (int64_t i = (int64_t)unit * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
     const int64_t r0 = (int64_t)bm * L.R;
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
-    for (int32_t i = threadIdx.x; i < kWaves * L.R; i += THREADS) ys_all[i] = 0.f;
+    for (int32_t i = threadIdx.x; i < kWaves * L.R; i += THREADS) ys_all[i] = T(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float *ys = ys_all + wave * L.R;
+    T *ys = ys_all + wave * L.R;
     const int32_t k1 = L.unit_k[unit + 1];
     for (int32_t k0 = L.unit_k[unit]; k0 < k1; k0 += kPass) {
         const int32_t nb = min(kPass, k1 - k0);
@@ -715,7 +724,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
                 constexpr int KU = decltype(ku)::value;
                 for (int32_t s = range[2 * i] + lane; s < s1; s += 64 * KU) {
                     uint32_t r[KU];
-                    float p[KU], o[KU];
+                    T p[KU], o[KU];
 #pragma unroll
                     for (int u = 0; u < KU; u++) {
                         const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
@@ -737,7 +746,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
     }
     __syncthreads();
     for (int32_t i = threadIdx.x; i < rows; i += THREADS) {
-        float sum = ys_all[i];
+        T sum = ys_all[i];
 #pragma unroll
         for (int w = 1; w < kWaves; w++) sum += ys_all[w * L.R + i];
         if (split) atomicAdd(&y[r0 + i], sum);
@@ -747,25 +756,27 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const float *__re
 
 // ------------------------------------------------------------------ CSR baselines (Algorithm 1)
 
+template <typename T>
 __global__ __launch_bounds__(256) void k_csr_scalar(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
-                                                    const float *__restrict__ val, const float *__restrict__ x,
-                                                    float *__restrict__ y, int64_t n_rows)
+                                                    const T *__restrict__ val, const T *__restrict__ x,
+                                                    T *__restrict__ y, int64_t n_rows)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n_rows) return;
-    float sum = 0.f;
+    T sum = T(0);
     for (int32_t j = ptr[i]; j < ptr[i + 1]; j++) sum += val[j] * x[col[j]];
     y[i] = sum;
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void k_csr_vector(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
-                                                    const float *__restrict__ val, const float *__restrict__ x,
-                                                    float *__restrict__ y, int64_t n_rows)
+                                                    const T *__restrict__ val, const T *__restrict__ x,
+                                                    T *__restrict__ y, int64_t n_rows)
 {
     const int lane = threadIdx.x & 63;
     const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= n_rows) return;
-    float sum = 0.f;
+    T sum = T(0);
     for (int32_t j = ptr[i] + lane; j < ptr[i + 1]; j += 64) sum += val[j] * x[col[j]];
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d);
@@ -797,12 +808,12 @@ Layout hbp_view(const hbp_handle_s *h)
 
 // Workers the schedule is built for when the caller does not say: as many workgroups as fit
 // on the device at once given the LDS a vector segment takes.
-int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out)
+int default_workers(int device, int32_t C, int32_t value_bytes, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out)
 {
     hipDeviceProp_t prop;
     HBP_HIP(hipGetDeviceProperties(&prop, device));
     const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    const size_t lds = (size_t)C * sizeof(float) + 64;
+    const size_t lds = (size_t)C * (size_t)value_bytes + 64;
     const int threads = threads_wanted ? threads_wanted : (lds > 80 * 1024 ? 1024 : 512);
     int per_cu = (int)((160 * 1024) / lds);
     const int by_threads = 2048 / threads;
@@ -813,73 +824,99 @@ int default_workers(int device, int32_t C, int32_t threads_wanted, int32_t *thre
     return HBP_OK;
 }
 
-template <int THREADS, int U, int GP, bool HEAVY>
-static int launch_part(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
+template <int THREADS, int U, int GP, bool HEAVY, typename T>
+static int launch_part(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st, uint64_t *dbg)
 {
-    const size_t lds = (size_t)h->C * sizeof(float);
+    const size_t lds = (size_t)h->C * sizeof(T);
     static int configured_device = -1;  // raise the dynamic-LDS cap once per device and instantiation
     if (configured_device != h->device) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U, GP, HEAVY>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kMaxC * (int)sizeof(float)));
+        HBP_HIP(hipFuncSetAttribute((const void *)k_spmv_part<THREADS, U, GP, HEAVY, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kMaxC * (int)sizeof(float)));  // 128 KB: kMaxC floats or kMaxC64 doubles
         configured_device = h->device;
     }
-    k_spmv_part<THREADS, U, GP, HEAVY><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, h->partial, y, h->ticket, dbg);
+    k_spmv_part<THREADS, U, GP, HEAVY, T><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, static_cast<T *>(h->partial), y, h->ticket, dbg);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
-template <int THREADS, bool HEAVY>
-static int launch_part_u(const hbp_handle_s *h, const Layout &L, const float *x, float *y, hipStream_t st, uint64_t *dbg)
+template <int THREADS, bool HEAVY, typename T>
+static int launch_part_u(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st, uint64_t *dbg)
 {
     switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
-    case 2: return launch_part<THREADS, 2, 8, HEAVY>(h, L, x, y, st, dbg);
-    case 4: return launch_part<THREADS, 4, 4, HEAVY>(h, L, x, y, st, dbg);
-    case 9: return launch_part<THREADS, 9, 1, HEAVY>(h, L, x, y, st, dbg);
-    case 16: return launch_part<THREADS, 16, 1, HEAVY>(h, L, x, y, st, dbg);
-    default: return launch_part<THREADS, 8, 1, HEAVY>(h, L, x, y, st, dbg);
+    case 2: return launch_part<THREADS, 2, 8, HEAVY, T>(h, L, x, y, st, dbg);
+    case 4: return launch_part<THREADS, 4, 4, HEAVY, T>(h, L, x, y, st, dbg);
+    case 9: return launch_part<THREADS, 9, 1, HEAVY, T>(h, L, x, y, st, dbg);
+    case 16: return launch_part<THREADS, 16, 1, HEAVY, T>(h, L, x, y, st, dbg);
+    default: return launch_part<THREADS, 8, 1, HEAVY, T>(h, L, x, y, st, dbg);
     }
 }
 
-int launch_spmv_part(const hbp_handle_s *h, const float *x, float *y, hipStream_t st, uint64_t *dbg)
+template <typename T>
+static int launch_part_t(const hbp_handle_s *h, const T *x, T *y, hipStream_t st, uint64_t *dbg)
 {
     const Layout L = hbp_view(h);
     // the kernel that can share heavy groups among a worker's wavefronts only where the matrix has one
     if (h->longest_segment > h->heavy_rounds) {
-        if (h->threads == 1024) return launch_part_u<1024, true>(h, L, x, y, st, dbg);
-        if (h->threads == 512) return launch_part_u<512, true>(h, L, x, y, st, dbg);
-        return launch_part_u<256, true>(h, L, x, y, st, dbg);
+        if (h->threads == 1024) return launch_part_u<1024, true, T>(h, L, x, y, st, dbg);
+        if (h->threads == 512) return launch_part_u<512, true, T>(h, L, x, y, st, dbg);
+        return launch_part_u<256, true, T>(h, L, x, y, st, dbg);
     }
-    if (h->threads == 1024) return launch_part_u<1024, false>(h, L, x, y, st, dbg);
-    if (h->threads == 512) return launch_part_u<512, false>(h, L, x, y, st, dbg);
-    return launch_part_u<256, false>(h, L, x, y, st, dbg);
+    if (h->threads == 1024) return launch_part_u<1024, false, T>(h, L, x, y, st, dbg);
+    if (h->threads == 512) return launch_part_u<512, false, T>(h, L, x, y, st, dbg);
+    return launch_part_u<256, false, T>(h, L, x, y, st, dbg);
 }
 
-int launch_combine(const hbp_handle_s *h, float *y, hipStream_t st)
+int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t st, uint64_t *dbg)
+{
+    if (h->value_bytes == 8) return launch_part_t<double>(h, static_cast<const double *>(x), static_cast<double *>(y), st, dbg);
+    return launch_part_t<float>(h, static_cast<const float *>(x), static_cast<float *>(y), st, dbg);
+}
+
+template <typename T>
+static int launch_combine_t(const hbp_handle_s *h, T *y, hipStream_t st)
 {
     const Layout L = hbp_view(h);
     static int configured_device = -1;
     if (configured_device != h->device) {
-        HBP_HIP(hipFuncSetAttribute((const void *)k_combine<256, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    4 * kMaxR * (int)sizeof(float)));
+        HBP_HIP(hipFuncSetAttribute((const void *)k_combine<256, true, T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    4 * kMaxR * (int)sizeof(float)));  // 128 KB: kMaxR floats or kMaxR64 doubles, four copies
         configured_device = h->device;
     }
+    const T *partial = static_cast<const T *>(h->partial);
     if (h->R <= 1024)
-        k_combine<128, false><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<128, false, T><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, h->ticket);
     else
-        k_combine<256, true><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(float), st>>>(L, h->partial, y, h->ticket);
+        k_combine<256, true, T><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, h->ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
-int launch_csr(int kind, const int32_t *ptr, const int32_t *col, const float *val, const float *x, float *y,
-               int64_t n_rows, hipStream_t st)
+int launch_combine(const hbp_handle_s *h, void *y, hipStream_t st)
+{
+    if (h->value_bytes == 8) return launch_combine_t<double>(h, static_cast<double *>(y), st);
+    return launch_combine_t<float>(h, static_cast<float *>(y), st);
+}
+
+template <typename T>
+static int launch_csr_t(int kind, const int32_t *ptr, const int32_t *col, const T *val, const T *x, T *y, int64_t n_rows,
+                        hipStream_t st)
 {
     if (kind == 0)
-        k_csr_scalar<<<dim3((unsigned)((n_rows + 255) / 256)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
+        k_csr_scalar<T><<<dim3((unsigned)((n_rows + 255) / 256)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
     else
-        k_csr_vector<<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
+        k_csr_vector<T><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
+}
+
+int launch_csr(int kind, int value_bytes, const int32_t *ptr, const int32_t *col, const void *val, const void *x, void *y,
+               int64_t n_rows, hipStream_t st)
+{
+    if (value_bytes == 8)
+        return launch_csr_t<double>(kind, ptr, col, static_cast<const double *>(val), static_cast<const double *>(x),
+                                    static_cast<double *>(y), n_rows, st);
+    return launch_csr_t<float>(kind, ptr, col, static_cast<const float *>(val), static_cast<const float *>(x),
+                               static_cast<float *>(y), n_rows, st);
 }
 
 }  // namespace hbp

@@ -9,6 +9,9 @@ from workloads import make_config, random_csr, worked_example_8x8
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
+# fp64 handles: the same multiple (168) of the unit roundoff as 1e-5 is of fp32's; the reference
+# is accumulated in extended precision and rounded once
+TOL_F64 = 168 * 2.0**-53
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
                  "group_ptr", "group_slot", "group_rounds", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col",
                  "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
@@ -32,8 +35,11 @@ def to_dev(m):
 def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
     import torch
     ptr, col, val, x = to_dev(m)
-    print(f"[case] {m.name} rows={m.n_rows} cols={m.n_cols} nnz={m.nnz} params={params}", flush=True)
-    h = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, **params)
+    f64 = m.val.dtype == np.float64
+    tol = TOL_F64 if f64 else TOL
+    build, spmv = (H.hbp_build_f64, H.hbp_spmv_f64) if f64 else (H.hbp_build, H.hbp_spmv)
+    print(f"[case] {m.name} rows={m.n_rows} cols={m.n_cols} nnz={m.nnz} {m.val.dtype} params={params}", flush=True)
+    h = build(ptr, col, val, m.n_rows, m.n_cols, **params)
     try:
         info = H.hbp_get_info(h)
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
@@ -42,7 +48,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
                              round_weight=info.round_weight, group_weight=info.group_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
-        assert info.hash_shift == o.a
+        assert info.hash_shift == o.a and info.value_bytes == m.val.dtype.itemsize
         assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
         assert info.hash_b == max(1, info.rows_per_block // 9)
         for name in LAYOUT_ARRAYS:
@@ -50,17 +56,19 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
                 continue
             got, want = H.hbp_export(h, name), o.array(name)
             if name == "data":
-                got, want = got.view(np.uint32), want.view(np.uint32)
+                assert got.dtype == want.dtype == m.val.dtype
+                bits = np.uint64 if f64 else np.uint32
+                got, want = got.view(bits), want.view(bits)
             assert got.shape == want.shape, name
             assert np.array_equal(got, want), f"{name} differs at {np.flatnonzero(got != want)[:5]}"
         y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
-        y = torch.full((m.n_rows,), float("nan"), device="cuda")
+        y = torch.full((m.n_rows,), float("nan"), device="cuda", dtype=x.dtype)
         for rep in range(2):  # the second call checks that the ticket counter was re-armed
             y.fill_(float("nan"))
-            H.hbp_spmv(h, x, y)
+            spmv(h, x, y)
             torch.cuda.synchronize()
             yh = y.cpu().numpy().astype(np.float64)
-            bad = np.flatnonzero(~(np.abs(yh - y_ref) <= TOL * s_abs))
+            bad = np.flatnonzero(~(np.abs(yh - y_ref) <= tol * s_abs))
             assert bad.size == 0, f"rep {rep}: rows {bad[:5]} y {yh[bad[:5]]} ref {y_ref[bad[:5]]}"
             assert np.all(yh[np.diff(m.ptr) == 0] == 0.0)
         # per-slot partial sums against the oracle's walk through the layout
@@ -68,7 +76,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
         p = H.hbp_export(h, "partial").astype(np.float64)
         slot_row = (np.repeat(o.array("blk_bm"), np.diff(o.array("slot_ptr"))).astype(np.int64) * o.R
                     + o.array("row_local"))
-        assert np.all(np.abs(p - p_ref) <= TOL * s_abs[slot_row])
+        assert np.all(np.abs(p - p_ref) <= tol * s_abs[slot_row])
         o.close()
         return info
     finally:

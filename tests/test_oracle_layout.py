@@ -387,7 +387,8 @@ def test_fp64_storage(oracle):
     assert np.all(np.abs(y - y_ref) <= 1e-13 * s_abs)
     for i in range(0, m.n_rows, 7):
         exact = sum((Fraction(float(m.val[j])) * Fraction(float(m.x[m.col[j]])) for j in range(m.ptr[i], m.ptr[i + 1])), Fraction(0))
-        assert abs(Fraction(float(y_ref[i])) - exact) <= Fraction(1, 10**13) * Fraction(float(s_abs[i])) + Fraction(1, 10**300)
+        # the reference is the exact sum rounded: half an ulp of the result plus extended-precision noise
+        assert abs(Fraction(float(y_ref[i])) - exact) <= Fraction(1, 2**53) * abs(exact) + Fraction(1, 2**60) * Fraction(float(s_abs[i]))
         assert abs(Fraction(float(y[i])) - exact) <= Fraction(1, 10**13) * Fraction(float(s_abs[i])) + Fraction(1, 10**300)
     # the float32 result of the same pattern differs by more than the fp64 bound on most rows
     y32, _ = oracle.csr_spmv_f64(m32.ptr, m32.col, m32.val, m32.x)
