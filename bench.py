@@ -57,6 +57,8 @@ def main() -> int:
     ap.add_argument("--hash-shift", type=int, default=-1)
     ap.add_argument("--round-weight", type=int, default=-1)
     ap.add_argument("--heavy-group-rounds", type=int, default=0)
+    ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
+                    help="value type: f32 is the headline metric; f64 runs the fp64 variant on the same pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-csr", action="store_true")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
@@ -73,13 +75,20 @@ def main() -> int:
 
     import paper_2504_08860_amd as H
     from paper_2504_08860_amd.presets import preset
-    from workloads import make_config
+    from workloads import make_config, widen_to_f64
 
     torch.cuda.set_device(0)
     t0 = time.time()
     m = make_config(args.config, args.scale)
     log(f"[bench] generated {m.name}: {m.n_rows} x {m.n_cols}, nnz {m.nnz} in {time.time() - t0:.1f}s")
-    params = preset(args.config)
+    f64 = args.dtype == "f64"
+    vb = 8 if f64 else 4
+    if f64:
+        m = widen_to_f64(m)
+    hbp_build, hbp_spmv, hbp_spmv_timed, hbp_csr_spmv = (
+        (H.hbp_build_f64, H.hbp_spmv_f64, H.hbp_spmv_timed_f64, H.hbp_csr_spmv_f64) if f64
+        else (H.hbp_build, H.hbp_spmv, H.hbp_spmv_timed, H.hbp_csr_spmv))
+    params = preset(args.config, args.dtype)
     if args.rows_per_block: params["rows_per_block"] = args.rows_per_block
     if args.cols_per_block: params["cols_per_block"] = args.cols_per_block
     if args.num_workers >= 0: params["num_workers"] = args.num_workers
@@ -93,11 +102,11 @@ def main() -> int:
     if args.hash_shift >= 0: params["hash_shift"] = args.hash_shift
     if args.round_weight >= 0: params["round_weight"] = args.round_weight
     if args.heavy_group_rounds: params["heavy_group_rounds"] = args.heavy_group_rounds
-    overridden = params != preset(args.config)
+    overridden = params != preset(args.config, args.dtype) or f64
 
     dev = lambda a: torch.from_numpy(a).cuda()
     ptr, col, val, x = dev(m.ptr), dev(m.col), dev(m.val), dev(m.x)
-    y = torch.empty(m.n_rows, device="cuda")
+    y = torch.empty(m.n_rows, device="cuda", dtype=x.dtype)
     torch.cuda.synchronize()
 
     # preprocessing time (validation off, allocation and synchronisation included)
@@ -108,7 +117,7 @@ def main() -> int:
             H.hbp_free(h)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        h = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, **params)
+        h = hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, **params)
         torch.cuda.synchronize()
         build_ms.append((time.perf_counter() - t0) * 1e3)
     info = H.hbp_get_info(h)
@@ -126,29 +135,29 @@ def main() -> int:
 
     # the timed region: exactly K steps between synchronisations
     for _ in range(args.warmup):
-        H.hbp_spmv(h, x, y)
+        hbp_spmv(h, x, y)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        H.hbp_spmv(h, x, y)
+        hbp_spmv(h, x, y)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # per-kernel durations from HIP events recorded on the launch stream
-    ms_part, ms_comb, ms_call = H.hbp_spmv_timed(h, x, y, max(20, min(args.steps, 200)))
+    ms_part, ms_comb, ms_call = hbp_spmv_timed(h, x, y, max(20, min(args.steps, 200)))
     gflops = 2.0 * m.nnz / (ms_per_step * 1e-3) / 1e9
     # algorithmic bytes of the whole call, as stored: col+data per nonzero, slot/group/block
     # metadata, x once, y once (the partial sums written and re-read are extra traffic, not counted)
-    alg_call = info.bytes_layout + 4 * m.n_cols + 4 * m.n_rows
-    csr_equiv = 8 * m.nnz + 4 * (m.n_rows + 1) + 4 * m.n_cols + 4 * m.n_rows
+    alg_call = info.bytes_layout + vb * m.n_cols + vb * m.n_rows
+    csr_equiv = (4 + vb) * m.nnz + 4 * (m.n_rows + 1) + vb * m.n_cols + vb * m.n_rows
     eff_gbs = alg_call / (ms_per_step * 1e-3) / 1e9
     part_gbs = info.bytes_spmv_part / (ms_part * 1e-3) / 1e9
 
     out = {
-        "metric": "HBP SpMV GFLOP/s (fp32, 2*nnz/t, t = SpMV part + combine)",
+        "metric": f"HBP SpMV GFLOP/s ({'fp64' if f64 else 'fp32'}, 2*nnz/t, t = SpMV part + combine)",
         "value": round(gflops, 2), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"config {args.config}: {m.name}, {m.n_rows}x{m.n_cols}, nnz {m.nnz}"
                                + ("" if args.scale == 1.0 else f" (scale {args.scale})"),
                    "rows_per_block": info.rows_per_block, "cols_per_block": info.cols_per_block,
@@ -173,12 +182,12 @@ def main() -> int:
     if not args.no_csr:
         for kind, name in ((0, "csr_scalar"), (1, "csr_vector")):
             for _ in range(5):
-                H.hbp_csr_spmv(kind, ptr, col, val, x, y)
+                hbp_csr_spmv(kind, ptr, col, val, x, y)
             torch.cuda.synchronize()
             reps = max(5, min(50, args.steps))
             t0 = time.perf_counter()
             for _ in range(reps):
-                H.hbp_csr_spmv(kind, ptr, col, val, x, y)
+                hbp_csr_spmv(kind, ptr, col, val, x, y)
             torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / reps
             out[name] = {"ms": round(ms, 5), "GFLOPs": round(2.0 * m.nnz / (ms * 1e-3) / 1e9, 2),
@@ -197,11 +206,11 @@ def main() -> int:
             var = np.maximum(s2 / cnt - (s1 / cnt) ** 2, 0.0)
             return float(np.sqrt(var).mean())
         plain_params = dict(params, fixed_fraction_q8=256)
-        hp = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, no_reorder=True, **plain_params)
+        hp = hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, no_reorder=True, **plain_params)
         for _ in range(5):
-            H.hbp_spmv(hp, x, y)
+            hbp_spmv(hp, x, y)
         torch.cuda.synchronize()
-        p_part, p_comb, p_call = H.hbp_spmv_timed(hp, x, y, max(5, min(50, args.steps)))
+        p_part, p_comb, p_call = hbp_spmv_timed(hp, x, y, max(5, min(50, args.steps)))
         ms = p_part + p_comb
         out["plain_2d"] = {"ms": round(ms, 5), "ms_spmv_part": round(p_part, 5), "ms_combine": round(p_comb, 5),
                            "GFLOPs": round(2.0 * m.nnz / (ms * 1e-3) / 1e9, 2),
@@ -224,7 +233,7 @@ def main() -> int:
         med = sorted(times)[len(times) // 2]
         out["cpu_baseline"] = {"value": round(2.0 * m.nnz / med / 1e9, 3), "unit": "GFLOP/s", "cores": 1,
                                "kind": "oracle",
-                               "sample": f"whole workload, oracle CSR SpMV (fp64 accumulate) median of {reps} runs; "
+                               "sample": f"whole workload, oracle CSR SpMV ({'extended-precision' if f64 else 'fp64'} accumulate) median of {reps} runs; "
                                          f"oracle HBP build once: {o_build * 1e3:.0f} ms",
                                "host_cpus": os.cpu_count()}
     H.hbp_free(h)

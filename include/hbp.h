@@ -108,7 +108,8 @@ typedef struct {
                                   block column at a time, 1..1024; 0 = default (two draws per wavefront) */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
-                                  (2 and 4 walk 8 and 4 groups at once); 0 = default                 */
+                                  (2 and 4 walk 8 and 4 groups at once; fp64 with 1024 threads: 4 and 2);
+                                  0 = default                                                       */
     int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 0..64; -1 = default 4  */
     int32_t group_weight;      /* schedule weight of a group as such, in nonzeros: 0..4096; -1 = default 0 */
     int32_t combine_unit_slots;/* slots one workgroup of the combine part should get at most: a row block

@@ -715,33 +715,70 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
             range[2 * t + 1] = L.slot_ptr[b + 1];
         }
         __syncthreads();
-        for (int32_t i = wave; i < nb; i += kWaves) {
-            const int32_t s1 = range[2 * i + 1];
-            // KU slots per lane in flight (the kernel is bound by the bytes it has in flight);
-            // the (up to) 64 KU slots of a step are distinct rows of one block: read all, then
-            // write all
-            auto add_block = [&](auto ku) __attribute__((always_inline)) {
-                constexpr int KU = decltype(ku)::value;
-                for (int32_t s = range[2 * i] + lane; s < s1; s += 64 * KU) {
-                    uint32_t r[KU];
-                    T p[KU], o[KU];
+        // A wavefront takes kTogether blocks at a time.  Blocks with few slots are one load deep:
+        // taken one by one, a wavefront would sit through a memory latency per block.  So the
+        // slots of those of the kTogether blocks that have at most 64 kFirst of them are loaded
+        // first; then the blocks are added one after the other (a row occurs once per block but
+        // may occur in several blocks), a larger block with KU slots per lane in flight (the
+        // kernel is bound by the bytes it has in flight).
+        constexpr int kTogether = 4, kFirst = 4;
+        for (int32_t i0 = wave; i0 < nb; i0 += kWaves * kTogether) {
+            int32_t b0[kTogether], b1[kTogether];
+            uint32_t rf[kTogether][kFirst];
+            T pf[kTogether][kFirst];
 #pragma unroll
-                    for (int u = 0; u < KU; u++) {
-                        const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
-                        r[u] = L.row_local[idx];
-                        p[u] = partial[idx];
+            for (int j = 0; j < kTogether; j++) {
+                const int32_t i = i0 + j * kWaves;
+                b0[j] = b1[j] = 0;
+                if (i < nb) { b0[j] = range[2 * i]; b1[j] = range[2 * i + 1]; }
+                const int32_t slots = b1[j] - b0[j];  // 0 for a block that does not exist
+#pragma unroll
+                for (int u = 0; u < kFirst; u++) {
+                    rf[j][u] = 0;
+                    pf[j][u] = T(0);
+                    if (slots > 64 * u && slots <= 64 * kFirst) {  // wave-uniform; clamped: always a slot of this block
+                        const int32_t idx = min(b0[j] + lane + 64 * u, b1[j] - 1);
+                        rf[j][u] = L.row_local[idx];
+                        pf[j][u] = partial[idx];
                     }
-#pragma unroll
-                    for (int u = 0; u < KU; u++) o[u] = ys[r[u]];
-#pragma unroll
-                    for (int u = 0; u < KU; u++)
-                        if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
                 }
-            };
-            const int32_t slots = s1 - range[2 * i];
-            if (DEEP && slots > 512) add_block(std::integral_constant<int, 16>{});
-            else if (DEEP && slots > 256) add_block(std::integral_constant<int, 8>{});
-            else add_block(std::integral_constant<int, 4>{});
+            }
+#pragma unroll
+            for (int j = 0; j < kTogether; j++) {
+                const int32_t s0 = b0[j], s1 = b1[j], slots = s1 - s0;
+                if (slots <= 64 * kFirst) {  // wave-uniform
+                    if (slots <= 0) continue;
+                    // the slots of a step are distinct rows of one block: read all, then write all
+                    T o[kFirst];
+#pragma unroll
+                    for (int u = 0; u < kFirst; u++) o[u] = ys[rf[j][u]];
+#pragma unroll
+                    for (int u = 0; u < kFirst; u++)
+                        if (s0 + lane + 64 * u < s1) ys[rf[j][u]] = o[u] + pf[j][u];
+                    continue;
+                }
+                auto add_block = [&](auto ku) __attribute__((always_inline)) {
+                    constexpr int KU = decltype(ku)::value;
+                    for (int32_t s = s0 + lane; s < s1; s += 64 * KU) {
+                        uint32_t r[KU];
+                        T p[KU], o[KU];
+#pragma unroll
+                        for (int u = 0; u < KU; u++) {
+                            const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
+                            r[u] = L.row_local[idx];
+                            p[u] = partial[idx];
+                        }
+#pragma unroll
+                        for (int u = 0; u < KU; u++) o[u] = ys[r[u]];
+#pragma unroll
+                        for (int u = 0; u < KU; u++)
+                            if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
+                    }
+                };
+                if (DEEP && slots > 512) add_block(std::integral_constant<int, 16>{});
+                else if (DEEP) add_block(std::integral_constant<int, 8>{});
+                else add_block(std::integral_constant<int, 4>{});
+            }
         }
     }
     __syncthreads();
@@ -842,9 +879,11 @@ static int launch_part(const hbp_handle_s *h, const Layout &L, const T *x, T *y,
 template <int THREADS, bool HEAVY, typename T>
 static int launch_part_u(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st, uint64_t *dbg)
 {
+    // fp64 at 1024 threads (128 registers per lane): half as many groups at once, or the batches spill
+    constexpr int kHalf = sizeof(T) == 8 && THREADS == 1024 ? 2 : 1;
     switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
-    case 2: return launch_part<THREADS, 2, 8, HEAVY, T>(h, L, x, y, st, dbg);
-    case 4: return launch_part<THREADS, 4, 4, HEAVY, T>(h, L, x, y, st, dbg);
+    case 2: return launch_part<THREADS, 2, 8 / kHalf, HEAVY, T>(h, L, x, y, st, dbg);
+    case 4: return launch_part<THREADS, 4, 4 / kHalf, HEAVY, T>(h, L, x, y, st, dbg);
     case 9: return launch_part<THREADS, 9, 1, HEAVY, T>(h, L, x, y, st, dbg);
     case 16: return launch_part<THREADS, 16, 1, HEAVY, T>(h, L, x, y, st, dbg);
     default: return launch_part<THREADS, 8, 1, HEAVY, T>(h, L, x, y, st, dbg);

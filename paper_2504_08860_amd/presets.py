@@ -14,5 +14,13 @@ PRESETS = {
 }
 
 
-def preset(config_number: int) -> dict:
-    return dict(PRESETS[config_number])
+def preset(config_number: int, dtype: str = "f32") -> dict:
+    """Parameters for workload ``config_number``; ``dtype`` "f64" gives those of the fp64 variant."""
+    p = dict(PRESETS[config_number])
+    if dtype == "f64":
+        # the vector segment of a block column has to fit the same 128 KB of LDS; with twice as
+        # many block columns the R-MAT matrix runs best without a competitive part
+        p["cols_per_block"] = min(p["cols_per_block"], 16384)
+        if config_number == 4:
+            p["fixed_fraction_q8"] = 256
+    return p
