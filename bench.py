@@ -217,6 +217,18 @@ def main() -> int:
                            "hbp_speedup": round(ms / (ms_part + ms_comb), 3),
                            "group_len_std": {"hbp": round(group_len_std(h), 4), "plain_2d": round(group_len_std(hp), 4)}}
         H.hbp_free(hp)
+        # hash study (Section 5's outlook): the same schedule and kernels with the rows of a block
+        # ordered by their length itself, which no hash of the length can improve on
+        hl = hbp_build(ptr, col, val, m.n_rows, m.n_cols, validate=False, key_length=True, **params)
+        for _ in range(5):
+            hbp_spmv(hl, x, y)
+        torch.cuda.synchronize()
+        l_part, l_comb, l_call = hbp_spmv_timed(hl, x, y, max(5, min(50, args.steps)))
+        out["length_key"] = {"ms": round(l_part + l_comb, 5), "ms_spmv_part": round(l_part, 5), "ms_combine": round(l_comb, 5),
+                             "speedup_over_hbp": round((ms_part + ms_comb) / (l_part + l_comb), 3),
+                             "group_len_std": round(group_len_std(hl), 4),
+                             "groups": H.hbp_get_info(hl).groups}
+        H.hbp_free(hl)
 
     if not args.no_cpu_baseline:
         import oracle

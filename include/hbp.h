@@ -92,6 +92,10 @@ typedef enum {
 #define HBP_FLAG_VALIDATE 1u /* check column order/range of the CSR input during the build */
 #define HBP_FLAG_NO_REORDER 2u /* plain 2D partitioning, the method Section 4 compares HBP with: no hash
                                   reorder, the slots of a block stay in ascending row order */
+#define HBP_FLAG_KEY_LENGTH 4u /* hash study (Section 5 names the hash function as open to improvement): the
+                                  key of a row is its length inside the block itself instead of the hash of
+                                  it, i.e. the limit of an ever finer mapping: slots in ascending (length,
+                                  row) order.  Ignored with HBP_FLAG_NO_REORDER. */
 
 /* Build parameters.  Block sizes follow Section 3.1 (the paper derives 4096 columns from
  * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is

@@ -210,7 +210,10 @@ void oracle_hbp_free(oracle_hbp *h)
 }
 
 /* Build the compact layout.  hash_shift = -1 samples a; hash_shift = -2 also switches the reorder off (the plain
- * 2D-partitioning method the paper compares with in Section 4: slots of a block in ascending row order).
+ * 2D-partitioning method the paper compares with in Section 4: slots of a block in ascending row order);
+ * hash_shift = -3 replaces the hash key by the row's length inside the block itself (the limit of an ever finer
+ * linear mapping, Section 5's "room for improvement in the hash function": rows of a block in ascending
+ * (length, row) order, which no hash of the length can improve on).
  * num_workers P and fixed_q8 (share of the work pre-assigned, in 1/256) define the schedule arrays.
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void *val, int32_t value_bytes, int64_t n_rows, int64_t n_cols,
@@ -223,6 +226,9 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
     h->R = R; h->C = C; h->W = W;
     h->a = hash_shift >= 0 ? hash_shift : oracle_sample_shift(ptr, col, n_rows, C);
     const int plain = hash_shift == -2;  /* plain 2D partition: no reorder, every row gets key 0 */
+    const int by_length = hash_shift == -3;  /* key = length of the row inside the block (at most C < 65536) */
+    const int64_t n_keys = by_length ? 65536 : R;
+#define ORACLE_KEY(n) (plain ? 0u : by_length ? (uint32_t)(n) : oracle_hash_key((uint32_t)(n), h->a, R))
     int64_t NBR = (n_rows + R - 1) / R, NBC = (n_cols + C - 1) / C;
     h->NBR = NBR; h->NBC = NBC;
 
@@ -273,19 +279,22 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
     h->row_local = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(S + 1));
     h->seg_len = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(S + 1));
     int32_t *slot_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S + 1));
-    int64_t *table = (int64_t *)malloc(sizeof(int64_t) * (size_t)(R + 1));
+    int64_t *table = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_keys + 1));
     for (int64_t b = 0; b < B; b++) {
         int64_t s0 = h->slot_ptr[b], s1 = h->slot_ptr[b + 1];
-        memset(table, 0, sizeof(int64_t) * (size_t)(R + 1));
-        for (int64_t s = s0; s < s1; s++) table[(plain ? 0 : oracle_hash_key((uint32_t)tn[s], h->a, R)) + 1]++;
-        for (int64_t k = 0; k < R; k++) table[k + 1] += table[k];
+        int64_t used = 0;  /* keys 0 .. used-1 occur in this block */
+        for (int64_t s = s0; s < s1; s++) if ((int64_t)ORACLE_KEY(tn[s]) >= used) used = (int64_t)ORACLE_KEY(tn[s]) + 1;
+        memset(table, 0, sizeof(int64_t) * (size_t)(used + 1));
+        for (int64_t s = s0; s < s1; s++) table[ORACLE_KEY(tn[s]) + 1]++;
+        for (int64_t k = 0; k < used; k++) table[k + 1] += table[k];
         for (int64_t s = s0; s < s1; s++) {   /* ascending local row */
-            int64_t slot = s0 + table[plain ? 0 : oracle_hash_key((uint32_t)tn[s], h->a, R)]++;
+            int64_t slot = s0 + table[ORACLE_KEY(tn[s])]++;
             h->row_local[slot] = (uint16_t)tq[s];
             h->seg_len[slot] = (uint16_t)tn[s];
             slot_j[slot] = tj[s];
         }
     }
+#undef ORACLE_KEY
 
     /* format conversion: groups of W slots, round-by-round fill, add_sign */
     h->group_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));

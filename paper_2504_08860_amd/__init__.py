@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhbp.so")
 HBP_OK = 0
 HBP_FLAG_VALIDATE = 1
 HBP_FLAG_NO_REORDER = 2
+HBP_FLAG_KEY_LENGTH = 4
 
 ARRAY_IDS = {
     "blk_bm": 0, "blk_bn": 1, "slot_ptr": 2, "blk_group_ptr": 3, "col_blk_ptr": 4, "stripe_ptr": 5,
@@ -155,6 +156,8 @@ def _build(f64: bool, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream,
             p.flags = (p.flags | HBP_FLAG_VALIDATE) if v else (p.flags & ~HBP_FLAG_VALIDATE)
         elif k == "no_reorder":
             p.flags = (p.flags | HBP_FLAG_NO_REORDER) if v else (p.flags & ~HBP_FLAG_NO_REORDER)
+        elif k == "key_length":
+            p.flags = (p.flags | HBP_FLAG_KEY_LENGTH) if v else (p.flags & ~HBP_FLAG_KEY_LENGTH)
         else:
             if not hasattr(p, k):
                 raise TypeError(f"hbp_params_t has no field {k}")
@@ -171,7 +174,7 @@ def _build(f64: bool, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream,
 def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
               **overrides) -> int:
     """CSR (device tensors, float32 values) -> handle.  ``overrides`` set fields of hbp_params_t by name
-    (``validate=True/False`` and ``no_reorder=True/False`` set the flags)."""
+    (``validate=``, ``no_reorder=`` and ``key_length=True/False`` set the flags)."""
     return _build(False, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, overrides)
 
 

@@ -484,7 +484,9 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_
     const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u, a = (uint32_t)*a_ptr;
     auto emit = [&](int64_t s, int32_t row, uint32_t pos) {
         const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-        bucket_key[pos] = ((reorder ? hash_key(n, a, b, R_u) : 0u) << 16) | (uint32_t)(row % R);
+        // reorder 0: no key (plain 2D partition), 1: the hash, 2: the length itself (n <= C < 65536)
+        const uint32_t key = reorder == 1 ? hash_key(n, a, b, R_u) : reorder == 2 ? n : 0u;
+        bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
         bucket_seg[pos] = (uint32_t)s;
     };
     if (t.span == 0) {
@@ -984,7 +986,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
                                                      h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
     k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a,
-                                                       (p.flags & HBP_FLAG_NO_REORDER) ? 0 : 1, slot_off,
+                                                       (p.flags & HBP_FLAG_NO_REORDER) ? 0 : (p.flags & HBP_FLAG_KEY_LENGTH) ? 2 : 1, slot_off,
                                                        bucket_key, bucket_seg);
     int n2 = 2;
     while (n2 < R) n2 <<= 1;

@@ -43,7 +43,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
     try:
         info = H.hbp_get_info(h)
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
-                             W=info.group_width, hash_shift=-2 if params.get("no_reorder") else params.get("hash_shift", -1),
+                             W=info.group_width, hash_shift=-2 if params.get("no_reorder") else -3 if params.get("key_length") else params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
                              round_weight=info.round_weight, group_weight=info.group_weight)
@@ -312,3 +312,11 @@ def test_plain_2d_partition(H, oracle, R, C):
     """HBP_FLAG_NO_REORDER: the plain 2D-partitioning method of Section 4 (no hash reorder)."""
     m = _mixed_matrix(seed=3)
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, no_reorder=True)
+
+
+@pytest.mark.parametrize("R,C", [(64, 128), (2048, 8192)])
+def test_length_key(H, oracle, R, C):
+    """HBP_FLAG_KEY_LENGTH (hash study): slots in ascending (length, row) order."""
+    m = _mixed_matrix(seed=11)
+    check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, key_length=True)
+    check_against_oracle(H, oracle, make_config(4, 2**-7), rows_per_block=512, cols_per_block=2048, key_length=True)

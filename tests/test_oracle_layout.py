@@ -393,3 +393,23 @@ def test_fp64_storage(oracle):
     # the float32 result of the same pattern differs by more than the fp64 bound on most rows
     y32, _ = oracle.csr_spmv_f64(m32.ptr, m32.col, m32.val, m32.x)
     assert np.mean(np.abs(y32 - y_ref) > 1e-11 * s_abs) > 0.5
+
+
+def test_length_key_orders_rows_by_length(oracle):
+    """hash_shift = -3 (the finest possible mapping of Section 5's outlook): the slots of every block
+    are in ascending (length, row) order, which is what numpy's stable sort gives; nothing else changes."""
+    m = random_csr(300, 400, 0.08, 17)
+    by_len = build(oracle, m, R=64, C=128, W=8, hash_shift=-3)
+    hbp = build(oracle, m, R=64, C=128, W=8)
+    sp, rl, sl = by_len.array("slot_ptr"), by_len.array("row_local").astype(np.int64), by_len.array("seg_len").astype(np.int64)
+    hsp, hrl, hsl = hbp.array("slot_ptr"), hbp.array("row_local").astype(np.int64), hbp.array("seg_len").astype(np.int64)
+    assert np.array_equal(sp, hsp)
+    for b in range(by_len.B):
+        rows, lens = hrl[hsp[b]:hsp[b + 1]], hsl[hsp[b]:hsp[b + 1]]
+        order = np.lexsort((rows, lens))                       # by length, then by row
+        assert np.array_equal(rl[sp[b]:sp[b + 1]], rows[order])
+        assert np.array_equal(sl[sp[b]:sp[b + 1]], lens[order])
+    assert coo_set(*by_len.to_coo()) == coo_set(*hbp.to_coo())
+    y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    y, _ = by_len.spmv(m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-12 * np.maximum(s_abs, 1e-300))
