@@ -189,7 +189,9 @@ int hbp_build(const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_v
  *   write it: x and y must not overlap).
  * Asynchronous on `stream`.  A handle supports one SpMV in flight at a time: calls on the
  * same stream serialise by themselves; calls on different streams must be ordered by the
- * caller (they share the partial-sum buffer and the ticket counter). */
+ * caller (they share the partial-sum buffer and the ticket counter).  The call allocates
+ * nothing and launches two kernels, no memset or copy: after one ordinary call on the device
+ * (which configures the kernels) it may be recorded into a HIP graph by stream capture. */
 int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream);
 
 /* The fp64 variant (Section 3.1 counts 8 bytes per stored value): hbp_build_f64 is hbp_build

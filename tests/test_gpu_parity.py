@@ -320,3 +320,41 @@ def test_length_key(H, oracle, R, C):
     m = _mixed_matrix(seed=11)
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, key_length=True)
     check_against_oracle(H, oracle, make_config(4, 2**-7), rows_per_block=512, cols_per_block=2048, key_length=True)
+
+
+@pytest.mark.parametrize("q8", [256, 128])
+def test_hip_graph_replay(H, oracle, q8):
+    """hbp_spmv allocates nothing and records no memset (the combine part re-arms the claim
+    counters), so a call can be captured into a HIP graph.  Replays, with eager calls and
+    synchronisations in between and x changing under the graph, must each give what an eager
+    call gives for the same x (bit for bit: without split row blocks every sum has one order)."""
+    import torch
+    m = random_csr(4000, 5000, 0.01, 77, empty_row_frac=0.1)
+    ptr, col, val, x = to_dev(m)
+    h = H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, rows_per_block=256, cols_per_block=1024, fixed_fraction_q8=q8,
+                    num_workers=24)
+    try:
+        assert H.hbp_get_info(h).split_row_blocks == 0
+        y_eager = torch.empty(m.n_rows, device="cuda")
+        y_graph = torch.full((m.n_rows,), float("nan"), device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):                 # first launches configure the kernels: not under capture
+            H.hbp_spmv(h, x, y_graph)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            H.hbp_spmv(h, x, y_graph)
+        for rep in range(4):
+            x.mul_(1.25).add_(0.01 * rep)
+            H.hbp_spmv(h, x, y_eager)
+            torch.cuda.synchronize()
+            y_graph.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_graph, y_eager), f"replay {rep}"
+            y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, x.cpu().numpy())
+            assert np.all(np.abs(y_graph.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs)
+    finally:
+        H.hbp_free(h)
