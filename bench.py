@@ -60,7 +60,9 @@ def main() -> int:
     ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
                     help="value type: f32 is the headline metric; f64 runs the fp64 variant on the same pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-csr", action="store_true")
+    ap.add_argument("--no-csr", action="store_true", help="skip the CSR baselines and the study legs")
+    ap.add_argument("--no-study", action="store_true",
+                    help="skip the plain 2D-partition and length-key legs (keeps a kernel trace to the HBP layout alone)")
     ap.add_argument("--builds", type=int, default=3, help="timed hbp_build repetitions")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 byte counters)")
@@ -193,7 +195,7 @@ def main() -> int:
             out[name] = {"ms": round(ms, 5), "GFLOPs": round(2.0 * m.nnz / (ms * 1e-3) / 1e9, 2),
                          "hbp_speedup": round(ms / ms_per_step, 3)}
 
-    if not args.no_csr:
+    if not args.no_csr and not args.no_study:
         # Section 4's second baseline: the same 2D partition without the hash reorder and with an
         # all-fixed schedule, and the diagnostic of Section 4.1 for both layouts (mean over the
         # groups of the standard deviation of their rows' lengths)

@@ -23,7 +23,7 @@ struct Layout {
     int32_t competitive;  // 0 when every group is fixed (nothing to compete for)
     int64_t n_rows, n_cols;
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
-    const int32_t *group_ptr, *group_slot;
+    const int32_t *group_ptr, *group_slot, *group_rounds;
     const int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;  // schedule (Section 3.3)
     const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
     int32_t NM;                                                        // row blocks with several units

@@ -399,6 +399,22 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         int32_t g = draw_resolve(draw_issue(), e), g1 = draw_resolve(draw_issue(), e1), g2 = kNone;
         unsigned long long raw2 = draw_issue();
         int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
+        // Packs of short rows have a path of their own in the fp64 kernels.  (In fp32 it measured
+        // 2-3 % slower than the general path: the kernel is bound by the latency of a pack's
+        // loads, not by its instructions, and the extra code costs registers.)
+        constexpr bool kShortPacks = GP > 1 && sizeof(T) == 8;
+        // longest row of the packs g and g1 (wave-uniform; only looked at where kShortPacks)
+        int32_t pack_longest = 0, pack_longestn = 0;
+        auto longest_in_pack = [&](int32_t first, int32_t end) __attribute__((always_inline)) {
+            int32_t most = 0;
+            if constexpr (kShortPacks) {
+#pragma unroll
+                for (int q = 0; q < GP; q++)
+                    if (in_pack(first, end, q))
+                        most = max(most, uniform_load(L.group_rounds, first + q + 1) - uniform_load(L.group_rounds, first + q));
+            }
+            return most;
+        };
         uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
         T done_acc[GP];
 #pragma unroll
@@ -419,6 +435,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
             }
         }
+        pack_longest = longest_in_pack(g, e);
+        pack_longestn = longest_in_pack(g1, e1);
         // the first packs' metadata is on its way while the slice of x is staged
         if (bn != staged_bn) {
             copy_slice(bn);
@@ -433,20 +451,23 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             // A group with a row of more than heavy_rounds nonzeros would keep this wavefront busy
             // long after the rest of the worker has run dry: it goes on the worker's list and
             // looks empty here (unless the list is full: then this wavefront walks it alone).
+            if (HEAVY && (!kShortPacks || pack_longest > L.heavy_rounds)) {
 #pragma unroll
-            for (int q = 0; q < GP; q++) {
-                if (HEAVY && __ballot(n[q] > L.heavy_rounds)) {
-                    int32_t idx = 0;
-                    if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
-                    idx = __builtin_amdgcn_readfirstlane(idx);
-                    if (idx < kHeavyCap) {
-                        if (lane == 0) sh_heavy[idx] = g + q;
-                        n[q] = 0;
-                        s1[q] = s0[q];
+                for (int q = 0; q < GP; q++) {
+                    if (__ballot(n[q] > L.heavy_rounds)) {
+                        int32_t idx = 0;
+                        if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
+                        idx = __builtin_amdgcn_readfirstlane(idx);
+                        if (idx < kHeavyCap) {
+                            if (lane == 0) sh_heavy[idx] = g + q;
+                            n[q] = 0;
+                            s1[q] = s0[q];
+                        }
                     }
                 }
             }
             int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
+            const int32_t pack_longestnn = longest_in_pack(g2, e2);
             uint32_t basenn[GP];
             T acc[GP];
 #pragma unroll
@@ -488,7 +509,53 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     slot[0] = s0[0] + (int32_t)((4u * (uint32_t)(lane & 15) + (uint32_t)m + 256u - (base[0] - chunk0)) & 63u);
                 }
             }
-            if (!wide) {
+            if (kShortPacks && pack_longest <= 2) {
+                // Packs of groups whose rows have one or two nonzeros (wave-uniform, known from the
+                // groups' longest rows): round 0 of a group is its slots in order, so lane q's first
+                // element sits at base + q and no ballot is needed; round 1 holds the second
+                // elements of the rows that have one.  Lanes without a slot or a second element read
+                // a position inside the group or the padding behind it and drop the product.
+                uint32_t c0[GP], c1[GP];
+                T v0[GP], v1[GP];
+#pragma unroll
+                for (int q = 0; q < GP; q++) {
+                    c0[q] = __builtin_nontemporal_load(L.col_local + base[q] + lane);
+                    v0[q] = __builtin_nontemporal_load(data + base[q] + lane);
+                }
+                if (pack_longest == 2) {
+#pragma unroll
+                    for (int q = 0; q < GP; q++) {
+                        const uint64_t live = __ballot(n[q] > 1);
+                        const uint32_t j = (uint32_t)__builtin_amdgcn_mbcnt_hi(
+                            (uint32_t)(live >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)live, base[q] + (uint32_t)(s1[q] - s0[q])));
+                        c1[q] = __builtin_nontemporal_load(L.col_local + j);
+                        v1[q] = __builtin_nontemporal_load(data + j);
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < GP; q++) {
+                    if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
+                    nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
+                }
+                if (pack_longest == 2) {
+                    T x0[GP], x1[GP];
+#pragma unroll
+                    for (int q = 0; q < GP; q++) { x0[q] = xs[c0[q]]; x1[q] = xs[c1[q]]; }
+#pragma unroll
+                    for (int q = 0; q < GP; q++) {
+                        const T p1 = v1[q] * x1[q];
+                        acc[q] = v0[q] * x0[q] + (n[q] > 1 ? p1 : T(0));
+                    }
+                } else {
+                    T x0[GP];
+#pragma unroll
+                    for (int q = 0; q < GP; q++) x0[q] = xs[c0[q]];
+#pragma unroll
+                    for (int q = 0; q < GP; q++) acc[q] = v0[q] * x0[q];
+                }
+#pragma unroll
+                for (int q = 0; q < GP; q++) slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
+            } else if (!wide) {
                 // general groups: round by round, U rounds per batch
                 Batch<U, T> bt[GP];
 #pragma unroll
@@ -512,9 +579,11 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 done_slot[q] = slot[q];
                 s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
                 s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
+
             }
             g = g1; g1 = g2;
             e = e1; e1 = e2;
+            pack_longest = pack_longestn; pack_longestn = pack_longestnn;
         }
 #pragma unroll
         for (int q = 0; q < GP; q++)
@@ -709,19 +778,51 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
     for (int32_t k0 = L.unit_k[unit]; k0 < k1; k0 += kPass) {
         const int32_t nb = min(kPass, k1 - k0);
         __syncthreads();  // slices zeroed / previous pass done with range[]
+        constexpr int kTogether = 4, kFirst = 4;
+        int small = 0;  // does the pass hold a block with few slots?
         for (int32_t t = threadIdx.x; t < nb; t += THREADS) {
             const int32_t b = L.stripe_blk[k0 + t];
-            range[2 * t] = L.slot_ptr[b];
-            range[2 * t + 1] = L.slot_ptr[b + 1];
+            const int32_t first = L.slot_ptr[b], end = L.slot_ptr[b + 1];
+            range[2 * t] = first;
+            range[2 * t + 1] = end;
+            small |= end - first <= 64 * kFirst;
         }
-        __syncthreads();
+        if (!__syncthreads_or(small)) {
+            // only blocks with many slots: wavefronts take them one by one, KU slots per lane in
+            // flight (the kernel is bound by the bytes it has in flight); the slots of a step are
+            // distinct rows of one block: read all, then write all
+            for (int32_t i = wave; i < nb; i += kWaves) {
+                const int32_t s0 = range[2 * i], s1 = range[2 * i + 1];
+                auto add_block = [&](auto ku) __attribute__((always_inline)) {
+                    constexpr int KU = decltype(ku)::value;
+                    for (int32_t s = s0 + lane; s < s1; s += 64 * KU) {
+                        uint32_t r[KU];
+                        T p[KU], o[KU];
+#pragma unroll
+                        for (int u = 0; u < KU; u++) {
+                            const int32_t idx = min(s + 64 * u, s1 - 1);  // clamped: always a slot of this block
+                            r[u] = L.row_local[idx];
+                            p[u] = partial[idx];
+                        }
+#pragma unroll
+                        for (int u = 0; u < KU; u++) o[u] = ys[r[u]];
+#pragma unroll
+                        for (int u = 0; u < KU; u++)
+                            if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
+                    }
+                };
+                if (DEEP && s1 - s0 > 512) add_block(std::integral_constant<int, 16>{});
+                else if (DEEP) add_block(std::integral_constant<int, 8>{});
+                else add_block(std::integral_constant<int, 4>{});
+            }
+            continue;
+        }
         // A wavefront takes kTogether blocks at a time.  Blocks with few slots are one load deep:
         // taken one by one, a wavefront would sit through a memory latency per block.  So the
         // slots of those of the kTogether blocks that have at most 64 kFirst of them are loaded
         // first; then the blocks are added one after the other (a row occurs once per block but
         // may occur in several blocks), a larger block with KU slots per lane in flight (the
         // kernel is bound by the bytes it has in flight).
-        constexpr int kTogether = 4, kFirst = 4;
         for (int32_t i0 = wave; i0 < nb; i0 += kWaves * kTogether) {
             int32_t b0[kTogether], b1[kTogether];
             uint32_t rf[kTogether][kFirst];
@@ -832,7 +933,7 @@ Layout hbp_view(const hbp_handle_s *h)
     L.n_rows = h->n_rows; L.n_cols = h->n_cols;
     L.blk_bm = h->blk_bm; L.blk_bn = h->blk_bn; L.slot_ptr = h->slot_ptr; L.blk_group_ptr = h->blk_group_ptr;
     L.col_blk_ptr = h->col_blk_ptr; L.stripe_ptr = h->stripe_ptr; L.stripe_blk = h->stripe_blk;
-    L.group_ptr = h->group_ptr; L.group_slot = h->group_slot;
+    L.group_ptr = h->group_ptr; L.group_slot = h->group_slot; L.group_rounds = h->group_rounds;
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
     L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
     L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
