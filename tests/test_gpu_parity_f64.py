@@ -2,6 +2,8 @@
 stored value): same checks as the fp32 tests, on inputs whose values are not representable in
 float32, so that a path that narrows anything to fp32 fails.  Layout bit-equal (data as 64-bit
 patterns); y and the per-slot partial sums within 168 * 2^-53 * sum_j |a_ij x_j|."""
+import os
+
 import numpy as np
 import pytest
 
@@ -67,7 +69,7 @@ def test_split_row_blocks(H, oracle, unit_slots):
             assert info.split_row_blocks > 0
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("HBP_RANDOM_CASES", "12"))))
 def test_random_parameters(H, oracle, seed):
     rng = np.random.default_rng(2000 + seed)
     n_rows = int(rng.integers(1, 6000))
