@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--combine-unit-slots", type=int, default=0)
     ap.add_argument("--hash-shift", type=int, default=-1)
     ap.add_argument("--round-weight", type=int, default=-1)
+    ap.add_argument("--column-weight", type=int, default=-1)
     ap.add_argument("--heavy-group-rounds", type=int, default=0)
     ap.add_argument("--dtype", choices=("f32", "f64"), default="f32",
                     help="value type: f32 is the headline metric; f64 runs the fp64 variant on the same pattern")
@@ -103,6 +104,7 @@ def main() -> int:
     if args.combine_unit_slots: params["combine_unit_slots"] = args.combine_unit_slots
     if args.hash_shift >= 0: params["hash_shift"] = args.hash_shift
     if args.round_weight >= 0: params["round_weight"] = args.round_weight
+    if args.column_weight >= 0: params["column_weight"] = args.column_weight
     if args.heavy_group_rounds: params["heavy_group_rounds"] = args.heavy_group_rounds
     overridden = params != preset(args.config, args.dtype) or f64
 
@@ -168,7 +170,7 @@ def main() -> int:
                    "fixed_fraction_q8": info.fixed_fraction_q8, "claim_chunk": info.claim_chunk,
                    "threads_per_worker": info.threads_per_worker, "rounds_per_batch": info.rounds_per_batch, "slot_weight": info.slot_weight, "group_weight": info.group_weight,
                    "combine_unit_slots": info.combine_unit_slots, "combine_units": info.combine_units,
-                   "round_weight": info.round_weight, "heavy_group_rounds": info.heavy_group_rounds},
+                   "round_weight": info.round_weight, "column_weight": info.column_weight, "heavy_group_rounds": info.heavy_group_rounds},
         "roofline": {"bound": "hbm", "kernel": "k_spmv_part", "achieved": round(part_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(part_gbs / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic("k_spmv_part", m.name) if args.scale == 1.0 and not overridden else None,

@@ -39,7 +39,8 @@
  *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
  *                                  the leading fixed_fraction of its weight as fixed part
  *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
- *                                  weight; worker w runs the fixed groups of range w
+ *                                  weight (a block column adds column_weight to its first
+ *                                  group here); worker w runs the fixed groups of range w
  *     fixed_col           [P]      block column that holds a worker's first group
  *   Combine units (Section 3.3, combine part: one workgroup per unit instead of one per row
  *   block, so that a row block with very many slots does not hold up the rest):
@@ -125,6 +126,9 @@ typedef struct {
                                   by all wavefronts of its worker together, each taking an equal share of
                                   its nonzeros, instead of by one: >= 1; 0 = default 2048              */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
+    int32_t column_weight;     /* schedule weight of entering a block column (the worker fetches its segment
+                                  of x), in nonzeros, charged to the column's first group when the group list
+                                  is cut into the workers' ranges: 0..16777216; -1 = default 0          */
 } hbp_params_t;
 
 typedef struct {
@@ -144,6 +148,7 @@ typedef struct {
     int32_t combine_unit_slots;  /* slots per combine unit the row blocks were cut for          */
     int32_t heavy_group_rounds;  /* row length from which a group is shared by a worker's wavefronts */
     int32_t round_weight;        /* schedule weight of a round of a group, in nonzeros          */
+    int32_t column_weight;       /* schedule weight of entering a block column, in nonzeros      */
     int64_t combine_units;       /* U: workgroups of the combine part                           */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int32_t value_bytes;         /* 4: fp32 handle, 8: fp64 handle                              */

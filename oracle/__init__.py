@@ -55,7 +55,7 @@ def _load():
         lib.oracle_hash_key.restype = ctypes.c_uint32
         lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
         lib.oracle_sample_shift.restype = i32
-        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32]
+        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32, i32]
         lib.oracle_hbp_build.restype = vp
         lib.oracle_hbp_free.argtypes = [vp]
         lib.oracle_hbp_free.restype = None
@@ -100,12 +100,12 @@ class OracleHbp:
     """The compact HBP layout built by the C oracle; arrays are numpy copies."""
 
     def __init__(self, ptr, col, val, n_rows, n_cols, R=512, C=4096, W=64, hash_shift=-1,
-                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, group_weight=0):
+                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, group_weight=0, column_weight=0):
         lib = _load()
         assert val.dtype in (np.float32, np.float64)
         self.value_dtype = val.dtype
         self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(val.dtype.itemsize), int(n_rows), int(n_cols), int(R), int(C), int(W),
-                                       int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(group_weight),
+                                       int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(group_weight), int(column_weight),
                                        int(unit_slots))
         if not self._h:
             raise ValueError("oracle_hbp_build rejected the parameters")

@@ -218,9 +218,9 @@ void oracle_hbp_free(oracle_hbp *h)
  * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void *val, int32_t value_bytes, int64_t n_rows, int64_t n_cols,
                              int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
-                             int32_t slot_weight, int32_t round_weight, int32_t group_weight, int32_t unit_slots)
+                             int32_t slot_weight, int32_t round_weight, int32_t group_weight, int32_t column_weight, int32_t unit_slots)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || (value_bytes != 4 && value_bytes != 8) || unit_slots < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || column_weight < 0 || (value_bytes != 4 && value_bytes != 8) || unit_slots < 1) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
@@ -351,7 +351,10 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
      *     leaves the rest to competition: comp_lo[c] is the column's first competitive group;
      *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
      *     the first group of worker w; a worker runs the fixed groups inside its range and then
-     *     competes, starting with the column it is on. */
+     *     competes, starting with the column it is on.  For this cut a block column weighs
+     *     column_weight on top of its groups (a worker that enters it has to fetch its segment of
+     *     the vector), charged to the column's first group: the weight before g is
+     *     Wt(g) + column_weight * (number of non-empty block columns that start before g). */
     h->group_rounds = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
     h->group_rounds[0] = 0;
     for (int64_t g = 0; g < G; g++) {
@@ -373,14 +376,22 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
         h->comp_lo[c] = (int32_t)g;
     }
     {
+        /* entered[g]: non-empty block columns whose first group lies before g */
+        int64_t *entered = (int64_t *)calloc((size_t)(G + 2), sizeof(int64_t));
+        for (int64_t c = 0; c < NBC; c++)
+            if (h->col_group_ptr[c + 1] > h->col_group_ptr[c]) entered[h->col_group_ptr[c] + 1]++;
+        for (int64_t g = 0; g <= G; g++) entered[g + 1] += entered[g];
+        #define WTC(g) (WT(g) + (int64_t)column_weight * entered[g])
         int64_t g = 0, c = 0;
         for (int64_t w = 0; w <= num_workers; w++) {
-            while (g < G && WT(g) * num_workers < w * WT(G)) g++;
+            while (g < G && WTC(g) * num_workers < w * WTC(G)) g++;
             h->fixed_start[w] = (int32_t)g;
             if (w == num_workers) break;
             while (c + 1 < NBC && h->col_group_ptr[c + 1] <= g) c++;   /* last column starting at or before g */
             h->fixed_col[w] = (int32_t)c;
         }
+        #undef WTC
+        free(entered);
     }
     #undef WT
 

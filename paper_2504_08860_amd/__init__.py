@@ -47,7 +47,7 @@ class hbp_params_t(ctypes.Structure):
                 ("claim_chunk", ctypes.c_int32), ("threads_per_worker", ctypes.c_int32),
                 ("rounds_per_batch", ctypes.c_int32), ("slot_weight", ctypes.c_int32), ("group_weight", ctypes.c_int32),
                 ("combine_unit_slots", ctypes.c_int32), ("round_weight", ctypes.c_int32), ("heavy_group_rounds", ctypes.c_int32),
-                ("flags", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("column_weight", ctypes.c_int32)]
 
 
 class hbp_info_t(ctypes.Structure):
@@ -59,7 +59,7 @@ class hbp_info_t(ctypes.Structure):
                 ("num_workers", ctypes.c_int32), ("fixed_fraction_q8", ctypes.c_int32), ("claim_chunk", ctypes.c_int32),
                 ("threads_per_worker", ctypes.c_int32), ("rounds_per_batch", ctypes.c_int32),
                 ("slot_weight", ctypes.c_int32), ("group_weight", ctypes.c_int32), ("combine_unit_slots", ctypes.c_int32),
-                ("heavy_group_rounds", ctypes.c_int32), ("round_weight", ctypes.c_int32),
+                ("heavy_group_rounds", ctypes.c_int32), ("round_weight", ctypes.c_int32), ("column_weight", ctypes.c_int32),
                 ("combine_units", ctypes.c_int64), ("split_row_blocks", ctypes.c_int64), ("value_bytes", ctypes.c_int32),
                 ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
                 ("build_ms", ctypes.c_double)]

@@ -50,6 +50,7 @@ int hbp_default_params(hbp_params_t *p)
     p->group_weight = -1;
     p->combine_unit_slots = 0;
     p->round_weight = -1;
+    p->column_weight = -1;
     p->heavy_group_rounds = 0;
     p->flags = HBP_FLAG_VALIDATE;
     return HBP_OK;
@@ -72,12 +73,13 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
     if (p.slot_weight < 0) p.slot_weight = 4;
     if (p.group_weight < 0) p.group_weight = 0;
     if (p.round_weight < 0) p.round_weight = 8;
+    if (p.column_weight < 0) p.column_weight = 0;
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
     const int32_t max_r = value_bytes == 8 ? hbp::kMaxR64 : hbp::kMaxR, max_c = value_bytes == 8 ? hbp::kMaxC64 : hbp::kMaxC;
     if (p.rows_per_block < 1 || p.rows_per_block > max_r || p.cols_per_block < 1 || p.cols_per_block > max_c ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
         p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 1024 || p.slot_weight > 64 || p.group_weight > 4096 ||
-        (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 || p.heavy_group_rounds < 1 ||
+        (p.combine_unit_slots != 0 && p.combine_unit_slots < 64) || p.round_weight > 1024 || p.column_weight > (1 << 24) || p.heavy_group_rounds < 1 ||
         (p.threads_per_worker != 0 && p.threads_per_worker != 256 && p.threads_per_worker != 512 &&
          p.threads_per_worker != 1024) ||
         (p.rounds_per_batch != 0 && p.rounds_per_batch != 2 && p.rounds_per_batch != 4 && p.rounds_per_batch != 8 &&
@@ -109,6 +111,7 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
         h->group_weight = p.group_weight;
         h->unit_slots = p.combine_unit_slots;
         h->round_weight = p.round_weight;
+        h->column_weight = p.column_weight;
         h->heavy_rounds = p.heavy_group_rounds;
         h->P = p.num_workers > 0 ? p.num_workers : workers;
         rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
@@ -224,6 +227,7 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->group_weight = h->group_weight;
     info->combine_unit_slots = h->unit_slots;
     info->round_weight = h->round_weight;
+    info->column_weight = h->column_weight;
     info->heavy_group_rounds = h->heavy_rounds;
     info->combine_units = h->U;
     info->split_row_blocks = h->NM;

@@ -750,18 +750,56 @@ __global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col
     comp_lo[c] = lo;
 }
 
-// fixed_start[w]: first g with Wt(g) * P >= w * Wt(G) (P contiguous ranges of equal weight);
+// col_rank[c], c in 0..NBC: block columns before c that hold a group.  One workgroup: every thread
+// counts a contiguous piece, the pieces' counts are scanned in LDS, every thread writes its piece.
+__global__ __launch_bounds__(256) void k_col_rank(const int32_t *__restrict__ col_group_ptr, int32_t NBC, int32_t *__restrict__ col_rank)
+{
+    __shared__ int32_t piece_sum[256];
+    const int32_t per = (NBC + 255) / 256, c0 = min(NBC, (int32_t)threadIdx.x * per), c1 = min(NBC, c0 + per);
+    int32_t mine = 0;
+    for (int32_t c = c0; c < c1; c++) mine += col_group_ptr[c + 1] > col_group_ptr[c];
+    piece_sum[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t run = 0;
+        for (int i = 0; i < 256; i++) { const int32_t v = piece_sum[i]; piece_sum[i] = run; run += v; }
+    }
+    __syncthreads();
+    int32_t run = piece_sum[threadIdx.x];
+    for (int32_t c = c0; c < c1; c++) {
+        col_rank[c] = run;
+        run += col_group_ptr[c + 1] > col_group_ptr[c];
+    }
+    if (c1 == NBC && c0 < NBC) col_rank[NBC] = run;  // the thread that holds the last column
+}
+
+// fixed_start[w]: first g with Wc(g) * P >= w * Wc(G) (P contiguous ranges of equal weight), where
+// Wc(g) = Wt(g) + CW * (block columns with a group that start before g): entering a block column
+// costs a worker the fetch of its vector segment, charged to the column's first group;
 // fixed_col[w]: the last block column that starts at or before that group.
-__global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, Weights wt, int32_t NBC, int32_t G,
+__global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__ col_group_ptr, Weights wt,
+                                                     const int32_t *__restrict__ col_rank, int64_t CW, int32_t NBC, int32_t G,
                                                      int32_t P, int32_t *__restrict__ fixed_start, int32_t *__restrict__ fixed_col)
 {
     const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (w > P) return;
-    const int64_t need = w * wt.before(G);
+    auto before = [&](int32_t g) {
+        int64_t v = wt.before(g);
+        if (CW) {
+            int32_t c_lo = 0, c_hi = NBC;  // first c in 0..NBC with col_group_ptr[c] >= g (col_group_ptr[NBC] = G)
+            while (c_lo < c_hi) {
+                const int32_t mid = c_lo + ((c_hi - c_lo) >> 1);
+                if (col_group_ptr[mid] >= g) c_hi = mid; else c_lo = mid + 1;
+            }
+            v += CW * col_rank[c_lo];
+        }
+        return v;
+    };
+    const int64_t need = w * before(G);
     int32_t lo = 0, hi = G;
     while (lo < hi) {
         const int32_t mid = lo + ((hi - lo) >> 1);
-        if (wt.before(mid) * P >= need) hi = mid; else lo = mid + 1;
+        if (before(mid) * P >= need) hi = mid; else lo = mid + 1;
     }
     fixed_start[w] = lo;
     if (w == P) return;
@@ -840,6 +878,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
     own0.reserve(&h->fixed_col, (int64_t)h->P);
     own0.reserve(&h->unit_ptr, NBR + 1);
+    own0.reserve(&h->col_rank, NBC + 1);
     HBP_TRY(own0.commit());
     h->arena[0] = own0.base();
     HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
@@ -1030,8 +1069,9 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
         const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight,
                          (int64_t)h->group_weight};
         k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
-        k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, (int32_t)h->G, h->P,
-                                                                          h->fixed_start, h->fixed_col);
+        k_col_rank<<<1, 256, 0, st>>>(h->col_group_ptr, NBC, h->col_rank);
+        k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, h->col_rank, (int64_t)h->column_weight,
+                                                                          NBC, (int32_t)h->G, h->P, h->fixed_start, h->fixed_col);
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

@@ -57,6 +57,8 @@ struct hbp_handle_s {
     int32_t group_weight;  // schedule weight of a group as such
     int32_t longest_segment;  // longest row segment of the matrix
     int32_t round_weight;  // schedule weight of a group on top of its nonzeros and slots
+    int32_t column_weight;  // schedule weight of entering a block column
+    int32_t *col_rank;     // [NBC+1] non-empty block columns before each column
     uint16_t *row_local, *seg_len, *col_local;
     int32_t value_bytes; // 4: fp32 values (data, partial, x, y), 8: fp64
     void *data;

@@ -6,11 +6,12 @@ from __future__ import annotations
 PRESETS = {
     1: dict(rows_per_block=512, cols_per_block=4096, fixed_fraction_q8=256),
     2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4),
-    3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
-    # weights from a least-squares fit of the workers' times: a range costs per group and per round, not per nonzero
-    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=224, slot_weight=0,
-            group_weight=100, round_weight=35),
-    5: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256),
+    3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256, column_weight=50000),
+    # weights from a least-squares fit of the workers' times: a range costs per group, per round and per block
+    # column entered (37 us + 23 ns, 5 ns and 14 us), not per nonzero
+    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=240, slot_weight=0,
+            group_weight=200, round_weight=46, column_weight=126000),
+    5: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256, column_weight=100000),
 }
 
 
@@ -22,5 +23,7 @@ def preset(config_number: int, dtype: str = "f32") -> dict:
         # many block columns the R-MAT matrix runs best without a competitive part
         p["cols_per_block"] = min(p["cols_per_block"], 16384)
         if config_number == 4:
-            p["fixed_fraction_q8"] = 256
+            p.update(fixed_fraction_q8=256, group_weight=400, round_weight=92, column_weight=252000)
+        if config_number == 5:
+            p["column_weight"] = 200000
     return p

@@ -28,7 +28,7 @@ def test_host_only_calls():
     assert H.lib().hbp_free(None) == 0
     assert H.lib().hbp_get_info(None, None) == -1
     assert H.lib().hbp_build(None, None, None, 1, 1, None, None, None) == -1
-    assert ctypes.sizeof(H.hbp_params_t) == 60
+    assert ctypes.sizeof(H.hbp_params_t) == 64
 
 
 def test_struct_layout_matches_header(tmp_path):

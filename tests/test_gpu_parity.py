@@ -48,7 +48,7 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
                              W=info.group_width, hash_shift=-2 if params.get("no_reorder") else -3 if params.get("key_length") else params.get("hash_shift", -1),
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
-                             round_weight=info.round_weight, group_weight=info.group_weight)
+                             round_weight=info.round_weight, group_weight=info.group_weight, column_weight=info.column_weight)
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a and info.value_bytes == m.val.dtype.itemsize
         assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
@@ -286,6 +286,7 @@ def test_random_parameters(H, oracle, seed):
         slot_weight=int(rng.choice([0, 1, 4, 64])),
         group_weight=int(rng.choice([0, 10, 4096])),
         round_weight=int(rng.choice([0, 8, 1024])),
+        column_weight=int(rng.choice([0, 0, 50, 100000])),
         combine_unit_slots=int(rng.choice([0, 64, 1000])),
         heavy_group_rounds=int(rng.choice([0, 1, 20, 300])),
         hash_shift=int(rng.choice([-1, 0, 3, 12])),

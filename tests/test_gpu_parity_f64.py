@@ -90,6 +90,7 @@ def test_random_parameters(H, oracle, seed):
         slot_weight=int(rng.choice([0, 1, 4, 64])),
         group_weight=int(rng.choice([0, 10, 4096])),
         round_weight=int(rng.choice([0, 8, 1024])),
+        column_weight=int(rng.choice([0, 0, 50, 100000])),
         combine_unit_slots=int(rng.choice([0, 64, 1000])),
         heavy_group_rounds=int(rng.choice([0, 1, 20, 300])),
         hash_shift=int(rng.choice([-1, 0, 3, 12])),

@@ -225,12 +225,16 @@ def test_schedule_split(oracle):
     every group exactly once; ranges have equal weight up to one group; every column keeps the
     stated share of its weight fixed, up to one group."""
     m = random_csr(300, 300, 0.05, 3)
-    for P, q8, sw, gw, cw in [(1, 128, 1, 0, 0), (4, 192, 4, 0, 7), (7, 255, 1, 9, 0), (64, 256, 6, 100, 300), (5, 0, 0, 1, 50),
-                              (1000, 100, 1, 0, 0)]:
-        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, round_weight=gw, group_weight=cw)
+    for P, q8, sw, gw, cw, colw in [(1, 128, 1, 0, 0, 0), (4, 192, 4, 0, 7, 0), (7, 255, 1, 9, 0, 40), (64, 256, 6, 100, 300, 0),
+                                    (5, 0, 0, 1, 50, 1000), (1000, 100, 1, 0, 0, 3), (6, 256, 1, 0, 0, 100000)]:
+        h = build(oracle, m, R=16, C=16, W=8, num_workers=P, fixed_q8=q8, slot_weight=sw, round_weight=gw, group_weight=cw,
+                  column_weight=colw)
         assert h.P == P and h.fixed_q8 == q8
         wt = h.array("group_ptr").astype(np.int64) + sw * h.array("group_slot").astype(np.int64) + gw * h.array("group_rounds").astype(np.int64) + cw * np.arange(h.G + 1)
         cgp, comp_lo = h.array("col_group_ptr"), h.array("comp_lo")
+        # the cut into ranges also charges every block column that holds a group to its first group
+        starts = cgp[:-1][np.diff(cgp) > 0]
+        wt_cut = wt + colw * np.array([(starts < g).sum() for g in range(h.G + 1)], dtype=np.int64)
         fs, fc = h.array("fixed_start"), h.array("fixed_col")
         assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
         assert fs[0] == 0 and fs[-1] == h.G and np.all(np.diff(fs) >= 0)
@@ -242,8 +246,8 @@ def test_schedule_split(oracle):
             if fs[w] < h.G:
                 assert fc[w] == col_of[fs[w]]
             # equal weight: the range starts at the first group whose preceding weight reaches w/P
-            assert wt[fs[w]] * P >= w * wt[-1]
-            assert fs[w] == 0 or wt[fs[w] - 1] * P < w * wt[-1]
+            assert wt_cut[fs[w]] * P >= w * wt_cut[-1]
+            assert fs[w] == 0 or wt_cut[fs[w] - 1] * P < w * wt_cut[-1]
         for c in range(h.NBC):
             covered[comp_lo[c]:cgp[c + 1]] += 1                    # the column's competitive groups
             assert cgp[c] <= comp_lo[c] <= cgp[c + 1]
@@ -255,6 +259,11 @@ def test_schedule_split(oracle):
             assert np.array_equal(comp_lo, cgp[1:])                # nothing left to competition
         if q8 == 0:
             assert np.array_equal(comp_lo, cgp[:-1])               # everything competitive
+        if colw == 100000:
+            # a column weighs far more than all groups: every worker's range starts at a column's
+            # first group or just behind it (there the column's charge has been paid)
+            first = np.isin(fs[:-1], cgp) | np.isin(fs[:-1] - 1, starts)
+            assert np.all(first)
 
 
 def test_group_rounds(oracle):
