@@ -128,7 +128,7 @@ typedef struct {
     uint32_t flags;            /* HBP_FLAG_*                                                    */
     int32_t column_weight;     /* schedule weight of entering a block column (the worker fetches its segment
                                   of x), in nonzeros, charged to the column's first group when the group list
-                                  is cut into the workers' ranges: 0..16777216; -1 = default 0          */
+                                  is cut into the workers' ranges: 0..16777216; -1 = default C           */
 } hbp_params_t;
 
 typedef struct {

@@ -73,7 +73,7 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
     if (p.slot_weight < 0) p.slot_weight = 4;
     if (p.group_weight < 0) p.group_weight = 0;
     if (p.round_weight < 0) p.round_weight = 8;
-    if (p.column_weight < 0) p.column_weight = 0;
+    if (p.column_weight < 0) p.column_weight = p.cols_per_block;  // about what staging C values of x costs, in nonzeros
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
     const int32_t max_r = value_bytes == 8 ? hbp::kMaxR64 : hbp::kMaxR, max_c = value_bytes == 8 ? hbp::kMaxC64 : hbp::kMaxC;
     if (p.rows_per_block < 1 || p.rows_per_block > max_r || p.cols_per_block < 1 || p.cols_per_block > max_c ||

@@ -5,7 +5,7 @@ from __future__ import annotations
 
 PRESETS = {
     1: dict(rows_per_block=512, cols_per_block=4096, fixed_fraction_q8=256),
-    2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4),
+    2: dict(rows_per_block=512, cols_per_block=32768, rounds_per_batch=9, fixed_fraction_q8=256, slot_weight=4, column_weight=0),
     3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256, column_weight=50000),
     # weights from a least-squares fit of the workers' times: a range costs per group, per round and per block
     # column entered (37 us + 23 ns, 5 ns and 14 us), not per nonzero
