@@ -36,12 +36,16 @@
  *   nonzeros plus slot_weight times its slots plus round_weight times its rounds, the
  *   length of its longest row, plus group_weight):
  *     col_group_ptr       [NBC+1]  first group of each block column
- *     comp_lo             [NBC]    first competitive group of a block column: the column keeps
- *                                  the leading fixed_fraction of its weight as fixed part
  *     fixed_start         [P+1]    the group list cut into P contiguous ranges of equal
  *                                  weight (a block column adds column_weight to its first
  *                                  group here); worker w runs the fixed groups of range w
  *     fixed_col           [P]      block column that holds a worker's first group
+ *     comp_lo             [P]      first competitive group of a worker's range: the range keeps the
+ *                                  leading fixed_fraction of its weight as fixed part; the rest, as
+ *                                  far as it lies in the block column of the range's last group, is
+ *                                  left to competition (the worker itself and workers that have
+ *                                  run out of work claim it piece by piece)
+ *     comp_col            [P]      that block column
  *   Combine units (Section 3.3, combine part: one workgroup per unit instead of one per row
  *   block, so that a row block with very many slots does not hold up the rest):
  *     unit_ptr            [NBR+1]  first unit of each row block; a row block has
@@ -107,7 +111,7 @@ typedef struct {
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = as many as
                                   fit on the device at once, but no more than one per threads_per_worker / 64 groups */
-    int32_t fixed_fraction_q8; /* share of every block column's work that is pre-assigned, in 1/256; -1 = default */
+    int32_t fixed_fraction_q8; /* share of every worker's range that is pre-assigned, in 1/256; -1 = default */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
     int32_t claim_chunk;       /* competitive part: groups per wavefront that a worker claims from a
                                   block column at a time, 1..1024; 0 = default (two draws per wavefront) */
@@ -168,7 +172,7 @@ typedef enum {
     HBP_ARRAY_PARTIAL = 14,  /* float or double [S], per-slot partial sums of the last SpMV      */
     HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
     HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22,
-    HBP_ARRAY_GROUP_ROUNDS = 23
+    HBP_ARRAY_GROUP_ROUNDS = 23, HBP_ARRAY_COMP_COL = 24
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */

@@ -27,7 +27,7 @@ ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
     "data": (12, np.float32), "add_sign": (13, np.int32), "col_group_ptr": (14, np.int32),
     "comp_lo": (15, np.int32), "fixed_start": (16, np.int32), "fixed_col": (17, np.int32),
     "unit_ptr": (18, np.int32), "unit_stripe": (19, np.int32), "unit_k": (20, np.int32), "multi_stripes": (21, np.int32),
-    "group_rounds": (22, np.int32),
+    "group_rounds": (22, np.int32), "comp_col": (23, np.int32),
 }
 DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8", "U", "NM")
 

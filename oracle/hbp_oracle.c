@@ -171,7 +171,8 @@ typedef struct {
     int32_t value_bytes;          /* 4 or 8                                                */
     int32_t *add_sign;            /* nnz : distance to the row's next nonzero, -1 at its end */
     int32_t *col_group_ptr;       /* NBC+1 : first group of each block column                 */
-    int32_t *comp_lo;             /* NBC : first competitive group of a block column          */
+    int32_t *comp_lo;             /* P   : first competitive group of a worker's range          */
+    int32_t *comp_col;            /* P   : block column that holds the range's competitive groups */
     int32_t *fixed_start;         /* P+1 : group ranges of the workers                        */
     int32_t *fixed_col;           /* P   : block column holding a worker's first group        */
     int64_t U, NM;                /* combine units, row blocks cut into more than one unit    */
@@ -204,7 +205,7 @@ void oracle_hbp_free(oracle_hbp *h)
     if (!h) return;
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_rounds); free(h->group_slot);
-    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->data64); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->fixed_start); free(h->fixed_col);
+    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->data64); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->comp_col); free(h->fixed_start); free(h->fixed_col);
     free(h->unit_ptr); free(h->unit_stripe); free(h->unit_k); free(h->multi_stripes);
     free(h);
 }
@@ -347,8 +348,10 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
      * its rounds (the length of its longest row: the steps a wavefront takes through it), so
      * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] + round_weight * group_rounds[g] is the
      * weight of all groups before g.
-     *   - every block column keeps the first fixed_q8/256 of its weight as its fixed part and
-     *     leaves the rest to competition: comp_lo[c] is the column's first competitive group;
+     *   - every range keeps the first fixed_q8/256 of its weight as its fixed part and leaves
+     *     the rest to competition, as far as that rest lies in the range's last block column (so
+     *     that whoever takes it needs one segment of the vector): comp_lo[w] is the range's
+     *     first competitive group, comp_col[w] that block column;
      *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
      *     the first group of worker w; a worker runs the fixed groups inside its range and then
      *     competes, starting with the column it is on.  For this cut a block column weighs
@@ -365,16 +368,12 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
     }
     h->P = num_workers; h->fixed_q8 = fixed_q8;
     h->col_group_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
-    h->comp_lo = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
+    h->comp_lo = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
+    h->comp_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
     for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
     #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g] + (int64_t)round_weight * (int64_t)h->group_rounds[g] + (int64_t)group_weight * (int64_t)(g))
-    for (int64_t c = 0; c < NBC; c++) {
-        int64_t g0 = h->col_group_ptr[c], g1 = h->col_group_ptr[c + 1], g = g0;
-        while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;
-        h->comp_lo[c] = (int32_t)g;
-    }
     {
         /* entered[g]: non-empty block columns whose first group lies before g */
         int64_t *entered = (int64_t *)calloc((size_t)(G + 2), sizeof(int64_t));
@@ -392,6 +391,17 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
         }
         #undef WTC
         free(entered);
+    }
+    for (int64_t w = 0; w < num_workers; w++) {
+        int64_t g0 = h->fixed_start[w], g1 = h->fixed_start[w + 1], g = g0, c = h->fixed_col[w];
+        while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;
+        if (g1 > g0) {
+            c = 0;
+            while (c + 1 < NBC && h->col_group_ptr[c + 1] <= g1 - 1) c++;   /* column of the range's last group */
+            if (g < h->col_group_ptr[c]) g = h->col_group_ptr[c];
+        }
+        h->comp_lo[w] = (int32_t)g;
+        h->comp_col[w] = (int32_t)c;
     }
     #undef WT
 
@@ -451,7 +461,7 @@ void oracle_hbp_dims(const oracle_hbp *h, int64_t *dims)
 /* which: 0 blk_bm 1 blk_bn 2 slot_ptr 3 blk_group_ptr 4 col_blk_ptr 5 stripe_ptr 6 stripe_blk
  *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign
  *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col
- *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 group_rounds.
+ *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 group_rounds 23 comp_col.
  * Copies the array into dst and returns its size in bytes (0 for an unknown id). */
 int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
 {
@@ -472,7 +482,7 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 12: src = h->value_bytes == 4 ? (const void *)h->data : (const void *)h->data64; bytes = h->value_bytes * h->nnz; break;
     case 13: src = h->add_sign; bytes = 4 * h->nnz; break;
     case 14: src = h->col_group_ptr; bytes = 4 * (h->NBC + 1); break;
-    case 15: src = h->comp_lo; bytes = 4 * h->NBC; break;
+    case 15: src = h->comp_lo; bytes = 4 * h->P; break;
     case 16: src = h->fixed_start; bytes = 4 * (h->P + 1); break;
     case 17: src = h->fixed_col; bytes = 4 * h->P; break;
     case 18: src = h->unit_ptr; bytes = 4 * (h->NBR + 1); break;
@@ -480,6 +490,7 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 20: src = h->unit_k; bytes = 4 * (h->U + 1); break;
     case 21: src = h->multi_stripes; bytes = 4 * h->NM; break;
     case 22: src = h->group_rounds; bytes = 4 * (h->G + 1); break;
+    case 23: src = h->comp_col; bytes = 4 * h->P; break;
     default: return 0;
     }
     if (dst && bytes) memcpy(dst, src, (size_t)bytes);

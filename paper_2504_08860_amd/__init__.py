@@ -22,7 +22,7 @@ ARRAY_IDS = {
     "stripe_blk": 6, "group_ptr": 7, "group_slot": 8, "row_local": 9, "seg_len": 10, "col_local": 11,
     "data": 12, "add_sign": 13, "partial": 14, "col_group_ptr": 15, "comp_lo": 16,
     "fixed_start": 17, "fixed_col": 18, "unit_ptr": 19, "unit_stripe": 20, "unit_k": 21, "multi_stripes": 22,
-    "group_rounds": 23,
+    "group_rounds": 23, "comp_col": 24,
 }
 ARRAY_DTYPES = {
     "blk_bm": "int32", "blk_bn": "int32", "slot_ptr": "int32", "blk_group_ptr": "int32", "col_blk_ptr": "int32",
@@ -31,7 +31,7 @@ ARRAY_DTYPES = {
     "partial": "float32", "col_group_ptr": "int32", "comp_lo": "int32",
     "fixed_start": "int32", "fixed_col": "int32",
     "unit_ptr": "int32", "unit_stripe": "int32", "unit_k": "int32", "multi_stripes": "int32",
-    "group_rounds": "int32",
+    "group_rounds": "int32", "comp_col": "int32",
 }
 # every symbol include/hbp.h declares
 EXPORTED_SYMBOLS = (

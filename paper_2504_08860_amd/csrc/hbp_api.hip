@@ -269,7 +269,8 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_ADD_SIGN: bytes = 4 * (size_t)h->nnz; break;
     case HBP_ARRAY_PARTIAL: src = h->partial; bytes = (size_t)h->value_bytes * (size_t)h->S; break;
     case HBP_ARRAY_COL_GROUP_PTR: src = h->col_group_ptr; bytes = 4 * (size_t)(h->NBC + 1); break;
-    case HBP_ARRAY_COMP_LO: src = h->comp_lo; bytes = 4 * (size_t)h->NBC; break;
+    case HBP_ARRAY_COMP_LO: src = h->comp_lo; bytes = 4 * (size_t)h->P; break;
+    case HBP_ARRAY_COMP_COL: src = h->comp_col; bytes = 4 * (size_t)h->P; break;
     case HBP_ARRAY_FIXED_START: src = h->fixed_start; bytes = 4 * (size_t)(h->P + 1); break;
     case HBP_ARRAY_FIXED_COL: src = h->fixed_col; bytes = 4 * (size_t)h->P; break;
     case HBP_ARRAY_UNIT_PTR: src = h->unit_ptr; bytes = 4 * (size_t)(h->NBR + 1); break;

@@ -732,14 +732,18 @@ __global__ __launch_bounds__(256) void k_col_group_ptr(const int32_t *__restrict
     if (c <= NBC) col_group_ptr[c] = blk_group_ptr[col_blk_ptr[c]];
 }
 
-// comp_lo[c]: first group of column c left to competition, i.e. the first g in the column whose
-// preceding weight inside the column reaches fixed_q8/256 of the column's weight.
-__global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, Weights wt, int32_t NBC,
-                                                 int32_t fixed_q8, int32_t *__restrict__ comp_lo)
+// comp_lo[w]: first group of worker w's range left to competition: the first g in the range whose
+// preceding weight inside the range reaches fixed_q8/256 of the range's weight, but not before
+// the first group of the block column that holds the range's last group (comp_col[w]), so that
+// the competitive groups of a range need one segment of the vector.
+__global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col_group_ptr, Weights wt, int32_t NBC, int32_t P,
+                                                 int32_t fixed_q8, const int32_t *__restrict__ fixed_start,
+                                                 const int32_t *__restrict__ fixed_col, int32_t *__restrict__ comp_lo,
+                                                 int32_t *__restrict__ comp_col)
 {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= NBC) return;
-    const int32_t g0 = col_group_ptr[c], g1 = col_group_ptr[c + 1];
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w >= P) return;
+    const int32_t g0 = fixed_start[w], g1 = fixed_start[w + 1];
     const int64_t w0 = wt.before(g0);
     const int64_t need = (wt.before(g1) - w0) * fixed_q8;
     int32_t lo = g0, hi = g1;  // smallest g in [g0, g1] with (Wt(g) - w0) * 256 >= need
@@ -747,7 +751,18 @@ __global__ __launch_bounds__(256) void k_comp_lo(const int32_t *__restrict__ col
         const int32_t mid = lo + ((hi - lo) >> 1);
         if ((wt.before(mid) - w0) * 256 >= need) hi = mid; else lo = mid + 1;
     }
-    comp_lo[c] = lo;
+    int32_t c = fixed_col[w];
+    if (g1 > g0) {
+        int32_t c_lo = 0, c_hi = NBC - 1;  // largest c with col_group_ptr[c] <= g1 - 1
+        while (c_lo < c_hi) {
+            const int32_t mid = c_lo + ((c_hi - c_lo + 1) >> 1);
+            if (col_group_ptr[mid] <= g1 - 1) c_lo = mid; else c_hi = mid - 1;
+        }
+        c = c_lo;
+        lo = max(lo, col_group_ptr[c]);
+    }
+    comp_lo[w] = lo;
+    comp_col[w] = c;
 }
 
 // col_rank[c], c in 0..NBC: block columns before c that hold a group.  One workgroup: every thread
@@ -872,8 +887,9 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     Arena own0(true);
     own0.reserve(&h->col_blk_ptr, NBC + 1);
     own0.reserve(&h->stripe_ptr, NBR + 1);
-    own0.reserve(&h->ticket, NBC);
-    own0.reserve(&h->comp_lo, NBC);
+    own0.reserve(&h->ticket, (int64_t)h->P);
+    own0.reserve(&h->comp_lo, (int64_t)h->P);
+    own0.reserve(&h->comp_col, (int64_t)h->P);
     own0.reserve(&h->col_group_ptr, NBC + 1);
     own0.reserve(&h->fixed_start, (int64_t)h->P + 1);
     own0.reserve(&h->fixed_col, (int64_t)h->P);
@@ -881,10 +897,11 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own0.reserve(&h->col_rank, NBC + 1);
     HBP_TRY(own0.commit());
     h->arena[0] = own0.base();
-    HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)NBC, st));
+    HBP_HIP(hipMemsetAsync(h->ticket, 0, sizeof(uint32_t) * (size_t)h->P, st));
     HBP_HIP(hipMemsetAsync(h->col_blk_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->stripe_ptr, 0, sizeof(int32_t) * (size_t)(NBR + 1), st));
-    HBP_HIP(hipMemsetAsync(h->comp_lo, 0, sizeof(int32_t) * (size_t)NBC, st));
+    HBP_HIP(hipMemsetAsync(h->comp_lo, 0, sizeof(int32_t) * (size_t)h->P, st));
+    HBP_HIP(hipMemsetAsync(h->comp_col, 0, sizeof(int32_t) * (size_t)h->P, st));
     HBP_HIP(hipMemsetAsync(h->col_group_ptr, 0, sizeof(int32_t) * (size_t)(NBC + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_start, 0, sizeof(int32_t) * (size_t)(h->P + 1), st));
     HBP_HIP(hipMemsetAsync(h->fixed_col, 0, sizeof(int32_t) * (size_t)h->P, st));
@@ -1068,10 +1085,11 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
         const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight,
                          (int64_t)h->group_weight};
-        k_comp_lo<<<blocks_for(h->NBC, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->fixed_q8, h->comp_lo);
         k_col_rank<<<1, 256, 0, st>>>(h->col_group_ptr, NBC, h->col_rank);
         k_fixed_start<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->col_group_ptr, wt, h->col_rank, (int64_t)h->column_weight,
                                                                           NBC, (int32_t)h->G, h->P, h->fixed_start, h->fixed_col);
+        k_comp_lo<<<blocks_for((int64_t)h->P, 256), 256, 0, st>>>(h->col_group_ptr, wt, NBC, h->P, h->fixed_q8, h->fixed_start,
+                                                                  h->fixed_col, h->comp_lo, h->comp_col);
     }
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));

@@ -19,12 +19,12 @@ constexpr int64_t kMaxDense = int64_t(1) << 27;  // NBR * NBC table entries
 struct Layout {
     int32_t R, C, W;
     int32_t B, S, G;
-    int32_t NBR, NBC;
+    int32_t NBR, NBC, P;
     int32_t competitive;  // 0 when every group is fixed (nothing to compete for)
     int64_t n_rows, n_cols;
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot, *group_rounds;
-    const int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;  // schedule (Section 3.3)
+    const int32_t *col_group_ptr, *comp_lo, *comp_col, *fixed_start, *fixed_col;  // schedule (Section 3.3)
     const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
     int32_t NM;                                                        // row blocks with several units
     int32_t claim;  // competitive groups a worker claims from a column's counter at a time
@@ -48,7 +48,7 @@ struct hbp_handle_s {
     void *arena[2];
     int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     int32_t *group_ptr, *group_slot;
-    int32_t *col_group_ptr, *comp_lo, *fixed_start, *fixed_col;
+    int32_t *col_group_ptr, *comp_lo, *comp_col, *fixed_start, *fixed_col;
     int32_t *group_rounds;               // [G+1] prefix sums of the groups' longest rows
     int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;
     int64_t U, NM;       // combine work units, row blocks cut into several units
@@ -63,7 +63,7 @@ struct hbp_handle_s {
     int32_t value_bytes; // 4: fp32 values (data, partial, x, y), 8: fp64
     void *data;
     void *partial;       // [S] per-slot partial sums of the SpMV part
-    uint32_t *ticket;    // [NBC] competitive groups of every block column claimed so far, zero between calls
+    uint32_t *ticket;    // [P] competitive groups of every worker's range claimed so far, zero between calls
 };
 
 namespace hbp {

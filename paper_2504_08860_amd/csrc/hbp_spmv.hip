@@ -1,10 +1,11 @@
 // Two-step HBP SpMV (Fig. 1, Algorithm 3, Section 3.3) and the in-repo CSR baselines.
 //
-// SpMV part: P persistent workgroups ("workers").  A worker first runs its fixed groups, a
-// contiguous piece of the column-major group list, then competes for the rest: each block
-// column has an atomic ticket counter over its competitive groups, and a worker draws tickets
-// from the column whose slice of x it has staged in LDS (the paper's single ticket lock, split
-// per column so that a 128 KB slice is not restaged for every claim).  A wavefront takes one
+// SpMV part: P persistent workgroups ("workers").  The column-major group list is cut into P
+// ranges; a worker first runs the fixed groups of its range, then competes for the rest: every
+// range has an atomic counter over its competitive groups (the tail of the range, inside one
+// block column), and a worker claims groups from the range whose slice of x it has staged in
+// LDS: its own first, then the range with the most left (the paper's single ticket lock, split
+// per range so that a 128 KB slice is not restaged for every claim).  A wavefront takes one
 // group at a time; lane q owns slot q of the group and walks its row round by round.  The
 // distance add_sign of Algorithm 3 is not read from memory: in round k the lanes still alive
 // are known from a ballot over the lane lengths, and a lane's element is the base of the
@@ -190,11 +191,11 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     uint64_t dbg_stage = 0, dbg_fixed_end = 0;
     extern __shared__ __align__(16) unsigned char dyn_lds[];
     T *const xs = reinterpret_cast<T *>(dyn_lds);  // the staged vector segment, C values
-    __shared__ int32_t sh_next;  // ticket / next column, broadcast to the worker
+    __shared__ int32_t sh_next;  // whose range to compete for next, broadcast to the worker
     __shared__ unsigned long long sh_rng;  // groups of the worker still to draw: end << 32 | next
-    __shared__ int32_t sh_dry;   // nothing more to claim from the current block column
+    __shared__ int32_t sh_dry;   // nothing more to claim from the current competitive part
     __shared__ int32_t sh_lock;  // end of the last range reported as used up
-    __shared__ int32_t sh_col[3];  // the current block column, its first competitive group, its end
+    __shared__ int32_t sh_col[3];  // whose competitive part is being claimed, its first group, its end
     __shared__ T sh_hand[THREADS];  // per wavefront: hand-over of span sums to the owning lanes
     constexpr int kHeavyCap = 64;
     __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
@@ -256,14 +257,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     // Draws.  sh_rng holds the worker's current range of groups; a draw takes GP groups off its
     // front with one LDS atomic (draw_issue) whose result is looked at an iteration later
     // (draw_resolve), so that its latency is never waited for.  A draw that finds the range
-    // used up, in a worker that competes for this block column (Section 3.3), leads to a claim:
+    // used up, in a worker that competes for some worker's range (Section 3.3), leads to a claim:
     // the first wavefront to report the range that ended at `end` as used up (atomic max on
-    // sh_lock; the ends of successive ranges grow) takes the column's next `claim` competitive
-    // groups from the column's counter in global memory and publishes them as the new range;
+    // sh_lock; the ends of successive ranges grow) takes that range's next `claim` competitive
+    // groups from its counter in global memory and publishes them as the new range;
     // the other wavefronts wait for the range to move (a bounded wait: a wavefront that gives
     // up just stops drawing, the claimed groups are walked by those that go on).  So the
     // wavefronts of a worker pass from fixed to competitive groups and from claim to claim
-    // without a barrier.  Once the column has nothing left (or in a worker that does not
+    // without a barrier.  Once the competitive part has nothing left (or in a worker that does not
     // compete) a used-up range makes the draw, and every later draw of the wavefront in this
     // range, return kNone.
     constexpr int32_t kNone = 0x7fffffff;
@@ -292,8 +293,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             if (lane == 0) reported = atomicMax(&sh_lock, end);
             reported = __builtin_amdgcn_readfirstlane(reported);
             if (reported < end) {
-                // first to report this range as used up: claim the column's next groups
-                // (the column's numbers sit in LDS: this path is rare, registers are not)
+                // first to report this range as used up: claim the next competitive groups
+                // (their owner's numbers sit in LDS: this path is rare, registers are not)
                 const int32_t claim = L.claim, col_end = sh_col[2];
                 uint32_t t = 0;
                 if (lane == 0) t = atomicAdd(&col_ticket[sh_col[0]], (uint32_t)claim);
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         }
     };
     // Runs the groups [g_begin, g_end) of block column bn with all wavefronts of the worker.
-    auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end, bool compete) __attribute__((always_inline)) {
+    auto run_range = [&](int32_t bn, int32_t g_begin, int32_t g_end, bool compete, int32_t owner) __attribute__((always_inline)) {
         const uint64_t t_in = dbg ? wall_clock64() : 0;
         __syncthreads();  // every wavefront has left the previous range (and its slice of x)
         if (threadIdx.x == 0) {
@@ -390,9 +391,9 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             sh_dry = compete ? 0 : 1;
             sh_lock = -1;
             sh_heavy_n = 0;
-            sh_col[0] = bn;
-            sh_col[1] = L.comp_lo[bn];
-            sh_col[2] = L.col_group_ptr[bn + 1];
+            sh_col[0] = owner;  // whose competitive groups are claimed from here on
+            sh_col[1] = L.comp_lo[owner];
+            sh_col[2] = L.fixed_start[owner + 1];
         }
         stop = false;
         __syncthreads();
@@ -654,31 +655,30 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 
     // The worker's ranges, one after the other (run_range is expanded once, here):
     //   phase 0, fixed part (Section 3.3): the group list is cut into P contiguous ranges of
-    //     equal weight; worker w runs, column by column, the groups of its range that lie in
-    //     the fixed part of their column (below comp_lo).  In the last column of its range the
-    //     worker goes on, without a break, to claim that column's competitive groups (its
-    //     segment of x is staged already);
-    //   phase 1: a worker without fixed groups competes in the column its range starts in;
-    //   phase 2, competitive part: the counter of a block column holds how many of its
-    //     competitive groups, [comp_lo, end of column), have been claimed; a worker whose
-    //     column has run dry moves to the column with the most groups left (and stages that
-    //     segment of x), until no column has any.
+    //     equal weight; worker w runs, column by column, the groups of its range below comp_lo[w].
+    //     The groups from comp_lo[w] on, all in the last column of the range, are its competitive
+    //     part: the worker goes on, without a break, to claim them piece by piece from the range's
+    //     counter (the segment of x is staged already), and so may others;
+    //   phase 2, competitive part: the counter of a range holds how many of its competitive groups
+    //     have been claimed; a worker that has run out of work moves to the range with the most
+    //     groups left (and stages the segment of x of that range's last column), until no range
+    //     has any.  So a range that takes longer than its weight said is finished by the workers
+    //     that were faster than theirs.
     const bool competitive = L.competitive != 0;
-    int32_t home = L.fixed_col[worker], col = home;
+    int32_t col = L.fixed_col[worker];
     int32_t g_next = L.fixed_start[worker];
     const int32_t g_stop = L.fixed_start[worker + 1];
-    bool competed_at_home = false;
+    const int32_t own_lo = L.comp_lo[worker];
     for (int phase = 0;;) {
-        int32_t r_bn = 0, r_g0 = 0, r_g1 = 0;
+        int32_t r_bn = 0, r_g0 = 0, r_g1 = 0, r_owner = worker;
         bool r_compete = true;
         if (phase == 0) {
             bool found = false;
             while (g_next < g_stop && !found) {
                 const int32_t c_end = L.col_group_ptr[col + 1];
                 if (g_next >= c_end) { col++; continue; }  // columns without groups
-                const int32_t ge = min(g_stop, c_end), fe = max(g_next, min(ge, L.comp_lo[col]));
+                const int32_t ge = min(g_stop, c_end), fe = max(g_next, min(ge, own_lo));
                 const bool last = ge == g_stop;
-                home = col;
                 if (g_next < fe || (last && competitive)) {
                     r_bn = col;
                     // (an empty fixed part is handed over as [0, 0): the ends of a worker's
@@ -686,49 +686,45 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     r_g0 = g_next < fe ? g_next : 0;
                     r_g1 = g_next < fe ? fe : 0;
                     r_compete = last && competitive;
-                    competed_at_home = r_compete;
                     found = true;
                 }
                 g_next = ge;
             }
             if (!found) {
                 if (dbg) dbg_fixed_end = wall_clock64();
-                phase = 1;
+                if (!competitive) break;
+                phase = 2;
                 continue;
             }
-        } else if (phase == 1) {
-            phase = 2;
-            if (!competitive) break;
-            if (competed_at_home) continue;
-            r_bn = home;
         } else {
             if (wave == 0) {
                 int32_t best = -1;
                 uint32_t best_left = 0;
-                for (int32_t c0 = 0; c0 < L.NBC; c0 += 64) {
-                    int32_t c = c0 + lane;
+                for (int32_t v0 = 0; v0 < L.P; v0 += 64) {
+                    int32_t v = v0 + lane;
                     uint32_t left = 0;
-                    if (c < L.NBC) {
-                        const int64_t total = L.col_group_ptr[c + 1] - L.comp_lo[c];
-                        const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (v < L.P) {
+                        const int64_t total = L.fixed_start[v + 1] - L.comp_lo[v];
+                        const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         left = used < total ? (uint32_t)(total - used) : 0u;
                     }
 #pragma unroll
                     for (int d = 32; d > 0; d >>= 1) {
                         const uint32_t o_left = __shfl_xor(left, d);
-                        const int32_t o_c = __shfl_xor(c, d);
-                        if (o_left > left || (o_left == left && o_c < c)) { left = o_left; c = o_c; }
+                        const int32_t o_v = __shfl_xor(v, d);
+                        if (o_left > left || (o_left == left && o_v < v)) { left = o_left; v = o_v; }
                     }
-                    if (left > best_left) { best_left = left; best = c; }
+                    if (left > best_left) { best_left = left; best = v; }
                 }
                 if (lane == 0) sh_next = best;
             }
             __syncthreads();
-            r_bn = sh_next;
+            r_owner = sh_next;
             __syncthreads();  // sh_next is rewritten in the next turn
-            if (r_bn < 0) break;
+            if (r_owner < 0) break;
+            r_bn = L.comp_col[r_owner];
         }
-        run_range(r_bn, r_g0, r_g1, r_compete);
+        run_range(r_bn, r_g0, r_g1, r_compete, r_owner);
     }
     // Row blocks that the combine part cuts into several units are summed into y with atomic
     // adds: their rows of y start at zero.  (Done last: in front of the first range it delays
@@ -768,7 +764,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
     const int32_t unit = blockIdx.x;
     const int32_t bm = L.unit_stripe[unit];
     const bool split = L.unit_ptr[bm + 1] - L.unit_ptr[bm] > 1;
-    for (int64_t i = (int64_t)unit * THREADS + threadIdx.x; i < L.NBC; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
+    for (int64_t i = (int64_t)unit * THREADS + threadIdx.x; i < L.P; i += (int64_t)gridDim.x * THREADS) ticket[i] = 0u;
     const int64_t r0 = (int64_t)bm * L.R;
     const int32_t rows = (int32_t)min((int64_t)L.R, L.n_rows - r0);
     for (int32_t i = threadIdx.x; i < kWaves * L.R; i += THREADS) ys_all[i] = T(0);
@@ -929,14 +925,14 @@ Layout hbp_view(const hbp_handle_s *h)
     Layout L;
     L.R = h->R; L.C = h->C; L.W = h->W;
     L.B = (int32_t)h->B; L.S = (int32_t)h->S; L.G = (int32_t)h->G;
-    L.NBR = (int32_t)h->NBR; L.NBC = (int32_t)h->NBC;
+    L.NBR = (int32_t)h->NBR; L.NBC = (int32_t)h->NBC; L.P = h->P;
     L.competitive = h->fixed_q8 < 256 ? 1 : 0;
     L.n_rows = h->n_rows; L.n_cols = h->n_cols;
     L.blk_bm = h->blk_bm; L.blk_bn = h->blk_bn; L.slot_ptr = h->slot_ptr; L.blk_group_ptr = h->blk_group_ptr;
     L.col_blk_ptr = h->col_blk_ptr; L.stripe_ptr = h->stripe_ptr; L.stripe_blk = h->stripe_blk;
     L.group_ptr = h->group_ptr; L.group_slot = h->group_slot; L.group_rounds = h->group_rounds;
     L.row_local = h->row_local; L.seg_len = h->seg_len; L.col_local = h->col_local; L.data = h->data;
-    L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo;
+    L.col_group_ptr = h->col_group_ptr; L.comp_lo = h->comp_lo; L.comp_col = h->comp_col;
     L.fixed_start = h->fixed_start; L.fixed_col = h->fixed_col;
     L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
     L.NM = (int32_t)h->NM;

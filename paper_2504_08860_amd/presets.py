@@ -9,7 +9,7 @@ PRESETS = {
     3: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256, column_weight=50000),
     # weights from a least-squares fit of the workers' times: a range costs per group, per round and per block
     # column entered (37 us + 23 ns, 5 ns and 14 us), not per nonzero
-    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=240, slot_weight=0,
+    4: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=224, slot_weight=0,
             group_weight=200, round_weight=46, column_weight=126000),
     5: dict(rows_per_block=2048, cols_per_block=32768, rounds_per_batch=4, fixed_fraction_q8=256, column_weight=100000),
 }

@@ -15,7 +15,7 @@ TOL = 1e-5
 # is accumulated in extended precision and rounded once
 TOL_F64 = 168 * 2.0**-53
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
-                 "group_ptr", "group_slot", "group_rounds", "col_group_ptr", "comp_lo", "fixed_start", "fixed_col",
+                 "group_ptr", "group_slot", "group_rounds", "col_group_ptr", "comp_lo", "comp_col", "fixed_start", "fixed_col",
                  "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
 
 

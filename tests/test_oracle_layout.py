@@ -53,7 +53,7 @@ def test_worked_example_compact(oracle):
     assert partial.tolist() == g["compact"]["partial"]
     sch = g["schedule"]
     h2 = build(oracle, m, R=g["R"], C=g["C"], W=g["W"], hash_shift=g["a"], num_workers=sch["P"], fixed_q8=sch["fixed_q8"])
-    for name in ("col_group_ptr", "comp_lo", "fixed_start", "fixed_col"):
+    for name in ("col_group_ptr", "comp_lo", "comp_col", "fixed_start", "fixed_col"):
         assert h2.array(name).tolist() == sch[name], name
 
 
@@ -221,9 +221,9 @@ def test_equal_rows_any_w_is_ell(oracle):
 
 
 def test_schedule_split(oracle):
-    """Section 3.3 split: fixed groups of the P ranges and the per-column competitive tails cover
-    every group exactly once; ranges have equal weight up to one group; every column keeps the
-    stated share of its weight fixed, up to one group."""
+    """Section 3.3 split: the P ranges tile the group list and have equal weight up to one group;
+    every range keeps the stated share of its weight fixed, up to one group, and its competitive
+    tail lies inside the block column of its last group."""
     m = random_csr(300, 300, 0.05, 3)
     for P, q8, sw, gw, cw, colw in [(1, 128, 1, 0, 0, 0), (4, 192, 4, 0, 7, 0), (7, 255, 1, 9, 0, 40), (64, 256, 6, 100, 300, 0),
                                     (5, 0, 0, 1, 50, 1000), (1000, 100, 1, 0, 0, 3), (6, 256, 1, 0, 0, 100000)]:
@@ -239,26 +239,29 @@ def test_schedule_split(oracle):
         assert np.array_equal(cgp, h.array("blk_group_ptr")[h.array("col_blk_ptr")])
         assert fs[0] == 0 and fs[-1] == h.G and np.all(np.diff(fs) >= 0)
         col_of = np.searchsorted(cgp, np.arange(h.G), side="right") - 1
-        covered = np.zeros(h.G, dtype=np.int32)
+        comp_col = h.array("comp_col")
+        assert comp_lo.shape == (P,) and comp_col.shape == (P,)
         for w in range(P):
-            gs = np.arange(fs[w], fs[w + 1])
-            covered[gs[gs < comp_lo[col_of[gs]]]] += 1            # the worker's fixed groups
             if fs[w] < h.G:
                 assert fc[w] == col_of[fs[w]]
             # equal weight: the range starts at the first group whose preceding weight reaches w/P
             assert wt_cut[fs[w]] * P >= w * wt_cut[-1]
             assert fs[w] == 0 or wt_cut[fs[w] - 1] * P < w * wt_cut[-1]
-        for c in range(h.NBC):
-            covered[comp_lo[c]:cgp[c + 1]] += 1                    # the column's competitive groups
-            assert cgp[c] <= comp_lo[c] <= cgp[c + 1]
-            tot = wt[cgp[c + 1]] - wt[cgp[c]]
-            assert (wt[comp_lo[c]] - wt[cgp[c]]) * 256 >= tot * q8
-            assert comp_lo[c] == cgp[c] or (wt[comp_lo[c] - 1] - wt[cgp[c]]) * 256 < tot * q8
-        assert np.all(covered == 1)
+            g0, g1 = fs[w], fs[w + 1]
+            assert g0 <= comp_lo[w] <= g1
+            if g1 == g0:
+                assert comp_col[w] == fc[w]
+                continue
+            last_col = col_of[g1 - 1]
+            assert comp_col[w] == last_col and np.all(col_of[comp_lo[w]:g1] == last_col)
+            tot = wt[g1] - wt[g0]
+            share = next(g for g in range(g0, g1 + 1) if (wt[g] - wt[g0]) * 256 >= tot * q8)   # by the definition
+            assert comp_lo[w] == max(share, cgp[last_col])
         if q8 == 256:
-            assert np.array_equal(comp_lo, cgp[1:])                # nothing left to competition
+            assert np.array_equal(comp_lo, fs[1:])                 # nothing left to competition
         if q8 == 0:
-            assert np.array_equal(comp_lo, cgp[:-1])               # everything competitive
+            # everything of a range's last block column is competitive
+            assert all(comp_lo[w] == max(fs[w], cgp[comp_col[w]]) for w in range(P) if fs[w + 1] > fs[w])
         if colw == 100000:
             # a column weighs far more than all groups: every worker's range starts at a column's
             # first group or just behind it (there the column's charge has been paid)
