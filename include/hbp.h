@@ -111,7 +111,7 @@ typedef struct {
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = as many as
                                   fit on the device at once, but no more than one per threads_per_worker / 64 groups */
-    int32_t fixed_fraction_q8; /* share of every worker's range that is pre-assigned, in 1/256; -1 = default */
+    int32_t fixed_fraction_q8; /* share of every worker's range that is pre-assigned, in 1/256; -1 = default 224 */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
     int32_t claim_chunk;       /* competitive part: groups per wavefront that a worker claims from a
                                   block column at a time, 1..1024; 0 = default (two draws per wavefront) */

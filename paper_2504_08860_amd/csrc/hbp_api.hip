@@ -69,7 +69,7 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
     if (p.rows_per_block == 0) p.rows_per_block = 512;
     if (p.cols_per_block == 0) p.cols_per_block = 4096;
     if (p.group_width == 0) p.group_width = 64;
-    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 192;
+    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 224;
     if (p.slot_weight < 0) p.slot_weight = 4;
     if (p.group_weight < 0) p.group_weight = 0;
     if (p.round_weight < 0) p.round_weight = 8;

@@ -27,7 +27,9 @@ struct Layout {
     const int32_t *col_group_ptr, *comp_lo, *comp_col, *fixed_start, *fixed_col;  // schedule (Section 3.3)
     const int32_t *unit_ptr, *unit_stripe, *unit_k, *multi_stripes;               // combine work units
     int32_t NM;                                                        // row blocks with several units
-    int32_t claim;  // competitive groups a worker claims from a column's counter at a time
+    int32_t claim;  // competitive groups a worker claims from a range's counter at a time
+    int32_t SW, RW, GW;  // schedule weights of a slot, a round, a group (a nonzero weighs 1)
+    int32_t steal_min;   // weight a range's competitive part must have left for another worker to enter it
     int32_t heavy_rounds;  // a group with a longer row is walked by all wavefronts of a worker together
     const uint16_t *row_local, *seg_len, *col_local;
     const void *data;  // float or double, by the handle's value type

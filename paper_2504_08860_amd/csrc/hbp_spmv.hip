@@ -661,8 +661,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     //     counter (the segment of x is staged already), and so may others;
     //   phase 2, competitive part: the counter of a range holds how many of its competitive groups
     //     have been claimed; a worker that has run out of work moves to the range with the most
-    //     groups left (and stages the segment of x of that range's last column), until no range
-    //     has any.  So a range that takes longer than its weight said is finished by the workers
+    //     weight left (and stages the segment of x of that range's last column), until no range
+    //     has enough left to be worth entering.  So a range that takes longer than its weight said is finished by the workers
     //     that were faster than theirs.
     const bool competitive = L.competitive != 0;
     int32_t col = L.fixed_col[worker];
@@ -704,9 +704,22 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     int32_t v = v0 + lane;
                     uint32_t left = 0;
                     if (v < L.P) {
-                        const int64_t total = L.fixed_start[v + 1] - L.comp_lo[v];
+                        // weight of the competitive groups of range v that nobody has claimed; a range
+                        // with less left than entering it costs (staging its segment of x, about two
+                        // block columns' weight counting the pipeline restart) is left to those who
+                        // are there already
+                        const int32_t end = L.fixed_start[v + 1];
+                        const int64_t total = end - L.comp_lo[v];
                         const int64_t used = (int64_t)__hip_atomic_load(&col_ticket[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        left = used < total ? (uint32_t)(total - used) : 0u;
+                        if (used < total) {
+                            const int32_t g = L.comp_lo[v] + (int32_t)used;
+                            auto before = [&](int32_t i) {
+                                return (int64_t)L.group_ptr[i] + (int64_t)L.SW * L.group_slot[i] + (int64_t)L.RW * L.group_rounds[i] +
+                                       (int64_t)L.GW * i;
+                            };
+                            const int64_t w_left = before(end) - before(g);
+                            left = w_left < L.steal_min ? 0u : w_left > 0xffffffffll ? 0xffffffffu : (uint32_t)w_left;
+                        }
                     }
 #pragma unroll
                     for (int d = 32; d > 0; d >>= 1) {
@@ -937,6 +950,8 @@ Layout hbp_view(const hbp_handle_s *h)
     L.unit_ptr = h->unit_ptr; L.unit_stripe = h->unit_stripe; L.unit_k = h->unit_k; L.multi_stripes = h->multi_stripes;
     L.NM = (int32_t)h->NM;
     L.claim = h->claim_chunk * (h->threads / kWave);
+    L.SW = h->slot_weight; L.RW = h->round_weight; L.GW = h->group_weight;
+    L.steal_min = 2 * h->column_weight;
     L.heavy_rounds = h->heavy_rounds;
     return L;
 }
