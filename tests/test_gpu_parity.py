@@ -361,3 +361,36 @@ def test_hip_graph_replay(H, oracle, q8):
             assert np.all(np.abs(y_graph.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs)
     finally:
         H.hbp_free(h)
+
+
+def test_two_handles_on_two_streams(H, oracle):
+    """Two handles may run at the same time on different streams (workers never wait for another
+    workgroup); each result equals what the handle gives alone."""
+    import torch
+    ms = [random_csr(6000, 7000, 0.004, 91, empty_row_frac=0.1), make_config(5, 0.01)]
+    hs, xs, ys, refs = [], [], [], []
+    for m in ms:
+        ptr, col, val, x = to_dev(m)
+        hs.append(H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, rows_per_block=512, cols_per_block=2048, fixed_fraction_q8=200))
+        xs.append(x)
+        y = torch.empty(m.n_rows, device="cuda")
+        H.hbp_spmv(hs[-1], x, y)
+        torch.cuda.synchronize()
+        refs.append(y.clone())
+        ys.append(torch.full((m.n_rows,), float("nan"), device="cuda"))
+    try:
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for rep in range(3):
+            for y in ys:
+                y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for h, x, y, s in zip(hs, xs, ys, streams):
+                for _ in range(4):                      # several calls in a row on each stream
+                    H.hbp_spmv(h, x, y, stream=s)
+            torch.cuda.synchronize()
+            for m, y, ref in zip(ms, ys, refs):
+                y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+                assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs), f"rep {rep} {m.name}"
+    finally:
+        for h in hs:
+            H.hbp_free(h)
