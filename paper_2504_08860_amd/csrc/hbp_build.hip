@@ -1050,7 +1050,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
                                                             h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
-                                                            group_blk, (uint32_t)h->heavy_rounds, longest_all);
+                                                            group_blk, (uint32_t)long_rounds_of(h->heavy_rounds), longest_all);
     HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
@@ -1073,7 +1073,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipMemcpyAsync(&n_multi, multi_idx + NBR, 4, hipMemcpyDeviceToHost, st));
     HBP_HIP(hipStreamSynchronize(st));
     h->U = n_units; h->NM = n_multi;
-    h->longest_segment = (int32_t)longest;  // 0 unless above heavy_rounds
+    h->longest_segment = (int32_t)longest;  // 0 unless it makes a group long
     return HBP_OK;
 }
 

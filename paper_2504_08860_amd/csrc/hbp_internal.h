@@ -14,6 +14,8 @@ constexpr int kMaxC = 32768;         // columns per block: fp32 vector segment o
 constexpr int kMaxC64 = 16384;       // the same 128 KB with fp64 values
 constexpr int kMaxR64 = 4096;        // fp64: the combine part keeps four copies of a y slice in LDS
 constexpr int64_t kMaxDense = int64_t(1) << 27;  // NBR * NBC table entries
+// rows longer than this (and up to heavy_group_rounds) make their group a "long" one
+inline int32_t long_rounds_of(int32_t heavy_rounds) { return heavy_rounds / 8 > 0 ? heavy_rounds / 8 : 1; }
 
 // Device-side view of the layout, passed by value to kernels.
 struct Layout {
@@ -31,6 +33,7 @@ struct Layout {
     int32_t SW, RW, GW;  // schedule weights of a slot, a round, a group (a nonzero weighs 1)
     int32_t steal_min;   // weight a range's competitive part must have left for another worker to enter it
     int32_t heavy_rounds;  // a group with a longer row is walked by all wavefronts of a worker together
+    int32_t long_rounds;   // a group with a longer row (up to heavy_rounds) waits for a wavefront of its own
     const uint16_t *row_local, *seg_len, *col_local;
     const void *data;  // float or double, by the handle's value type
 };
@@ -57,7 +60,7 @@ struct hbp_handle_s {
     int32_t unit_slots;  // target slots per combine unit
     int32_t heavy_rounds;  // groups with a longer row are shared by a worker's wavefronts
     int32_t group_weight;  // schedule weight of a group as such
-    int32_t longest_segment;  // longest row segment of the matrix
+    int32_t longest_segment;  // longest row segment of the matrix (0 unless it makes a group long)
     int32_t round_weight;  // schedule weight of a group on top of its nonzeros and slots
     int32_t column_weight;  // schedule weight of entering a block column
     int32_t *col_rank;     // [NBC+1] non-empty block columns before each column

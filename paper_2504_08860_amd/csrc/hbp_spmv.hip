@@ -200,6 +200,9 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     constexpr int kHeavyCap = 64;
     __shared__ int32_t sh_heavy[kHeavyCap];  // heavy groups of the current range, left to the whole worker
     __shared__ int32_t sh_heavy_n;
+    constexpr int kLongCap = 256;
+    __shared__ int32_t sh_long[kLongCap];  // long groups of the current range, each left to the next free wavefront
+    __shared__ int32_t sh_long_n, sh_long_next;
     __shared__ int32_t sh_lens[THREADS];  // per wavefront: segment lengths of the heavy group being cut
     __shared__ int32_t sh_cut_k[THREADS / 64 + 1];   // heavy group: first round of every wavefront's share
     __shared__ uint32_t sh_cut_pos[THREADS / 64 + 1];  // and the nonzeros before that round
@@ -391,6 +394,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             sh_dry = compete ? 0 : 1;
             sh_lock = -1;
             sh_heavy_n = 0;
+            sh_long_n = 0;
+            sh_long_next = 0;
             sh_col[0] = owner;  // whose competitive groups are claimed from here on
             sh_col[1] = L.comp_lo[owner];
             sh_col[2] = L.fixed_start[owner + 1];
@@ -451,17 +456,22 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             if (g == kNone && g1 == kNone && g2 == kNone) break;  // and this wavefront has stopped drawing
             raw2 = draw_issue();
             // A group with a row of more than heavy_rounds nonzeros would keep this wavefront busy
-            // long after the rest of the worker has run dry: it goes on the worker's list and
-            // looks empty here (unless the list is full: then this wavefront walks it alone).
-            if (HEAVY && (!kShortPacks || pack_longest > L.heavy_rounds)) {
+            // long after the rest of the worker has run dry: it goes on the worker's heavy list and
+            // looks empty here (unless the list is full: then this wavefront walks it alone).  A
+            // group with a row of more than long_rounds goes on the long list: such groups come in
+            // runs (the last groups of a block), a pack would hand several of them to one
+            // wavefront to walk one after the other, and they are taken one per wavefront instead
+            // once the range's other groups are done.
+            if (HEAVY && (!kShortPacks || pack_longest > L.long_rounds)) {
 #pragma unroll
                 for (int q = 0; q < GP; q++) {
-                    if (__ballot(n[q] > L.heavy_rounds)) {
+                    if (__ballot(n[q] > L.long_rounds)) {
+                        const bool heavy = __ballot(n[q] > L.heavy_rounds) != 0;
                         int32_t idx = 0;
-                        if (lane == 0) idx = atomicAdd(&sh_heavy_n, 1);
+                        if (lane == 0) idx = atomicAdd(heavy ? &sh_heavy_n : &sh_long_n, 1);
                         idx = __builtin_amdgcn_readfirstlane(idx);
-                        if (idx < kHeavyCap) {
-                            if (lane == 0) sh_heavy[idx] = g + q;
+                        if (idx < (heavy ? kHeavyCap : kLongCap)) {
+                            if (lane == 0) (heavy ? sh_heavy : sh_long)[idx] = g + q;
                             n[q] = 0;
                             s1[q] = s0[q];
                         }
@@ -597,6 +607,23 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         // are added in LDS in wavefront order.
         if constexpr (!HEAVY) return;
         __syncthreads();
+        // Long groups of this range: one wavefront each, whoever is free next.
+        const int32_t n_long = min(sh_long_n, kLongCap);
+        if (n_long > 0) {
+            for (;;) {
+                int32_t i = 0;
+                if (lane == 0) i = atomicAdd(&sh_long_next, 1);
+                i = __builtin_amdgcn_readfirstlane(i);
+                if (i >= n_long) break;
+                const int32_t gl = sh_long[i];
+                const int32_t ls0 = uniform_load(L.group_slot, gl), ls1 = uniform_load(L.group_slot, gl + 1);
+                uint32_t pos = (uint32_t)uniform_load(L.group_ptr, gl);
+                const int32_t len = ls0 + lane < ls1 ? (int32_t)L.seg_len[ls0 + lane] : 0;
+                T sum = T(0);
+                walk_rounds(pos, len, 0, sum);
+                if (ls0 + lane < ls1) partial[ls0 + lane] = sum;
+            }
+        }
         const int32_t n_heavy = min(sh_heavy_n, kHeavyCap);
         for (int32_t i = 0; i < n_heavy; i++) {
             const int32_t gh = sh_heavy[i];
@@ -953,6 +980,7 @@ Layout hbp_view(const hbp_handle_s *h)
     L.SW = h->slot_weight; L.RW = h->round_weight; L.GW = h->group_weight;
     L.steal_min = 2 * h->column_weight;
     L.heavy_rounds = h->heavy_rounds;
+    L.long_rounds = long_rounds_of(h->heavy_rounds);
     return L;
 }
 
@@ -1008,7 +1036,7 @@ static int launch_part_t(const hbp_handle_s *h, const T *x, T *y, hipStream_t st
 {
     const Layout L = hbp_view(h);
     // the kernel that can share heavy groups among a worker's wavefronts only where the matrix has one
-    if (h->longest_segment > h->heavy_rounds) {
+    if (h->longest_segment > long_rounds_of(h->heavy_rounds)) {
         if (h->threads == 1024) return launch_part_u<1024, true, T>(h, L, x, y, st, dbg);
         if (h->threads == 512) return launch_part_u<512, true, T>(h, L, x, y, st, dbg);
         return launch_part_u<256, true, T>(h, L, x, y, st, dbg);
