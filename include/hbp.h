@@ -128,7 +128,9 @@ typedef struct {
                                   its longest row), in nonzeros: 0..1024; -1 = default 8             */
     int32_t heavy_group_rounds;/* a group with a row of more nonzeros than this (inside the block) is walked
                                   by all wavefronts of its worker together, each taking an equal share of
-                                  its nonzeros, instead of by one: >= 1; 0 = default 2048              */
+                                  its nonzeros, instead of by one: >= 1; 0 = default 2048.  A group with a row of
+                                  more than an eighth of this waits until the worker's other groups are done and
+                                  is then walked by the next free wavefront                              */
     uint32_t flags;            /* HBP_FLAG_*                                                    */
     int32_t column_weight;     /* schedule weight of entering a block column (the worker fetches its segment
                                   of x), in nonzeros, charged to the column's first group when the group list
