@@ -394,3 +394,24 @@ def test_two_handles_on_two_streams(H, oracle):
     finally:
         for h in hs:
             H.hbp_free(h)
+
+
+@pytest.mark.parametrize("rounds,threads", [(4, 512), (8, 1024)])
+def test_long_group_list_overflows(H, oracle, rounds, threads):
+    """Groups with a row above heavy_group_rounds / 8 wait on a per-range list for a wavefront of
+    their own.  Here nearly every group is such a group and a single worker holds hundreds of them:
+    the list (256 entries) overflows and the rest are walked where they were drawn; a few rows are
+    long enough for the cooperative heavy path as well."""
+    from workloads import CsrMatrix
+    rng = np.random.default_rng(12)
+    n_cols = 3000
+    lens = np.r_[rng.integers(3, 11, 30000), [900, 40, 35], rng.integers(0, 3, 2000)]
+    rng.shuffle(lens)
+    col = np.concatenate([np.sort(rng.choice(n_cols, n, replace=False)) for n in lens]).astype(np.int32)
+    ptr = np.r_[0, np.cumsum(lens)].astype(np.int32)
+    m = CsrMatrix("long_list", len(lens), n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32),
+                  rng.uniform(-1, 1, n_cols).astype(np.float32))
+    for workers, q8 in ((1, 256), (3, 128)):
+        check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=4096, cols_per_block=4096,
+                             rounds_per_batch=rounds, threads_per_worker=threads, num_workers=workers,
+                             fixed_fraction_q8=q8, heavy_group_rounds=16)
