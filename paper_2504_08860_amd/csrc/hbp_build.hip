@@ -278,59 +278,116 @@ __global__ __launch_bounds__(256) void k_word_rows(const int32_t *__restrict__ p
     word_row[w] = (int32_t)lo;
 }
 
-// One wavefront per 64 consecutive nonzeros: segment-start bits and their count.
+// A wavefront takes kWordsPerWave words of 64 consecutive nonzeros each, all loads issued before
+// the first use: segment-start bits of every word and their count.  (One word per wavefront
+// left the kernel waiting on a single load per lane.)  shift_c >= 0: C = 2^shift_c.
+constexpr int kWordsPerWave = 4;
+
+__device__ __forceinline__ int32_t block_column(int32_t c, int32_t C, int32_t shift_c)
+{
+    return shift_c >= 0 ? c >> shift_c : c / C;
+}
+
 __global__ __launch_bounds__(256) void k_seg_flags(const int32_t *__restrict__ col, const uint32_t *__restrict__ row_bits,
-                                                   int64_t nnz, int64_t n_cols, int32_t C, int64_t n_words, int validate,
-                                                   uint64_t *__restrict__ seg_bits, uint32_t *__restrict__ seg_cnt,
-                                                   int32_t *__restrict__ err)
+                                                   int64_t nnz, int64_t n_cols, int32_t C, int32_t shift_c, int64_t n_words,
+                                                   int validate, uint64_t *__restrict__ seg_bits,
+                                                   uint32_t *__restrict__ seg_cnt, int32_t *__restrict__ err)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (w >= n_words) return;
-    const int64_t j = w * 64 + lane;
-    const bool valid = j < nnz;
-    const int32_t c = valid ? col[j] : 0;
-    int32_t c_prev = __shfl_up(c, 1);
-    if (lane == 0) c_prev = j > 0 && valid ? col[j - 1] : -1;
-    const bool row_start = valid && ((row_bits[j >> 5] >> (j & 31)) & 1u);
-    const bool in_range = c >= 0 && c < n_cols;
-    if (valid && !in_range) atomicOr(err, kErrCol);
-    if (validate && valid && !row_start && c <= c_prev) atomicOr(err, kErrCol);
-    const bool start = valid && (row_start || (c / C) != (c_prev / C));
-    const uint64_t mask = __ballot(start);
-    if (lane == 0) {
-        seg_bits[w] = mask;
-        seg_cnt[w] = (uint32_t)__popcll(mask);
+    const int64_t w0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * kWordsPerWave;
+    if (w0 >= n_words) return;
+    int32_t c[kWordsPerWave];
+    uint32_t bits[kWordsPerWave];
+#pragma unroll
+    for (int u = 0; u < kWordsPerWave; u++) {
+        const int64_t j = (w0 + u) * 64 + lane;
+        c[u] = j < nnz ? col[j] : 0;
+        bits[u] = j < nnz ? row_bits[j >> 5] : 0u;
+    }
+    int32_t before = -1;  // the nonzero in front of this wavefront's first
+    if (lane == 0 && w0 > 0) before = col[w0 * 64 - 1];
+#pragma unroll
+    for (int u = 0; u < kWordsPerWave; u++) {
+        const int64_t w = w0 + u;
+        if (w >= n_words) break;  // wave-uniform
+        const int64_t j = w * 64 + lane;
+        const bool valid = j < nnz;
+        int32_t c_prev = __shfl_up(c[u], 1);
+        const int32_t last_of_prev = u > 0 ? __shfl(c[u > 0 ? u - 1 : 0], 63) : before;
+        if (lane == 0) c_prev = last_of_prev;
+        const bool row_start = valid && ((bits[u] >> (j & 31)) & 1u);
+        const bool in_range = c[u] >= 0 && c[u] < n_cols;
+        if (valid && !in_range) atomicOr(err, kErrCol);
+        if (validate && valid && !row_start && c[u] <= c_prev) atomicOr(err, kErrCol);
+        const bool start = valid && (row_start || block_column(c[u], C, shift_c) != block_column(c_prev, C, shift_c));
+        const uint64_t mask = __ballot(start);
+        if (lane == 0) {
+            seg_bits[w] = mask;
+            seg_cnt[w] = (uint32_t)__popcll(mask);
+        }
     }
 }
 
-// Segment records in CSR order.
+// Segment list: every set bit of seg_bits becomes a segment (first nonzero, row, block column).
+// A wavefront takes kWordsPerWave words; the row of a segment start is found by a binary search
+// over the rows its word spans, the searches of the wavefront's words advancing together so that
+// their loads overlap.
 __global__ __launch_bounds__(256) void k_seg_emit(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
                                                   const uint64_t *__restrict__ seg_bits, const uint32_t *__restrict__ word_off,
                                                   const int32_t *__restrict__ word_row, int64_t nnz, int64_t n_cols,
-                                                  int32_t R, int32_t C, int32_t NBR, int64_t n_words,
+                                                  int32_t R, int32_t C, int32_t shift_c, int32_t NBR, int64_t n_words,
                                                   int32_t *__restrict__ seg_j, int32_t *__restrict__ seg_row,
                                                   int32_t *__restrict__ seg_bn)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (w >= n_words) return;
-    const uint64_t mask = seg_bits[w];
-    if (w == n_words - 1 && lane == 0) seg_j[word_off[n_words]] = (int32_t)nnz;  // sentinel: end of the last segment
-    if (!((mask >> lane) & 1ull)) return;
-    const int64_t j = w * 64 + lane;
-    const int32_t c = col[j];
-    if (c < 0 || c >= n_cols) return;  // already reported; never index with it
-    int32_t lo = word_row[w], hi = word_row[w + 1];
-    while (lo < hi) {                  // largest row with ptr[row] <= j
-        const int32_t mid = lo + ((hi - lo + 1) >> 1);
-        if (ptr[mid] <= j) lo = mid; else hi = mid - 1;
+    const int64_t w0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * kWordsPerWave;
+    if (w0 >= n_words) return;
+    uint64_t mask[kWordsPerWave];
+    int32_t c[kWordsPerWave], lo[kWordsPerWave], hi[kWordsPerWave];
+    uint32_t off[kWordsPerWave];
+    bool mine[kWordsPerWave];
+#pragma unroll
+    for (int u = 0; u < kWordsPerWave; u++) {
+        const int64_t w = min(w0 + u, n_words - 1);
+        mask[u] = w0 + u < n_words ? seg_bits[w] : 0ull;
+        off[u] = word_off[w];
+        lo[u] = word_row[w];
+        hi[u] = word_row[w + 1];
     }
-    const uint32_t s = word_off[w] + (uint32_t)lanes_below(mask);
-    const int32_t bn = c / C;
-    seg_j[s] = (int32_t)j;
-    seg_row[s] = lo;
-    seg_bn[s] = bn;
+    if (w0 + kWordsPerWave >= n_words && lane == 0) seg_j[word_off[n_words]] = (int32_t)nnz;  // sentinel: end of the last segment
+#pragma unroll
+    for (int u = 0; u < kWordsPerWave; u++) {
+        mine[u] = (mask[u] >> lane) & 1ull;
+        c[u] = mine[u] ? col[(w0 + u) * 64 + lane] : 0;
+        if (c[u] < 0 || c[u] >= n_cols) mine[u] = false;  // already reported; never index with it
+        if (!mine[u]) hi[u] = lo[u];
+    }
+    for (;;) {  // largest row with ptr[row] <= j, for all words at once
+        bool any = false;
+        int32_t mid[kWordsPerWave], p[kWordsPerWave];
+#pragma unroll
+        for (int u = 0; u < kWordsPerWave; u++) {
+            mid[u] = lo[u] + ((hi[u] - lo[u] + 1) >> 1);
+            any |= lo[u] < hi[u];
+        }
+        if (!__ballot(any)) break;
+#pragma unroll
+        for (int u = 0; u < kWordsPerWave; u++) p[u] = ptr[mid[u]];
+#pragma unroll
+        for (int u = 0; u < kWordsPerWave; u++) {
+            if (lo[u] < hi[u]) {
+                if (p[u] <= (w0 + u) * 64 + lane) lo[u] = mid[u]; else hi[u] = mid[u] - 1;
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kWordsPerWave; u++) {
+        if (!mine[u]) continue;
+        const uint32_t s = off[u] + (uint32_t)lanes_below(mask[u]);
+        seg_j[s] = (int32_t)((w0 + u) * 64 + lane);
+        seg_row[s] = lo[u];
+        seg_bn[s] = block_column(c[u], C, shift_c);
+    }
 }
 
 // ------------------------------------------------------------------ step 4: block table
@@ -968,11 +1025,14 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     // steps 1-3
     k_row_bits<<<blocks_for(n_rows, 256), 256, 0, st>>>(csr_ptr, n_rows, nnz, row_bits, d_err);
     k_word_rows<<<blocks_for(n_words + 1, 256), 256, 0, st>>>(csr_ptr, n_rows, n_words, word_row);
-    k_seg_flags<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_col, row_bits, nnz, n_cols, C, n_words,
-                                                       (p.flags & HBP_FLAG_VALIDATE) ? 1 : 0, seg_bits, seg_cnt, d_err);
+    int32_t shift_c = -1;  // C = 2^shift_c, or -1
+    for (int32_t b = 0; b < 31; b++)
+        if (C == (int32_t(1) << b)) shift_c = b;
+    k_seg_flags<<<blocks_for(n_words, 4 * kWordsPerWave), 256, 0, st>>>(csr_col, row_bits, nnz, n_cols, C, shift_c, n_words,
+                                                                       (p.flags & HBP_FLAG_VALIDATE) ? 1 : 0, seg_bits, seg_cnt, d_err);
     HBP_TRY(exclusive_scan<kOpIdentity>(seg_cnt, word_off, n_words, 1, scan_tmp, st));
-    k_seg_emit<<<blocks_for(n_words, 4), 256, 0, st>>>(csr_ptr, csr_col, seg_bits, word_off, word_row, nnz, n_cols, R, C,
-                                                      (int32_t)NBR, n_words, seg_j, seg_row, seg_bn);
+    k_seg_emit<<<blocks_for(n_words, 4 * kWordsPerWave), 256, 0, st>>>(csr_ptr, csr_col, seg_bits, word_off, word_row, nnz, n_cols, R, C,
+                                                                      shift_c, (int32_t)NBR, n_words, seg_j, seg_row, seg_bn);
     k_count_blocks<<<blocks_for(nnz, kTileSegs), 256, 0, st>>>(seg_row, seg_bn, word_off + n_words, d_err, R, (int32_t)NBR, (int32_t)NBC,
                                                                dense_cnt);
     // step 4: scans over the block table
