@@ -242,6 +242,12 @@ int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const
 int hbp_csr_spmv_f64(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val,
                      const double *x, double *y, int64_t n_rows, void *stream);
 
+/* hbp_build keeps its scratch memory (a few hundred megabytes for the large workloads, per
+ * device) for the next build instead of freeing it: freeing costs a good part of a build.
+ * Builds of one process therefore run one at a time.  This call gives the memory back (no build
+ * may be running). */
+int hbp_release_workspace(void);
+
 const char *hbp_status_string(int status);
 /* hipError_t of the most recent HBP_ERR_HIP on this thread, as int. */
 int hbp_last_hip_error(void);

@@ -37,7 +37,7 @@ ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = (
     "hbp_default_params", "hbp_build", "hbp_spmv", "hbp_free", "hbp_get_info", "hbp_export", "hbp_spmv_timed",
     "hbp_csr_spmv", "hbp_status_string", "hbp_last_hip_error",
-    "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64",
+    "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64", "hbp_release_workspace",
 )
 
 
@@ -102,6 +102,7 @@ def lib() -> ctypes.CDLL:
         L.hbp_status_string.argtypes = [ctypes.c_int]
         L.hbp_status_string.restype = ctypes.c_char_p
         L.hbp_last_hip_error.argtypes = []
+        L.hbp_release_workspace.argtypes = []
         for name in EXPORTED_SYMBOLS:
             if name not in ("hbp_status_string",):
                 getattr(L, name).restype = ctypes.c_int
@@ -247,3 +248,8 @@ def hbp_csr_spmv_f64(kind: int, csr_ptr, csr_col, csr_val, x, y, stream=None) ->
     _check(lib().hbp_csr_spmv_f64(int(kind), _dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"),
                                   _dev_f64(csr_val, "csr_val"), _dev_f64(x, "x"), _dev_f64(y, "y"),
                                   csr_ptr.numel() - 1, _stream_ptr(stream)), "hbp_csr_spmv_f64")
+
+
+def hbp_release_workspace() -> None:
+    """Gives back the scratch memory hbp_build keeps between builds."""
+    _check(lib().hbp_release_workspace(), "hbp_release_workspace")

@@ -365,4 +365,6 @@ const char *hbp_status_string(int status)
 
 int hbp_last_hip_error(void) { return hbp::g_last_hip_error; }
 
+int hbp_release_workspace(void) { return hbp::release_workspace(); }
+
 }  // extern "C"

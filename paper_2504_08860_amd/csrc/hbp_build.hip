@@ -21,6 +21,7 @@
 #include "hbp_internal.h"
 
 #include <chrono>
+#include <mutex>
 #include <vector>
 
 namespace hbp {
@@ -659,8 +660,35 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
     const int64_t j = lane < cnt ? slot_j[s0 + lane] : 0;
     int64_t base = group_ptr[g];
     // eight rounds at a time: the sixteen loads are independent of each other and of the stores
-    constexpr int kRounds = 8;
+    constexpr int kRounds = 8, kLongRounds = 32;
     for (int k = 0; __ballot(k < n); k += kRounds) {
+        // Few rows left, each with at least kLongRounds more nonzeros: the set of live lanes does
+        // not change over these rounds, so round k + u of a live lane lands at base + u * m + its
+        // rank, and a lane copies kLongRounds of its row at a time.  (Eight rounds per memory
+        // round trip made the longest row of the matrix the critical path of the whole kernel.)
+        for (;;) {
+            const uint64_t live = __ballot(k < n);
+            const int m = __popcll(live);
+            if (m == 0 || m > 16 || __ballot(k + kLongRounds <= n) != live) break;
+            if (k < n) {
+                const int64_t dst0 = base + lanes_below(live);
+                int32_t cl[kLongRounds];
+                T vl[kLongRounds];
+#pragma unroll
+                for (int u = 0; u < kLongRounds; u++) {
+                    cl[u] = csr_col[j + k + u];
+                    vl[u] = csr_val[j + k + u];
+                }
+#pragma unroll
+                for (int u = 0; u < kLongRounds; u++) {
+                    col_local[dst0 + (int64_t)u * m] = (uint16_t)(cl[u] - col0);
+                    data[dst0 + (int64_t)u * m] = vl[u];
+                }
+            }
+            base += (int64_t)kLongRounds * m;
+            k += kLongRounds;
+        }
+        if (!__ballot(k < n)) break;
         int32_t c[kRounds];
         T v[kRounds];
 #pragma unroll
@@ -883,13 +911,40 @@ __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__
     fixed_col[w] = c_lo;
 }
 
+// Scratch memory of the build, kept between builds: freeing a few hundred megabytes costs a
+// quarter of a millisecond per allocation, a good part of a build.  Two slots per device (a
+// build has two scratch arenas alive at a time), grown when a build needs more, given back by
+// hbp_release_workspace().  g_workspace_mutex is held for the whole of build_layout: builds on
+// one process are serialised.
+constexpr int kWorkspaceDevices = 64, kWorkspaceSlots = 2;
+struct Workspace { void *base = nullptr; size_t bytes = 0; };
+Workspace g_workspace[kWorkspaceDevices][kWorkspaceSlots];
+std::mutex g_workspace_mutex;
+
+int workspace_get(int device, int slot, size_t bytes, void **out)
+{
+    if (device < 0 || device >= kWorkspaceDevices) return HBP_ERR_INTERNAL;
+    Workspace &w = g_workspace[device][slot];
+    if (w.bytes < bytes) {
+        if (w.base) (void)hipFree(w.base);
+        w.base = nullptr;
+        w.bytes = 0;
+        const size_t want = bytes + bytes / 8;  // some room, so that similar matrices do not reallocate
+        HBP_HIP(hipMalloc(&w.base, want));
+        w.bytes = want;
+    }
+    *out = w.base;
+    return HBP_OK;
+}
+
 // One device allocation carved into 256-byte aligned arrays: reserve() every array first,
 // commit() allocates once and hands out the pointers.  hipMalloc/hipFree calls are a large part
-// of the preprocessing time otherwise (each hipFree synchronises the device).
+// of the preprocessing time otherwise (each hipFree synchronises the device).  An arena is
+// either handed to the caller (the handle's arrays) or lives in a workspace slot.
 class Arena {
 public:
-    explicit Arena(bool owned_by_caller) : keep_(owned_by_caller) {}
-    ~Arena() { if (!keep_ && base_) (void)hipFree(base_); }
+    explicit Arena(bool owned_by_caller, int device = -1, int workspace_slot = -1)
+        : keep_(owned_by_caller), device_(device), slot_(workspace_slot) {}
     template <typename T>
     void reserve(T **out, int64_t count)
     {
@@ -903,7 +958,12 @@ public:
     }
     int commit()
     {
-        HBP_HIP(hipMalloc(&base_, total_ ? total_ : 256));
+        if (keep_) {
+            HBP_HIP(hipMalloc(&base_, total_ ? total_ : 256));
+        } else {
+            const int rc = workspace_get(device_, slot_, total_ ? total_ : 256, &base_);
+            if (rc != HBP_OK) return rc;
+        }
         for (auto &s : slots_) *s.out = (char *)base_ + s.offset;
         return HBP_OK;
     }
@@ -915,6 +975,7 @@ private:
     size_t total_ = 0;
     void *base_ = nullptr;
     bool keep_;
+    int device_, slot_;
 };
 
 inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -926,6 +987,7 @@ inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + pe
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t st)
 {
+    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
     const int64_t n_rows = h->n_rows, n_cols = h->n_cols;
     const int32_t R = h->R, C = h->C, W = h->W;
     const int64_t NBR = h->NBR, NBC = h->NBC, D = NBR * NBC;
@@ -984,7 +1046,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         return HBP_OK;
     }
 
-    Arena tmp(false);
+    Arena tmp(false, h->device, 0);
     const int64_t n_words = (nnz + 63) / 64;
     const int64_t scan_n = std::max<int64_t>(std::max<int64_t>(n_words, D), std::max<int64_t>(NBR, nnz / W + D)) + 1;
     uint32_t *row_bits, *seg_cnt, *word_off, *dense_cnt, *slot_off, *group_off, *blk_id, *scan_tmp, *hist, *stripe_cnt;
@@ -1076,7 +1138,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own1.reserve(&h->multi_stripes, NBR);
     HBP_TRY(own1.commit());
     h->arena[1] = own1.base();
-    Arena tmp2(false);
+    Arena tmp2(false, h->device, 1);
     uint32_t *stripe_cum, *unit_cnt, *multi_idx;
     tmp2.reserve(&stripe_cum, B + 1); tmp2.reserve(&unit_cnt, NBR + 1); tmp2.reserve(&multi_idx, NBR + 1);
     uint32_t *bucket_key, *bucket_seg, *group_nnz, *group_longest, *longest_all;
@@ -1154,6 +1216,19 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
     HBP_HIP(hipGetLastError());
     HBP_HIP(hipStreamSynchronize(st));
     return HBP_OK;
+}
+
+int release_workspace()
+{
+    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
+    int rc = HBP_OK;
+    for (auto &dev : g_workspace)
+        for (auto &w : dev) {
+            if (w.base && hipFree(w.base) != hipSuccess) rc = HBP_ERR_HIP;
+            w.base = nullptr;
+            w.bytes = 0;
+        }
+    return rc;
 }
 
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t st)

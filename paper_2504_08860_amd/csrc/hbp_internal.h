@@ -89,6 +89,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
                  const hbp_params_t &p, hipStream_t stream);
 int build_schedule(hbp_handle_s *h, hipStream_t stream);
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
+int release_workspace();
 
 // spmv (hbp_spmv.hip)
 Layout hbp_view(const hbp_handle_s *h);

@@ -415,3 +415,14 @@ def test_long_group_list_overflows(H, oracle, rounds, threads):
         check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=4096, cols_per_block=4096,
                              rounds_per_batch=rounds, threads_per_worker=threads, num_workers=workers,
                              fixed_fraction_q8=q8, heavy_group_rounds=16)
+
+
+def test_release_workspace(H, oracle):
+    """The build's scratch memory is kept between builds and can be given back; builds before
+    and after that are the same."""
+    m = random_csr(3000, 2000, 0.01, 61)
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=256)
+    H.hbp_release_workspace()
+    H.hbp_release_workspace()           # nothing held: still fine
+    check_against_oracle(H, oracle, make_config(3, 2**-6), rows_per_block=256, cols_per_block=1024)
+    check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=256)   # a smaller one in the kept memory
