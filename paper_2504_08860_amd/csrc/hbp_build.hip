@@ -694,11 +694,8 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
                 const int64_t dst0 = base + lanes_below(live);
                 int32_t cl[kLongRounds];
                 T vl[kLongRounds];
-#pragma unroll
-                for (int u = 0; u < kLongRounds; u++) {
-                    cl[u] = csr_col[j + k + u];
-                    vl[u] = csr_val[j + k + u];
-                }
+                __builtin_memcpy(cl, csr_col + j + k, sizeof cl);  // unaligned 16-byte loads
+                __builtin_memcpy(vl, csr_val + j + k, sizeof vl);
 #pragma unroll
                 for (int u = 0; u < kLongRounds; u++) {
                     col_local[dst0 + (int64_t)u * m] = (uint16_t)(cl[u] - col0);
@@ -711,13 +708,21 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
         if (!__ballot(k < n)) break;
         int32_t c[kRounds];
         T v[kRounds];
+        if (k + kRounds <= n) {
+            // a full batch: 16-byte loads (the row starts at any multiple of 4 bytes; the copies
+            // below are unaligned vector loads).  Lanes read different rows, so a 4-byte load
+            // would cost a whole sector of L2 traffic per element.
+            __builtin_memcpy(c, csr_col + j + k, sizeof c);
+            __builtin_memcpy(v, csr_val + j + k, sizeof v);
+        } else {
 #pragma unroll
-        for (int u = 0; u < kRounds; u++) {
-            c[u] = 0;
-            v[u] = T(0);
-            if (k + u < n) {
-                c[u] = csr_col[j + k + u];
-                v[u] = csr_val[j + k + u];
+            for (int u = 0; u < kRounds; u++) {
+                c[u] = 0;
+                v[u] = T(0);
+                if (k + u < n) {
+                    c[u] = csr_col[j + k + u];
+                    v[u] = csr_val[j + k + u];
+                }
             }
         }
 #pragma unroll
