@@ -625,12 +625,10 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
     __syncthreads();
     for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = threadIdx.x; i < n2; i += 256) {
-                const int p = i ^ j;
-                if (p > i) {
-                    const uint64_t x = keys[i], y = keys[p];
-                    if ((x > y) == ((i & k) == 0)) { keys[i] = y; keys[p] = x; }
-                }
+            for (int t = threadIdx.x; t < n2 / 2; t += 256) {  // pair t: i has bit j clear, its partner has it set
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), p = i | j;
+                const uint64_t x = keys[i], y = keys[p];
+                if ((x > y) == ((i & k) == 0)) { keys[i] = y; keys[p] = x; }
             }
             __syncthreads();
         }
