@@ -635,7 +635,9 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
     for (int i = threadIdx.x; i < m; i += 256) {
         const uint64_t e = keys[i];
         const uint32_t seg = (uint32_t)e;
-        const int32_t j0 = seg_j[seg], n = seg_j[seg + 1] - j0;
+        int32_t ends[2];  // seg_j[seg], seg_j[seg + 1] in one (unaligned) 8-byte load: a gather per slot
+        __builtin_memcpy(ends, seg_j + seg, sizeof ends);
+        const int32_t j0 = ends[0], n = ends[1] - j0;
         row_local[s0 + i] = (uint16_t)((e >> 32) & 0xffffu);
         seg_len[s0 + i] = (uint16_t)n;
         slot_j[s0 + i] = j0;
