@@ -426,3 +426,17 @@ def test_release_workspace(H, oracle):
     H.hbp_release_workspace()           # nothing held: still fine
     check_against_oracle(H, oracle, make_config(3, 2**-6), rows_per_block=256, cols_per_block=1024)
     check_against_oracle(H, oracle, m, rows_per_block=128, cols_per_block=256)   # a smaller one in the kept memory
+
+
+def test_maximum_workers(H, oracle):
+    """The largest worker count the library accepts (65536 ranges, nearly all of them empty), with
+    and without a competitive part, and one more than that refused."""
+    m = random_csr(2000, 3000, 0.01, 71, empty_row_frac=0.2)
+    for q8 in (256, 100):
+        info = check_against_oracle(H, oracle, m, check_add_sign=False, rows_per_block=64, cols_per_block=256,
+                                    num_workers=65536, threads_per_worker=256, fixed_fraction_q8=q8)
+        assert info.num_workers == 65536
+    ptr, col, val, x = to_dev(m)
+    with pytest.raises(H.HbpError) as e:
+        H.hbp_build(ptr, col, val, m.n_rows, m.n_cols, num_workers=65537)
+    assert e.value.status == -1
