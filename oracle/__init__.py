@@ -4,8 +4,10 @@ Only tests, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg 
 import this package.  It imports nothing from the HIP binding, and the HIP binding
 imports nothing from here.
 
-``hbp_oracle.c`` holds the compact-layout builder and the fp64 SpMV definitions;
-``hbp_literal.py`` holds the paper's literal layout for tiny inputs.
+``hbp_oracle.c`` holds what the paper defines (Algorithm 1, the hash, the compact-layout builder,
+Algorithm 3's walk and the combine); ``hbp_oracle_schedule.c`` holds the schedule of Section 3.3
+(the paper's own sentence as one mode, this build's weighted ranges as the other) and the work
+units of the combine part; ``hbp_literal.py`` holds the paper's literal layout for tiny inputs.
 """
 from __future__ import annotations
 
@@ -16,7 +18,8 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "hbp_oracle.c")
+_SRCS = [os.path.join(_HERE, f) for f in ("hbp_oracle.c", "hbp_oracle_schedule.c")]
+_DEPS = _SRCS + [os.path.join(_HERE, "hbp_oracle.h")]
 _LIB = os.path.join(_HERE, "libhbp_oracle.so")
 
 ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
@@ -27,15 +30,16 @@ ARRAYS = {  # name -> (id in oracle_hbp_copy, dtype)
     "data": (12, np.float32), "add_sign": (13, np.int32), "col_group_ptr": (14, np.int32),
     "comp_lo": (15, np.int32), "fixed_start": (16, np.int32), "fixed_col": (17, np.int32),
     "unit_ptr": (18, np.int32), "unit_stripe": (19, np.int32), "unit_k": (20, np.int32), "multi_stripes": (21, np.int32),
-    "group_rounds": (22, np.int32), "comp_col": (23, np.int32),
+    "group_rounds": (22, np.int32), "comp_col": (23, np.int32), "slot_key": (24, np.uint32), "blk_shift": (25, np.int32),
 }
-DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8", "U", "NM")
+DIMS = ("n_rows", "n_cols", "nnz", "R", "C", "W", "a", "NBR", "NBC", "B", "S", "G", "P", "fixed_q8", "U", "NM",
+        "first_ticket_block")
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (plain -O2, single-threaded)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB])
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _DEPS):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-shared", "-fPIC", *_SRCS, "-o", _LIB])
     return _LIB
 
 
@@ -55,8 +59,12 @@ def _load():
         lib.oracle_hash_key.restype = ctypes.c_uint32
         lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
         lib.oracle_sample_shift.restype = i32
-        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i64, i32, i32, i32, i32, i32, i32]
+        lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32]
         lib.oracle_hbp_build.restype = vp
+        lib.oracle_hbp_schedule.argtypes = [vp, i64, i32, i32, i32, i32, i32, i32]
+        lib.oracle_hbp_schedule.restype = i32
+        lib.oracle_hbp_units.argtypes = [vp, i32]
+        lib.oracle_hbp_units.restype = i32
         lib.oracle_hbp_free.argtypes = [vp]
         lib.oracle_hbp_free.restype = None
         lib.oracle_hbp_dims.argtypes = [vp, vp]
@@ -100,15 +108,22 @@ class OracleHbp:
     """The compact HBP layout built by the C oracle; arrays are numpy copies."""
 
     def __init__(self, ptr, col, val, n_rows, n_cols, R=512, C=4096, W=64, hash_shift=-1,
-                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, group_weight=0, column_weight=0):
+                 num_workers=1, fixed_q8=128, slot_weight=1, unit_slots=16384, round_weight=0, group_weight=0, column_weight=0,
+                 paper_schedule=False):
+        """hash_shift: 0..12 given, -1 sampled, -2 no reorder, -3 length as key, -4 one shift per block.
+        paper_schedule: Section 3.3 read literally (equal block counts, one ticket counter)."""
         lib = _load()
         assert val.dtype in (np.float32, np.float64)
         self.value_dtype = val.dtype
         self._h = lib.oracle_hbp_build(_p(ptr), _p(col), _p(val), int(val.dtype.itemsize), int(n_rows), int(n_cols), int(R), int(C), int(W),
-                                       int(hash_shift), int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(group_weight), int(column_weight),
-                                       int(unit_slots))
+                                       int(hash_shift))
         if not self._h:
             raise ValueError("oracle_hbp_build rejected the parameters")
+        if lib.oracle_hbp_schedule(self._h, int(num_workers), int(fixed_q8), int(slot_weight), int(round_weight), int(group_weight),
+                                   int(column_weight), 1 if paper_schedule else 0) != 0 or lib.oracle_hbp_units(self._h, int(unit_slots)) != 0:
+            lib.oracle_hbp_free(self._h)
+            self._h = None
+            raise ValueError("oracle schedule parameters rejected")
         dims = np.zeros(len(DIMS), dtype=np.int64)
         lib.oracle_hbp_dims(self._h, _p(dims))
         for k, v in zip(DIMS, dims):

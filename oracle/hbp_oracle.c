@@ -15,9 +15,10 @@
  *   - oracle_hbp_build         2D partition (Section 3.1), per-(row, column block) segment
  *                              discovery (Algorithm 2), hash reorder, warp-group
  *                              column-major fill with add_sign (Section 3.2, last
- *                              paragraph), block schedule split (Section 3.3), work
- *                              units of the combine part (Fig. 1: which partial sums
- *                              one task of the combine adds up).
+ *                              paragraph).  (The block schedule of Section 3.3 and the work
+ *                              units of the combine part are in hbp_oracle_schedule.c: the
+ *                              paper leaves them open, and nothing in this file depends on
+ *                              them.)
  *   - oracle_hbp_spmv          the two-step SpMV through the layout: per-block walk via
  *                              add_sign (Algorithm 3, with the do-while reading of its
  *                              loop) then the combine of partial sums (Fig. 1), fp64.
@@ -35,16 +36,17 @@
  * insertion.  W consecutive slots of a block form a group; a group's nonzeros are
  * stored round by round (round k = the k-th nonzero of every row that still has one).
  *
- * Parity status: y, segments, permutation, fill, add_sign and schedule are pinned by
- * the tests under tests/ (definitions, brute force, round trip, closed forms, a
- * hand-worked 8x8 example).  The hash formula itself, the sampling quantile, the
- * fixed/competitive split (its ratio and the weights of a group) and the work units of
- * the combine part are NOT given by the paper: "parity unpinned" against the authors'
+ * Parity status: y, segments, permutation, fill and add_sign are pinned by the tests under
+ * tests/ (definitions, brute force, round trip, closed forms, a hand-worked 8x8 example).
+ * The hash formula itself and the sampling quantile are NOT given by the paper (its figure
+ * with the formula is not available): "parity unpinned" against the authors'
  * implementation; they are pinned only to this build's stated reading.
  */
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+#include "hbp_oracle.h"
 
 /* ------------------------------------------------------------------ Algorithm 1 */
 
@@ -148,39 +150,6 @@ int32_t oracle_sample_shift(const int32_t *ptr, const int32_t *col, int64_t n_ro
 
 /* ------------------------------------------------------------------ the layout */
 
-typedef struct {
-    int64_t n_rows, n_cols, nnz;
-    int32_t R, C, W, a;
-    int64_t NBR, NBC;   /* row blocks, column blocks */
-    int64_t B, S, G;    /* non-empty blocks, slots (= segments), groups */
-    int64_t P, fixed_q8; /* workers, share of the work that is pre-assigned in 1/256 (Section 3.3) */
-    int32_t *blk_bm, *blk_bn;     /* B   : block coordinates, column-major order          */
-    int32_t *slot_ptr;            /* B+1 : first slot of each block                        */
-    int32_t *blk_group_ptr;       /* B+1 : first group of each block                       */
-    int32_t *col_blk_ptr;         /* NBC+1 : first block of each block column              */
-    int32_t *stripe_ptr;          /* NBR+1 : per row block, range into stripe_blk          */
-    int32_t *stripe_blk;          /* B   : blocks of a row block, bn ascending             */
-    int32_t *group_ptr;           /* G+1 : position of a group's first nonzero (begin_ptr) */
-    int32_t *group_rounds;        /* G+1 : rounds of all groups before (a group's rounds = its longest row) */
-    int32_t *group_slot;          /* G+1 : a group's first slot                            */
-    uint16_t *row_local;          /* S   : slot -> row inside its block (output_hash)      */
-    uint16_t *seg_len;            /* S   : nonzeros of that row inside the block           */
-    uint16_t *col_local;          /* nnz : column inside the block's column range          */
-    float *data;                  /* nnz (fp32 storage)                                    */
-    double *data64;               /* nnz (fp64 storage); exactly one of data / data64 is set */
-    int32_t value_bytes;          /* 4 or 8                                                */
-    int32_t *add_sign;            /* nnz : distance to the row's next nonzero, -1 at its end */
-    int32_t *col_group_ptr;       /* NBC+1 : first group of each block column                 */
-    int32_t *comp_lo;             /* P   : first competitive group of a worker's range          */
-    int32_t *comp_col;            /* P   : block column that holds the range's competitive groups */
-    int32_t *fixed_start;         /* P+1 : group ranges of the workers                        */
-    int32_t *fixed_col;           /* P   : block column holding a worker's first group        */
-    int64_t U, NM;                /* combine units, row blocks cut into more than one unit    */
-    int32_t *unit_ptr;            /* NBR+1 : units of each row block                          */
-    int32_t *unit_stripe;         /* U   : row block of a unit                                */
-    int32_t *unit_k;              /* U+1 : first stripe_blk entry of a unit                   */
-    int32_t *multi_stripes;       /* NM  : row blocks with more than one unit, ascending      */
-} oracle_hbp;
 
 typedef struct { int64_t *cnt; int64_t NBR; int32_t R; } count_ctx;
 static void count_seg(void *vctx, int64_t row, int64_t bn, int64_t j0, int64_t n)
@@ -205,7 +174,7 @@ void oracle_hbp_free(oracle_hbp *h)
     if (!h) return;
     free(h->blk_bm); free(h->blk_bn); free(h->slot_ptr); free(h->blk_group_ptr); free(h->col_blk_ptr);
     free(h->stripe_ptr); free(h->stripe_blk); free(h->group_ptr); free(h->group_rounds); free(h->group_slot);
-    free(h->row_local); free(h->seg_len); free(h->col_local); free(h->data); free(h->data64); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->comp_col); free(h->fixed_start); free(h->fixed_col);
+    free(h->row_local); free(h->seg_len); free(h->slot_key); free(h->blk_shift); free(h->col_local); free(h->data); free(h->data64); free(h->add_sign); free(h->col_group_ptr); free(h->comp_lo); free(h->comp_col); free(h->fixed_start); free(h->fixed_col);
     free(h->unit_ptr); free(h->unit_stripe); free(h->unit_k); free(h->multi_stripes);
     free(h);
 }
@@ -214,22 +183,26 @@ void oracle_hbp_free(oracle_hbp *h)
  * 2D-partitioning method the paper compares with in Section 4: slots of a block in ascending row order);
  * hash_shift = -3 replaces the hash key by the row's length inside the block itself (the limit of an ever finer
  * linear mapping, Section 5's "room for improvement in the hash function": rows of a block in ascending
- * (length, row) order, which no hash of the length can improve on).
- * num_workers P and fixed_q8 (share of the work pre-assigned, in 1/256) define the schedule arrays.
- * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1). */
+ * (length, row) order, which no hash of the length can improve on);
+ * hash_shift = -4 takes the shift per block instead of per matrix (Section 3.2: "as matrix blocks become denser,
+ * the value of a will increase"): a block's a is the smallest value in 0..12 for which at least 15/16 of the
+ * block's own segments have n < 9 * 2^a -- the rule of the sampled shift applied to all rows of the block.
+ * Returns NULL on invalid parameters (R in 1..65536, C in 1..65535, W >= 1).  The schedule arrays and the
+ * combine units are filled in by oracle_hbp_schedule / oracle_hbp_units (hbp_oracle_schedule.c). */
 oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void *val, int32_t value_bytes, int64_t n_rows, int64_t n_cols,
-                             int32_t R, int32_t C, int32_t W, int32_t hash_shift, int64_t num_workers, int32_t fixed_q8,
-                             int32_t slot_weight, int32_t round_weight, int32_t group_weight, int32_t column_weight, int32_t unit_slots)
+                             int32_t R, int32_t C, int32_t W, int32_t hash_shift)
 {
-    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || num_workers < 1 || slot_weight < 0 || round_weight < 0 || group_weight < 0 || column_weight < 0 || (value_bytes != 4 && value_bytes != 8) || unit_slots < 1) return NULL;
+    if (R < 1 || R > 65536 || C < 1 || C > 65535 || W < 1 || n_rows < 1 || n_cols < 1 || (value_bytes != 4 && value_bytes != 8)) return NULL;
     oracle_hbp *h = (oracle_hbp *)calloc(1, sizeof *h);
     h->n_rows = n_rows; h->n_cols = n_cols; h->nnz = ptr[n_rows];
     h->R = R; h->C = C; h->W = W;
     h->a = hash_shift >= 0 ? hash_shift : oracle_sample_shift(ptr, col, n_rows, C);
     const int plain = hash_shift == -2;  /* plain 2D partition: no reorder, every row gets key 0 */
     const int by_length = hash_shift == -3;  /* key = length of the row inside the block (at most C < 65536) */
+    const int per_block = hash_shift == -4;  /* the shift is taken from the block's own segment lengths */
     const int64_t n_keys = by_length ? 65536 : R;
-#define ORACLE_KEY(n) (plain ? 0u : by_length ? (uint32_t)(n) : oracle_hash_key((uint32_t)(n), h->a, R))
+    int32_t a_blk = h->a;                    /* shift of the block being ordered */
+#define ORACLE_KEY(n) (plain ? 0u : by_length ? (uint32_t)(n) : oracle_hash_key((uint32_t)(n), a_blk, R))
     int64_t NBR = (n_rows + R - 1) / R, NBC = (n_cols + C - 1) / C;
     h->NBR = NBR; h->NBC = NBC;
 
@@ -281,8 +254,19 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
     h->seg_len = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(S + 1));
     int32_t *slot_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)(S + 1));
     int64_t *table = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_keys + 1));
+    h->slot_key = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(S + 1));
+    h->blk_shift = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B + 1));
     for (int64_t b = 0; b < B; b++) {
         int64_t s0 = h->slot_ptr[b], s1 = h->slot_ptr[b + 1];
+        if (per_block) {   /* smallest a with 16 #{n < 9 2^a} >= 15 #{segments of the block} */
+            a_blk = 12;
+            for (int a = 0; a <= 12; a++) {
+                int64_t below = 0;
+                for (int64_t s = s0; s < s1; s++) if (tn[s] < (int64_t)9 << a) below++;
+                if (16 * below >= 15 * (s1 - s0)) { a_blk = a; break; }
+            }
+        }
+        h->blk_shift[b] = a_blk;
         int64_t used = 0;  /* keys 0 .. used-1 occur in this block */
         for (int64_t s = s0; s < s1; s++) if ((int64_t)ORACLE_KEY(tn[s]) >= used) used = (int64_t)ORACLE_KEY(tn[s]) + 1;
         memset(table, 0, sizeof(int64_t) * (size_t)(used + 1));
@@ -292,6 +276,7 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
             int64_t slot = s0 + table[ORACLE_KEY(tn[s])]++;
             h->row_local[slot] = (uint16_t)tq[s];
             h->seg_len[slot] = (uint16_t)tn[s];
+            h->slot_key[slot] = ORACLE_KEY(tn[s]);
             slot_j[slot] = tj[s];
         }
     }
@@ -343,125 +328,24 @@ oracle_hbp *oracle_hbp_build(const int32_t *ptr, const int32_t *col, const void 
         h->stripe_ptr[NBR] = (int32_t)k;
     }
 
-    /* Section 3.3, mixed execution allocation.  The unit handed to a wavefront is a group; the
-     * weight of a group is group_weight plus its nonzeros plus slot_weight times its slots plus round_weight times
-     * its rounds (the length of its longest row: the steps a wavefront takes through it), so
-     * Wt(g) = group_ptr[g] + slot_weight * group_slot[g] + round_weight * group_rounds[g] is the
-     * weight of all groups before g.
-     *   - every range keeps the first fixed_q8/256 of its weight as its fixed part and leaves
-     *     the rest to competition, as far as that rest lies in the range's last block column (so
-     *     that whoever takes it needs one segment of the vector): comp_lo[w] is the range's
-     *     first competitive group, comp_col[w] that block column;
-     *   - the group list is cut into P contiguous ranges of equal weight, fixed_start[w] being
-     *     the first group of worker w; a worker runs the fixed groups inside its range and then
-     *     competes, starting with the column it is on.  For this cut a block column weighs
-     *     column_weight on top of its groups (a worker that enters it has to fetch its segment of
-     *     the vector), charged to the column's first group: the weight before g is
-     *     Wt(g) + column_weight * (number of non-empty block columns that start before g). */
-    h->group_rounds = (int32_t *)malloc(sizeof(int32_t) * (size_t)(G + 1));
-    h->group_rounds[0] = 0;
-    for (int64_t g = 0; g < G; g++) {
-        int32_t longest = 0;
-        for (int64_t q = h->group_slot[g]; q < h->group_slot[g + 1]; q++)
-            if (h->seg_len[q] > longest) longest = h->seg_len[q];
-        h->group_rounds[g + 1] = h->group_rounds[g] + longest;
-    }
-    h->P = num_workers; h->fixed_q8 = fixed_q8;
-    h->col_group_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBC + 1));
-    h->comp_lo = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
-    h->comp_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
-    h->fixed_start = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
-    h->fixed_col = (int32_t *)malloc(sizeof(int32_t) * (size_t)(num_workers + 1));
-    for (int64_t c = 0; c <= NBC; c++) h->col_group_ptr[c] = h->blk_group_ptr[h->col_blk_ptr[c]];
-    #define WT(g) ((int64_t)h->group_ptr[g] + (int64_t)slot_weight * (int64_t)h->group_slot[g] + (int64_t)round_weight * (int64_t)h->group_rounds[g] + (int64_t)group_weight * (int64_t)(g))
-    {
-        /* entered[g]: non-empty block columns whose first group lies before g */
-        int64_t *entered = (int64_t *)calloc((size_t)(G + 2), sizeof(int64_t));
-        for (int64_t c = 0; c < NBC; c++)
-            if (h->col_group_ptr[c + 1] > h->col_group_ptr[c]) entered[h->col_group_ptr[c] + 1]++;
-        for (int64_t g = 0; g <= G; g++) entered[g + 1] += entered[g];
-        #define WTC(g) (WT(g) + (int64_t)column_weight * entered[g])
-        int64_t g = 0, c = 0;
-        for (int64_t w = 0; w <= num_workers; w++) {
-            while (g < G && WTC(g) * num_workers < w * WTC(G)) g++;
-            h->fixed_start[w] = (int32_t)g;
-            if (w == num_workers) break;
-            while (c + 1 < NBC && h->col_group_ptr[c + 1] <= g) c++;   /* last column starting at or before g */
-            h->fixed_col[w] = (int32_t)c;
-        }
-        #undef WTC
-        free(entered);
-    }
-    for (int64_t w = 0; w < num_workers; w++) {
-        int64_t g0 = h->fixed_start[w], g1 = h->fixed_start[w + 1], g = g0, c = h->fixed_col[w];
-        while (g < g1 && (WT(g) - WT(g0)) * 256 < (WT(g1) - WT(g0)) * (int64_t)fixed_q8) g++;
-        if (g1 > g0) {
-            c = 0;
-            while (c + 1 < NBC && h->col_group_ptr[c + 1] <= g1 - 1) c++;   /* column of the range's last group */
-            if (g < h->col_group_ptr[c]) g = h->col_group_ptr[c];
-        }
-        h->comp_lo[w] = (int32_t)g;
-        h->comp_col[w] = (int32_t)c;
-    }
-    #undef WT
-
-    /* Work units of the combine part.  A row block with many slots is cut into
-     * u = ceil(slots / unit_slots) units of consecutive stripe_blk entries; unit i starts at the
-     * first entry whose preceding slots, times u, reach i times the row block's slots. */
-    {
-        int64_t *cum = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B + 1));
-        cum[0] = 0;
-        for (int64_t k = 0; k < B; k++) {
-            int64_t b = h->stripe_blk[k];
-            cum[k + 1] = cum[k] + (h->slot_ptr[b + 1] - h->slot_ptr[b]);
-        }
-        h->unit_ptr = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NBR + 1));
-        int64_t U = 0, NM = 0;
-        for (int64_t bm = 0; bm < NBR; bm++) {
-            int64_t slots = cum[h->stripe_ptr[bm + 1]] - cum[h->stripe_ptr[bm]];
-            int64_t u = (slots + unit_slots - 1) / unit_slots;
-            if (u < 1) u = 1;
-            h->unit_ptr[bm] = (int32_t)U;
-            U += u;
-            if (u > 1) NM++;
-        }
-        h->unit_ptr[NBR] = (int32_t)U;
-        h->U = U; h->NM = NM;
-        h->unit_stripe = (int32_t *)malloc(sizeof(int32_t) * (size_t)(U + 1));
-        h->unit_k = (int32_t *)malloc(sizeof(int32_t) * (size_t)(U + 1));
-        h->multi_stripes = (int32_t *)malloc(sizeof(int32_t) * (size_t)(NM + 1));
-        int64_t nm = 0;
-        for (int64_t bm = 0; bm < NBR; bm++) {
-            int64_t k0 = h->stripe_ptr[bm], k1 = h->stripe_ptr[bm + 1];
-            int64_t slots = cum[k1] - cum[k0], u = h->unit_ptr[bm + 1] - h->unit_ptr[bm];
-            int64_t k = k0;
-            for (int64_t i = 0; i < u; i++) {
-                while (k < k1 && (cum[k] - cum[k0]) * u < i * slots) k++;
-                h->unit_stripe[h->unit_ptr[bm] + i] = (int32_t)bm;
-                h->unit_k[h->unit_ptr[bm] + i] = (int32_t)k;
-            }
-            if (u > 1) h->multi_stripes[nm++] = (int32_t)bm;
-        }
-        h->unit_k[U] = (int32_t)B;
-        free(cum);
-    }
-
+    h->first_ticket_block = -1;
     free(cnt); free(cursor); free(compact_id); free(tq); free(tn); free(tj); free(slot_j); free(table);
     return h;
 }
 
-/* dims[0..15] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 U NM */
+/* dims[0..16] = n_rows n_cols nnz R C W a NBR NBC B S G P fixed_q8 U NM first_ticket_block */
 void oracle_hbp_dims(const oracle_hbp *h, int64_t *dims)
 {
-    int64_t v[16] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8,
-                      h->U, h->NM };
+    int64_t v[17] = { h->n_rows, h->n_cols, h->nnz, h->R, h->C, h->W, h->a, h->NBR, h->NBC, h->B, h->S, h->G, h->P, h->fixed_q8,
+                      h->U, h->NM, h->first_ticket_block };
     memcpy(dims, v, sizeof v);
 }
 
 /* which: 0 blk_bm 1 blk_bn 2 slot_ptr 3 blk_group_ptr 4 col_blk_ptr 5 stripe_ptr 6 stripe_blk
  *        7 group_ptr 8 group_slot 9 row_local 10 seg_len 11 col_local 12 data 13 add_sign
  *        14 col_group_ptr 15 comp_lo 16 fixed_start 17 fixed_col
- *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 group_rounds 23 comp_col.
+ *        18 unit_ptr 19 unit_stripe 20 unit_k 21 multi_stripes 22 group_rounds 23 comp_col
+ *        24 slot_key 25 blk_shift.
  * Copies the array into dst and returns its size in bytes (0 for an unknown id). */
 int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
 {
@@ -491,6 +375,8 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
     case 21: src = h->multi_stripes; bytes = 4 * h->NM; break;
     case 22: src = h->group_rounds; bytes = 4 * (h->G + 1); break;
     case 23: src = h->comp_col; bytes = 4 * h->P; break;
+    case 24: src = h->slot_key; bytes = 4 * h->S; break;
+    case 25: src = h->blk_shift; bytes = 4 * h->B; break;
     default: return 0;
     }
     if (dst && bytes) memcpy(dst, src, (size_t)bytes);

@@ -156,47 +156,35 @@ static int spmv_timed_any(int32_t value_bytes, hbp_handle_t h, const void *x, vo
     DeviceGuard guard(h->device);
     if (!guard.ok) return HBP_ERR_HIP;
     hipStream_t st = (hipStream_t)stream;
-    hipEvent_t ev[3];
-    for (auto &e : ev) HBP_HIP(hipEventCreate(&e));
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     double part = 0, comb = 0, total = 0;
+    // every HIP call goes through `check`, so that the events are destroyed on every way out
+    hipError_t err = hipSuccess;
+    auto check = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; return err == hipSuccess; };
     int rc = HBP_OK;
-    for (int i = 0; i < iters && rc == HBP_OK; i++) {
-        HBP_HIP(hipEventRecord(ev[0], st));
+    for (auto &e : ev)
+        if (!check(hipEventCreate(&e))) break;
+    for (int i = 0; i < iters && rc == HBP_OK && err == hipSuccess; i++) {
+        if (!check(hipEventRecord(ev[0], st))) break;
         rc = hbp::launch_spmv_part(h, x, y, st);
-        HBP_HIP(hipEventRecord(ev[1], st));
+        if (!check(hipEventRecord(ev[1], st))) break;
         if (rc == HBP_OK) rc = hbp::launch_combine(h, y, st);
-        HBP_HIP(hipEventRecord(ev[2], st));
-        HBP_HIP(hipEventSynchronize(ev[2]));
+        if (!check(hipEventRecord(ev[2], st))) break;
+        if (!check(hipEventSynchronize(ev[2])) || rc != HBP_OK) break;
         float a = 0, b = 0, c = 0;
-        HBP_HIP(hipEventElapsedTime(&a, ev[0], ev[1]));
-        HBP_HIP(hipEventElapsedTime(&b, ev[1], ev[2]));
-        HBP_HIP(hipEventElapsedTime(&c, ev[0], ev[2]));
+        if (!check(hipEventElapsedTime(&a, ev[0], ev[1])) || !check(hipEventElapsedTime(&b, ev[1], ev[2])) ||
+            !check(hipEventElapsedTime(&c, ev[0], ev[2])))
+            break;
         part += a; comb += b; total += c;
     }
-    for (auto &e : ev) (void)hipEventDestroy(e);
+    if (err != hipSuccess || rc != HBP_OK) (void)hipStreamSynchronize(st);  // nothing of this call is left in flight
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
     if (rc != HBP_OK) return rc;
+    HBP_HIP(err);
     if (ms_part) *ms_part = (float)(part / iters);
     if (ms_combine) *ms_combine = (float)(comb / iters);
     if (ms_total) *ms_total = (float)(total / iters);
-    return HBP_OK;
-}
-
-// Investigation hook (not part of the public header): per-wavefront timestamps of one SpMV-part
-// launch, 4 x uint64 per wavefront: start, end of fixed part, end, time spent staging (10 ns ticks).
-int hbp_debug_timeline(hbp_handle_t h, const void *x, void *y, void *stream, uint64_t *host_out, size_t capacity)
-{
-    if (!h || !x || !y || !host_out) return HBP_ERR_INVALID_ARGUMENT;
-    const size_t n = (size_t)h->P * (h->threads / 64) * 4;
-    if (capacity < n * sizeof(uint64_t)) return HBP_ERR_INVALID_ARGUMENT;
-    uint64_t *d = nullptr;
-    HBP_HIP(hipMalloc((void **)&d, n * sizeof(uint64_t)));
-    int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream, d);
-    if (rc == HBP_OK) rc = hbp::launch_combine(h, y, (hipStream_t)stream);
-    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
-    if (e == hipSuccess) e = hipMemcpy(host_out, d, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
-    (void)hipFree(d);
-    if (rc != HBP_OK) return rc;
-    HBP_HIP(e);
     return HBP_OK;
 }
 

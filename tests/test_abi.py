@@ -6,18 +6,36 @@ import re
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def _declared_in_header():
+    header = open(os.path.join(ROOT, "include", "hbp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    return set(re.findall(r"\b(hbp_[a-z_0-9]+)\s*\(", header))
+
+
+def _exported_by_library(path):
+    """The hbp_* functions in the library's dynamic symbol table (what a C caller can link against)."""
+    import subprocess
+    out = subprocess.check_output(["nm", "-D", "--defined-only", path]).decode()
+    names = set()
+    for line in out.splitlines():
+        parts = line.split()
+        if len(parts) >= 3 and parts[1] in ("T", "W") and parts[2].startswith("hbp_"):
+            names.add(parts[2].split("@")[0])
+    return names
+
+
 def test_header_symbols_are_exported():
     import paper_2504_08860_amd as H
     if not os.path.exists(H.LIB_PATH):
         from paper_2504_08860_amd.build import build_library
         build_library()
     lib = ctypes.CDLL(H.LIB_PATH)
-    header = open(os.path.join(ROOT, "include", "hbp.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(hbp_[a-z_0-9]+)\s*\(", header))
+    declared = _declared_in_header()
     assert declared == set(H.EXPORTED_SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
+    # and nothing else: every extern "C" hbp_* entry point of the built library is declared in the header
+    assert _exported_by_library(H.LIB_PATH) == declared
 
 
 def test_host_only_calls():
