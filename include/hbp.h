@@ -102,6 +102,17 @@ typedef enum {
                                   it, i.e. the limit of an ever finer mapping: slots in ascending (length,
                                   row) order.  Ignored with HBP_FLAG_NO_REORDER. */
 
+#define HBP_FLAG_PAPER_SCHEDULE 8u /* Section 3.3 read literally instead of this library's schedule: the units are
+                                  blocks in the layout's column-major order, every worker is pre-assigned
+                                  F = floor(B * fixed_fraction / P) of them (blocks [w F, (w + 1) F) go to worker w)
+                                  and the blocks from P F on are claimed one at a time through a single ticket
+                                  counter.  The weights and claim_chunk are ignored. */
+#define HBP_FLAG_BLOCK_SHIFT 16u /* hash study: one shift a per block (Section 3.2: denser blocks call for a larger
+                                  a) instead of one per matrix: the smallest a in 0..12 for which at least 15/16
+                                  of the block's own rows have fewer than 9 * 2^a nonzeros in it.  hash_shift is
+                                  ignored; ignored itself with HBP_FLAG_NO_REORDER or HBP_FLAG_KEY_LENGTH. */
+#define HBP_FLAG_KEEP_KEYS 32u /* keep the key every slot was placed by (4 bytes per slot) for hbp_export */
+
 /* Build parameters.  Block sizes follow Section 3.1 (the paper derives 4096 columns from
  * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is
  * staged in the 160 KB LDS of a gfx950 compute unit as fp32. */
@@ -158,6 +169,7 @@ typedef struct {
     int64_t combine_units;       /* U: workgroups of the combine part                           */
     int64_t split_row_blocks;    /* NM: row blocks cut into more than one unit                  */
     int32_t value_bytes;         /* 4: fp32 handle, 8: fp64 handle                              */
+    int64_t first_ticket_block;  /* HBP_FLAG_PAPER_SCHEDULE: first block of the competitive part (P F); else -1 */
     int64_t bytes_layout;        /* device bytes of all layout arrays                           */
     int64_t bytes_spmv_part;     /* algorithmic bytes one SpMV-part launch moves                 */
     int64_t bytes_combine;       /* algorithmic bytes one combine launch moves                  */
@@ -174,7 +186,9 @@ typedef enum {
     HBP_ARRAY_PARTIAL = 14,  /* float or double [S], per-slot partial sums of the last SpMV      */
     HBP_ARRAY_COL_GROUP_PTR = 15, HBP_ARRAY_COMP_LO = 16, HBP_ARRAY_FIXED_START = 17, HBP_ARRAY_FIXED_COL = 18,
     HBP_ARRAY_UNIT_PTR = 19, HBP_ARRAY_UNIT_STRIPE = 20, HBP_ARRAY_UNIT_K = 21, HBP_ARRAY_MULTI_STRIPES = 22,
-    HBP_ARRAY_GROUP_ROUNDS = 23, HBP_ARRAY_COMP_COL = 24
+    HBP_ARRAY_GROUP_ROUNDS = 23, HBP_ARRAY_COMP_COL = 24,
+    HBP_ARRAY_SLOT_KEY = 25, /* uint32 [S], the key each slot was placed by; only with HBP_FLAG_KEEP_KEYS  */
+    HBP_ARRAY_BLK_SHIFT = 26 /* int32 [B], the shift a each block's keys were taken with                  */
 } hbp_array_id;
 
 /* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */
@@ -241,6 +255,12 @@ int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const
                  const float *x, float *y, int64_t n_rows, void *stream);
 int hbp_csr_spmv_f64(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val,
                      const double *x, double *y, int64_t n_rows, void *stream);
+
+/* The device's hash function on its own (Section 3.2: aggregation, dispersion, linear mapping):
+ * keys[i] = key of a row with n[i] nonzeros inside its block, for shift a (0..12) and R rows per
+ * block (1..8192), exactly as hbp_build computes it when it places that row.
+ *   n DEVICE uint32 [count], keys DEVICE uint32 [count]; asynchronous on `stream`. */
+int hbp_hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t rows_per_block, uint32_t *keys, void *stream);
 
 /* hbp_build keeps its scratch memory (a few hundred megabytes for the large workloads, per
  * device) for the next build instead of freeing it: freeing costs a good part of a build.

@@ -57,6 +57,8 @@ def _load():
         lib.oracle_csr_spmv_f64_d.restype = None
         lib.oracle_hash_key.argtypes = [ctypes.c_uint32, i32, i32]
         lib.oracle_hash_key.restype = ctypes.c_uint32
+        lib.oracle_hash_keys.argtypes = [vp, i64, i32, i32, vp]
+        lib.oracle_hash_keys.restype = None
         lib.oracle_sample_shift.argtypes = [vp, vp, i64, i32]
         lib.oracle_sample_shift.restype = i32
         lib.oracle_hbp_build.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i32]
@@ -98,6 +100,14 @@ def csr_spmv_f64(ptr, col, val, x):
 
 def hash_key(n: int, a: int, R: int) -> int:
     return int(_load().oracle_hash_key(int(n), int(a), int(R)))
+
+
+def hash_keys(n: np.ndarray, a: int, R: int) -> np.ndarray:
+    """hash_key of every length in ``n`` (uint32)."""
+    n = np.ascontiguousarray(n, dtype=np.uint32)
+    out = np.empty_like(n)
+    _load().oracle_hash_keys(_p(n), len(n), int(a), int(R), _p(out))
+    return out
 
 
 def sample_shift(ptr, col, n_rows: int, C: int) -> int:

@@ -109,6 +109,12 @@ uint32_t oracle_hash_key(uint32_t n, int32_t a, int32_t R)
     return key;
 }
 
+/* keys[i] = oracle_hash_key(n[i], a, R): the same function over a vector of lengths. */
+void oracle_hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t R, uint32_t *keys)
+{
+    for (int64_t i = 0; i < count; i++) keys[i] = oracle_hash_key(n[i], a, R);
+}
+
 /* Walk one row and call back once per segment (maximal run of nonzeros whose columns
  * fall in the same column block), left to right as Algorithm 2 does, with the row-end
  * guard its inner loop lacks. */

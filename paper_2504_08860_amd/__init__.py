@@ -16,13 +16,16 @@ HBP_OK = 0
 HBP_FLAG_VALIDATE = 1
 HBP_FLAG_NO_REORDER = 2
 HBP_FLAG_KEY_LENGTH = 4
+HBP_FLAG_PAPER_SCHEDULE = 8
+HBP_FLAG_BLOCK_SHIFT = 16
+HBP_FLAG_KEEP_KEYS = 32
 
 ARRAY_IDS = {
     "blk_bm": 0, "blk_bn": 1, "slot_ptr": 2, "blk_group_ptr": 3, "col_blk_ptr": 4, "stripe_ptr": 5,
     "stripe_blk": 6, "group_ptr": 7, "group_slot": 8, "row_local": 9, "seg_len": 10, "col_local": 11,
     "data": 12, "add_sign": 13, "partial": 14, "col_group_ptr": 15, "comp_lo": 16,
     "fixed_start": 17, "fixed_col": 18, "unit_ptr": 19, "unit_stripe": 20, "unit_k": 21, "multi_stripes": 22,
-    "group_rounds": 23, "comp_col": 24,
+    "group_rounds": 23, "comp_col": 24, "slot_key": 25, "blk_shift": 26,
 }
 ARRAY_DTYPES = {
     "blk_bm": "int32", "blk_bn": "int32", "slot_ptr": "int32", "blk_group_ptr": "int32", "col_blk_ptr": "int32",
@@ -31,13 +34,13 @@ ARRAY_DTYPES = {
     "partial": "float32", "col_group_ptr": "int32", "comp_lo": "int32",
     "fixed_start": "int32", "fixed_col": "int32",
     "unit_ptr": "int32", "unit_stripe": "int32", "unit_k": "int32", "multi_stripes": "int32",
-    "group_rounds": "int32", "comp_col": "int32",
+    "group_rounds": "int32", "comp_col": "int32", "slot_key": "uint32", "blk_shift": "int32",
 }
 # every symbol include/hbp.h declares
 EXPORTED_SYMBOLS = (
     "hbp_default_params", "hbp_build", "hbp_spmv", "hbp_free", "hbp_get_info", "hbp_export", "hbp_spmv_timed",
     "hbp_csr_spmv", "hbp_status_string", "hbp_last_hip_error",
-    "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64", "hbp_release_workspace",
+    "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64", "hbp_release_workspace", "hbp_hash_keys",
 )
 
 
@@ -61,7 +64,7 @@ class hbp_info_t(ctypes.Structure):
                 ("slot_weight", ctypes.c_int32), ("group_weight", ctypes.c_int32), ("combine_unit_slots", ctypes.c_int32),
                 ("heavy_group_rounds", ctypes.c_int32), ("round_weight", ctypes.c_int32), ("column_weight", ctypes.c_int32),
                 ("combine_units", ctypes.c_int64), ("split_row_blocks", ctypes.c_int64), ("value_bytes", ctypes.c_int32),
-                ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
+                ("first_ticket_block", ctypes.c_int64), ("bytes_layout", ctypes.c_int64), ("bytes_spmv_part", ctypes.c_int64), ("bytes_combine", ctypes.c_int64),
                 ("build_ms", ctypes.c_double)]
 
 
@@ -103,6 +106,7 @@ def lib() -> ctypes.CDLL:
         L.hbp_status_string.restype = ctypes.c_char_p
         L.hbp_last_hip_error.argtypes = []
         L.hbp_release_workspace.argtypes = []
+        L.hbp_hash_keys.argtypes = [vp, i64, i32, i32, vp, vp]
         for name in EXPORTED_SYMBOLS:
             if name not in ("hbp_status_string",):
                 getattr(L, name).restype = ctypes.c_int
@@ -159,6 +163,12 @@ def _build(f64: bool, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream,
             p.flags = (p.flags | HBP_FLAG_NO_REORDER) if v else (p.flags & ~HBP_FLAG_NO_REORDER)
         elif k == "key_length":
             p.flags = (p.flags | HBP_FLAG_KEY_LENGTH) if v else (p.flags & ~HBP_FLAG_KEY_LENGTH)
+        elif k == "paper_schedule":
+            p.flags = (p.flags | HBP_FLAG_PAPER_SCHEDULE) if v else (p.flags & ~HBP_FLAG_PAPER_SCHEDULE)
+        elif k == "block_shift":
+            p.flags = (p.flags | HBP_FLAG_BLOCK_SHIFT) if v else (p.flags & ~HBP_FLAG_BLOCK_SHIFT)
+        elif k == "keep_keys":
+            p.flags = (p.flags | HBP_FLAG_KEEP_KEYS) if v else (p.flags & ~HBP_FLAG_KEEP_KEYS)
         else:
             if not hasattr(p, k):
                 raise TypeError(f"hbp_params_t has no field {k}")
@@ -175,7 +185,8 @@ def _build(f64: bool, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream,
 def hbp_build(csr_ptr, csr_col, csr_val, n_rows: int, n_cols: int, params: hbp_params_t | None = None, stream=None,
               **overrides) -> int:
     """CSR (device tensors, float32 values) -> handle.  ``overrides`` set fields of hbp_params_t by name
-    (``validate=``, ``no_reorder=`` and ``key_length=True/False`` set the flags)."""
+    (``validate=``, ``no_reorder=``, ``key_length=``, ``paper_schedule=``, ``block_shift=`` and ``keep_keys=True/False``
+    set the flags)."""
     return _build(False, csr_ptr, csr_col, csr_val, n_rows, n_cols, params, stream, overrides)
 
 
@@ -248,6 +259,16 @@ def hbp_csr_spmv_f64(kind: int, csr_ptr, csr_col, csr_val, x, y, stream=None) ->
     _check(lib().hbp_csr_spmv_f64(int(kind), _dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"),
                                   _dev_f64(csr_val, "csr_val"), _dev_f64(x, "x"), _dev_f64(y, "y"),
                                   csr_ptr.numel() - 1, _stream_ptr(stream)), "hbp_csr_spmv_f64")
+
+
+def hbp_hash_keys(n, a: int, rows_per_block: int, stream=None):
+    """The device's hash key (Section 3.2) of every length in ``n`` (uint32/int32 CUDA tensor) -> int32 CUDA tensor."""
+    import torch
+    assert n.is_cuda and n.dtype == torch.int32 and n.is_contiguous()
+    out = torch.empty_like(n)
+    _check(lib().hbp_hash_keys(n.data_ptr(), n.numel(), int(a), int(rows_per_block), out.data_ptr(), _stream_ptr(stream)),
+           "hbp_hash_keys")
+    return out
 
 
 def hbp_release_workspace() -> None:

@@ -93,6 +93,8 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
     if (hipGetDevice(&h->device) != hipSuccess) { delete h; return HBP_ERR_HIP; }
     h->n_rows = n_rows; h->n_cols = n_cols;
     h->value_bytes = value_bytes;
+    h->flags = p.flags;
+    h->first_ticket_block = -1;
     h->R = p.rows_per_block; h->C = p.cols_per_block; h->W = p.group_width;
     h->NBR = (n_rows + h->R - 1) / h->R;
     h->NBC = (n_cols + h->C - 1) / h->C;
@@ -220,6 +222,7 @@ int hbp_get_info(hbp_handle_t h, hbp_info_t *info)
     info->combine_units = h->U;
     info->split_row_blocks = h->NM;
     info->value_bytes = h->value_bytes;
+    info->first_ticket_block = h->first_ticket_block;
     const int64_t blk = 4 * (4 * (h->B + 1) + h->B + (h->NBC + 1) + (h->NBR + 1));
     const int64_t grp = 4 * 2 * (h->G + 1);
     const int64_t vb = h->value_bytes;
@@ -266,6 +269,10 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
     case HBP_ARRAY_UNIT_K: src = h->unit_k; bytes = 4 * (size_t)(h->U + 1); break;
     case HBP_ARRAY_MULTI_STRIPES: src = h->multi_stripes; bytes = 4 * (size_t)h->NM; break;
     case HBP_ARRAY_GROUP_ROUNDS: src = h->group_rounds; bytes = 4 * (size_t)(h->G + 1); break;
+    case HBP_ARRAY_SLOT_KEY:
+        if (!h->slot_key) return HBP_ERR_INVALID_ARGUMENT;  // built without HBP_FLAG_KEEP_KEYS
+        src = h->slot_key; bytes = 4 * (size_t)h->S; break;
+    case HBP_ARRAY_BLK_SHIFT: src = h->blk_shift; bytes = 4 * (size_t)h->B; break;
     default: return HBP_ERR_INVALID_ARGUMENT;
     }
     if (bytes_out) *bytes_out = bytes;
@@ -354,5 +361,12 @@ const char *hbp_status_string(int status)
 int hbp_last_hip_error(void) { return hbp::g_last_hip_error; }
 
 int hbp_release_workspace(void) { return hbp::release_workspace(); }
+
+int hbp_hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t rows_per_block, uint32_t *keys, void *stream)
+{
+    if (count < 0 || (count > 0 && (!n || !keys)) || a < 0 || a > 12 || rows_per_block < 1 || rows_per_block > hbp::kMaxR)
+        return HBP_ERR_INVALID_ARGUMENT;
+    return hbp::hash_keys(n, count, a, rows_per_block, keys, (hipStream_t)stream);
+}
 
 }  // extern "C"

@@ -562,8 +562,9 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_
     const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u, a = (uint32_t)*a_ptr;
     auto emit = [&](int64_t s, int32_t row, uint32_t pos) {
         const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-        // reorder 0: no key (plain 2D partition), 1: the hash, 2: the length itself (n <= C < 65536)
-        const uint32_t key = reorder == 1 ? hash_key(n, a, b, R_u) : reorder == 2 ? n : 0u;
+        // reorder 0: no key (plain 2D partition), 1: the hash, 2: the length itself (n <= C < 65536),
+        // 3: the length for now (k_order_block hashes it with the block's own shift)
+        const uint32_t key = reorder == 1 ? hash_key(n, a, b, R_u) : reorder >= 2 ? n : 0u;
         bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
         bucket_seg[pos] = (uint32_t)s;
     };
@@ -613,15 +614,49 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
                                                      uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
                                                      int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz, uint32_t *__restrict__ group_longest,
                                                      int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk, uint32_t heavy_rounds,
-                                                     uint32_t *__restrict__ longest_all)
+                                                     uint32_t *__restrict__ longest_all, int32_t block_shift, uint32_t R,
+                                                     const int32_t *__restrict__ a_ptr, int32_t *__restrict__ blk_shift,
+                                                     uint32_t *__restrict__ slot_key)
 {
     extern __shared__ uint64_t keys[];
+    __shared__ uint32_t sh_hist[14];
+    __shared__ int32_t sh_shift;
     const int b = blockIdx.x;
     const int s0 = slot_ptr[b], m = slot_ptr[b + 1] - s0;
     int n2 = 1;
     while (n2 < m) n2 <<= 1;
     for (int i = threadIdx.x; i < n2; i += 256)
         keys[i] = i < m ? ((uint64_t)bucket_key[s0 + i] << 32) | bucket_seg[s0 + i] : ~0ull;
+    if (block_shift) {
+        // One shift per block (Section 3.2: denser blocks call for a larger a): the entries carry the
+        // rows' lengths; a = smallest shift for which at least 15/16 of the block's rows aggregate
+        // into 0..8; then the lengths are replaced by their keys.
+        if (threadIdx.x < 14) sh_hist[threadIdx.x] = 0u;
+        __syncthreads();
+        for (int i = threadIdx.x; i < m; i += 256) {
+            const uint32_t n = (uint32_t)(keys[i] >> 48);
+            int a = 0;
+            while (a < 13 && n >= (9u << a)) a++;
+            atomicAdd(&sh_hist[a], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t below = 0;
+            int a = 12;
+            for (int i = 0; i <= 12; i++) {
+                below += sh_hist[i];
+                if (16ull * below >= 15ull * (uint32_t)m) { a = i; break; }
+            }
+            sh_shift = a;
+        }
+        __syncthreads();
+        const uint32_t a = (uint32_t)sh_shift, band = R / 9u ? R / 9u : 1u;
+        for (int i = threadIdx.x; i < m; i += 256) {
+            const uint64_t e = keys[i];
+            keys[i] = ((uint64_t)hash_key((uint32_t)(e >> 48), a, band, R) << 48) | (e & 0xffffffffffffull);
+        }
+    }
+    if (threadIdx.x == 0) blk_shift[b] = block_shift ? sh_shift : *a_ptr;
     __syncthreads();
     for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
@@ -640,6 +675,7 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
         const int32_t j0 = ends[0], n = ends[1] - j0;
         row_local[s0 + i] = (uint16_t)((e >> 32) & 0xffffu);
         seg_len[s0 + i] = (uint16_t)n;
+        if (slot_key) slot_key[s0 + i] = (uint32_t)(e >> 48);
         slot_j[s0 + i] = j0;
         keys[i] = (uint64_t)n;  // only this thread touches entry i in this phase
     }
@@ -936,6 +972,33 @@ __global__ __launch_bounds__(256) void k_fixed_start(const int32_t *__restrict__
     fixed_col[w] = c_lo;
 }
 
+// The paper's schedule (Section 3.3 read literally): worker w is pre-assigned the F blocks
+// [w F, (w + 1) F) of the column-major block list; handed over as group ranges (the unit the
+// kernels walk).  Nothing inside a range is competitive: the blocks from P F on are claimed one at
+// a time through a single ticket counter.
+__global__ __launch_bounds__(256) void k_paper_schedule(const int32_t *__restrict__ blk_group_ptr, const int32_t *__restrict__ blk_bn,
+                                                        int64_t F, int32_t B, int32_t NBC, int32_t P, int32_t *__restrict__ fixed_start,
+                                                        int32_t *__restrict__ fixed_col, int32_t *__restrict__ comp_lo,
+                                                        int32_t *__restrict__ comp_col)
+{
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (w > P) return;
+    const int64_t b = w * F;  // <= P F <= B
+    fixed_start[w] = blk_group_ptr[b];
+    if (w == P) return;
+    const int32_t first_col = b < B ? blk_bn[b] : NBC - 1;
+    fixed_col[w] = first_col;
+    comp_lo[w] = blk_group_ptr[b + F];
+    comp_col[w] = F > 0 ? blk_bn[b + F - 1] : first_col;
+}
+
+__global__ __launch_bounds__(256) void k_hash_keys(const uint32_t *__restrict__ n, int64_t count, uint32_t a, uint32_t R,
+                                                   uint32_t *__restrict__ keys)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) keys[i] = hash_key(n[i], a, R / 9u ? R / 9u : 1u, R);
+}
+
 // Scratch memory of the build, kept between builds: freeing a few hundred megabytes costs a
 // quarter of a millisecond per allocation, a good part of a build.  Two slots per device (a
 // build has two scratch arenas alive at a time), grown when a build needs more, given back by
@@ -1060,7 +1123,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
         Arena own1(true);
         own1.reserve(&h->blk_bm, 1); own1.reserve(&h->blk_bn, 1); own1.reserve(&h->slot_ptr, 1);
         own1.reserve(&h->blk_group_ptr, 1); own1.reserve(&h->stripe_blk, 1); own1.reserve(&h->group_ptr, 1);
-        own1.reserve(&h->group_slot, 1); own1.reserve(&h->group_rounds, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1);
+        own1.reserve(&h->group_slot, 1); own1.reserve(&h->group_rounds, 1); own1.reserve(&h->row_local, 1); own1.reserve(&h->seg_len, 1); own1.reserve(&h->blk_shift, 1);
         own1.reserve(&h->col_local, 1); own1.reserve_bytes(&h->data, 8); own1.reserve_bytes(&h->partial, 8);
         own1.reserve(&h->unit_stripe, NBR + 1); own1.reserve(&h->unit_k, NBR + 2); own1.reserve(&h->multi_stripes, 1);
         HBP_TRY(own1.commit());
@@ -1154,6 +1217,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     own1.reserve(&h->stripe_blk, B + 1);
     own1.reserve(&h->group_ptr, G + 1); own1.reserve(&h->group_slot, G + 1); own1.reserve(&h->group_rounds, G + 1);
     own1.reserve(&h->row_local, S + 1); own1.reserve(&h->seg_len, S + 1);
+    own1.reserve(&h->blk_shift, B + 1);
+    if (p.flags & HBP_FLAG_KEEP_KEYS) own1.reserve(&h->slot_key, S + 1);
     // 256 elements of padding: the SpMV part reads whole aligned 256-element chunks
     own1.reserve(&h->col_local, nnz + 256); own1.reserve_bytes(&h->data, (nnz + 256) * h->value_bytes);
     own1.reserve_bytes(&h->partial, (S + 1) * h->value_bytes);
@@ -1192,8 +1257,9 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     k_unit_fill<<<blocks_for(NBR, 256), 256, 0, st>>>(h->stripe_ptr, stripe_cum, h->unit_ptr, multi_idx, (int32_t)NBR, (int32_t)B,
                                                      h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
+    const int32_t reorder = (p.flags & HBP_FLAG_NO_REORDER) ? 0 : (p.flags & HBP_FLAG_KEY_LENGTH) ? 2 : (p.flags & HBP_FLAG_BLOCK_SHIFT) ? 3 : 1;
     k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a,
-                                                       (p.flags & HBP_FLAG_NO_REORDER) ? 0 : (p.flags & HBP_FLAG_KEY_LENGTH) ? 2 : 1, slot_off,
+                                                       reorder, slot_off,
                                                        bucket_key, bucket_seg);
     int n2 = 2;
     while (n2 < R) n2 <<= 1;
@@ -1201,7 +1267,8 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
     HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
     k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
                                                             h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
-                                                            group_blk, (uint32_t)long_rounds_of(h->heavy_rounds), longest_all);
+                                                            group_blk, (uint32_t)long_rounds_of(h->heavy_rounds), longest_all,
+                                                            reorder == 3 ? 1 : 0, (uint32_t)R, d_a, h->blk_shift, h->slot_key);
     HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
@@ -1231,7 +1298,15 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
 // Section 3.3: which groups are pre-assigned to which worker and which are left to competition.
 int build_schedule(hbp_handle_s *h, hipStream_t st)
 {
-    if (h->G > 0) {
+    h->first_ticket_block = -1;
+    if (h->G > 0 && (h->flags & HBP_FLAG_PAPER_SCHEDULE)) {
+        const int32_t NBC = (int32_t)h->NBC;
+        const int64_t F = (h->B * (int64_t)h->fixed_q8) / (256 * (int64_t)h->P);
+        h->first_ticket_block = F * h->P;
+        k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
+        k_paper_schedule<<<blocks_for((int64_t)h->P + 1, 256), 256, 0, st>>>(h->blk_group_ptr, h->blk_bn, F, (int32_t)h->B, NBC, h->P,
+                                                                             h->fixed_start, h->fixed_col, h->comp_lo, h->comp_col);
+    } else if (h->G > 0) {
         const int32_t NBC = (int32_t)h->NBC;
         k_col_group_ptr<<<blocks_for(h->NBC + 1, 256), 256, 0, st>>>(h->col_blk_ptr, h->blk_group_ptr, NBC, h->col_group_ptr);
         const Weights wt{h->group_ptr, h->group_slot, h->group_rounds, (int64_t)h->slot_weight, (int64_t)h->round_weight,
@@ -1258,6 +1333,13 @@ int release_workspace()
             w.bytes = 0;
         }
     return rc;
+}
+
+int hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t R, uint32_t *keys, hipStream_t st)
+{
+    if (count > 0) k_hash_keys<<<blocks_for(count, 256), 256, 0, st>>>(n, count, (uint32_t)a, (uint32_t)R, keys);
+    HBP_HIP(hipGetLastError());
+    return HBP_OK;
 }
 
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t st)

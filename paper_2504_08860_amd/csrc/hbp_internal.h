@@ -23,6 +23,7 @@ struct Layout {
     int32_t B, S, G;
     int32_t NBR, NBC, P;
     int32_t competitive;  // 0 when every group is fixed (nothing to compete for)
+    int32_t ticket_b0;    // the paper's schedule: first block behind the single ticket counter; -1: not in use
     int64_t n_rows, n_cols;
     const int32_t *blk_bm, *blk_bn, *slot_ptr, *blk_group_ptr, *col_blk_ptr, *stripe_ptr, *stripe_blk;
     const int32_t *group_ptr, *group_slot, *group_rounds;
@@ -69,6 +70,10 @@ struct hbp_handle_s {
     void *data;
     void *partial;       // [S] per-slot partial sums of the SpMV part
     uint32_t *ticket;    // [P] competitive groups of every worker's range claimed so far, zero between calls
+    uint32_t *slot_key;  // [S] key each slot was placed by, or null (HBP_FLAG_KEEP_KEYS)
+    int32_t *blk_shift;  // [B] shift a of each block's keys
+    int64_t first_ticket_block;  // the paper's schedule (HBP_FLAG_PAPER_SCHEDULE): P F; -1 otherwise
+    uint32_t flags;      // HBP_FLAG_* the handle was built with
 };
 
 namespace hbp {
@@ -89,6 +94,7 @@ int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col
                  const hbp_params_t &p, hipStream_t stream);
 int build_schedule(hbp_handle_s *h, hipStream_t stream);
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
+int hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t R, uint32_t *keys, hipStream_t stream);
 int release_workspace();
 
 // spmv (hbp_spmv.hip)

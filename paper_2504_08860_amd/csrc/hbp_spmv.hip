@@ -23,7 +23,9 @@ Layout hbp_view(const hbp_handle_s *h)
     L.R = h->R; L.C = h->C; L.W = h->W;
     L.B = (int32_t)h->B; L.S = (int32_t)h->S; L.G = (int32_t)h->G;
     L.NBR = (int32_t)h->NBR; L.NBC = (int32_t)h->NBC; L.P = h->P;
-    L.competitive = h->fixed_q8 < 256 ? 1 : 0;
+    const bool paper = h->first_ticket_block >= 0;
+    L.competitive = !paper && h->fixed_q8 < 256 ? 1 : 0;
+    L.ticket_b0 = paper ? (int32_t)h->first_ticket_block : -1;
     L.n_rows = h->n_rows; L.n_cols = h->n_cols;
     L.blk_bm = h->blk_bm; L.blk_bn = h->blk_bn; L.slot_ptr = h->slot_ptr; L.blk_group_ptr = h->blk_group_ptr;
     L.col_blk_ptr = h->col_blk_ptr; L.stripe_ptr = h->stripe_ptr; L.stripe_blk = h->stripe_blk;

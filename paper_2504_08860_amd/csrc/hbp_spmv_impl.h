@@ -677,7 +677,8 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
     //     have been claimed; a worker that has run out of work moves to the range with the most
     //     weight left (and stages the segment of x of that range's last column), until no range
     //     has enough left to be worth entering.  So a range that takes longer than its weight said is finished by the workers
-    //     that were faster than theirs.
+    //     that were faster than theirs;
+    //   phase 3 instead of 2, the paper's schedule: one ticket counter over the blocks that were not pre-assigned.
     const bool competitive = L.competitive != 0;
     int32_t col = L.fixed_col[worker];
     int32_t g_next = L.fixed_start[worker];
@@ -705,10 +706,24 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                 g_next = ge;
             }
             if (!found) {
+                if (L.ticket_b0 >= 0) { phase = 3; continue; }
                 if (!competitive) break;
                 phase = 2;
                 continue;
             }
+        } else if (phase == 3) {
+            // The paper's own competitive part (Section 3.3, when the handle was built for it): the
+            // blocks behind the pre-assigned ones are claimed one at a time through a single ticket
+            // counter; whoever holds a ticket fetches that block's segment of x and walks the block.
+            if (threadIdx.x == 0) sh_next = (int32_t)atomicAdd(&col_ticket[0], 1u);
+            __syncthreads();
+            const int64_t b = (int64_t)L.ticket_b0 + (uint32_t)sh_next;
+            __syncthreads();  // sh_next is rewritten in the next turn
+            if (b >= L.B) break;
+            r_bn = L.blk_bn[b];
+            r_g0 = L.blk_group_ptr[b];
+            r_g1 = L.blk_group_ptr[b + 1];
+            r_compete = false;
         } else {
             if (wave == 0) {
                 int32_t best = -1;

@@ -16,7 +16,8 @@ TOL = 1e-5
 TOL_F64 = 168 * 2.0**-53
 LAYOUT_ARRAYS = ("blk_bm", "blk_bn", "slot_ptr", "blk_group_ptr", "col_blk_ptr", "stripe_ptr", "stripe_blk",
                  "group_ptr", "group_slot", "group_rounds", "col_group_ptr", "comp_lo", "comp_col", "fixed_start", "fixed_col",
-                 "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "col_local", "data", "add_sign")
+                 "unit_ptr", "unit_stripe", "unit_k", "multi_stripes", "row_local", "seg_len", "slot_key", "blk_shift", "col_local",
+                 "data", "add_sign")
 
 
 @pytest.fixture(scope="module")
@@ -41,14 +42,18 @@ def check_against_oracle(H, oracle, m, check_add_sign=True, **params):
     tol = TOL_F64 if f64 else TOL
     build, spmv = (H.hbp_build_f64, H.hbp_spmv_f64) if f64 else (H.hbp_build, H.hbp_spmv)
     print(f"[case] {m.name} rows={m.n_rows} cols={m.n_cols} nnz={m.nnz} {m.val.dtype} params={params}", flush=True)
-    h = build(ptr, col, val, m.n_rows, m.n_cols, **params)
+    h = build(ptr, col, val, m.n_rows, m.n_cols, keep_keys=True, **params)   # the keys themselves are compared too
     try:
         info = H.hbp_get_info(h)
+        shift = (-2 if params.get("no_reorder") else -3 if params.get("key_length") else -4 if params.get("block_shift")
+                 else params.get("hash_shift", -1))
         o = oracle.OracleHbp(m.ptr, m.col, m.val, m.n_rows, m.n_cols, R=info.rows_per_block, C=info.cols_per_block,
-                             W=info.group_width, hash_shift=-2 if params.get("no_reorder") else -3 if params.get("key_length") else params.get("hash_shift", -1),
+                             W=info.group_width, hash_shift=shift,
                              num_workers=info.num_workers, fixed_q8=info.fixed_fraction_q8,
                              slot_weight=info.slot_weight, unit_slots=info.combine_unit_slots,
-                             round_weight=info.round_weight, group_weight=info.group_weight, column_weight=info.column_weight)
+                             round_weight=info.round_weight, group_weight=info.group_weight, column_weight=info.column_weight,
+                             paper_schedule=bool(params.get("paper_schedule")))
+        assert info.first_ticket_block == o.first_ticket_block
         assert (info.nnz, info.blocks, info.slots, info.groups) == (o.nnz, o.B, o.S, o.G)
         assert info.hash_shift == o.a and info.value_bytes == m.val.dtype.itemsize
         assert (info.combine_units, info.split_row_blocks) == (o.U, o.NM)
@@ -323,6 +328,46 @@ def test_length_key(H, oracle, R, C):
     m = _mixed_matrix(seed=11)
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, key_length=True)
     check_against_oracle(H, oracle, make_config(4, 2**-7), rows_per_block=512, cols_per_block=2048, key_length=True)
+
+
+def test_hash_values_all_lengths(H, oracle):
+    """The device's hash function, value by value: every length a block can hold (0..C with C the
+    largest block width), every shift 0..12, for block heights that exercise the clamp to R - 1
+    (R = 1, 4), a band of one (R = 9), the paper's 512 and the largest the library accepts."""
+    import torch
+    n = np.arange(0, 32768 + 1, dtype=np.uint32)
+    n_dev = torch.from_numpy(n.astype(np.int32)).cuda()
+    for R in (1, 4, 9, 512, 8192):
+        for a in range(13):
+            got = H.hbp_hash_keys(n_dev, a, R).cpu().numpy().view(np.uint32)
+            want = oracle.hash_keys(n, a, R)
+            assert np.array_equal(got, want), f"R={R} a={a}: first difference at n={np.flatnonzero(got != want)[:3]}"
+    with pytest.raises(H.HbpError):
+        H.hbp_hash_keys(n_dev, 13, 512)
+    with pytest.raises(H.HbpError):
+        H.hbp_hash_keys(n_dev, 0, 8193)
+
+
+@pytest.mark.parametrize("R,C", [(64, 128), (512, 4096), (2048, 8192)])
+def test_block_shift(H, oracle, R, C):
+    """HBP_FLAG_BLOCK_SHIFT (hash study): one shift per block, taken from the block's own rows."""
+    m = _mixed_matrix(seed=13)
+    info = check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C, block_shift=True)
+    check_against_oracle(H, oracle, make_config(4, 2**-7), rows_per_block=512, cols_per_block=2048, block_shift=True)
+    check_against_oracle(H, oracle, make_config(5, 0.01), rows_per_block=R, cols_per_block=C, block_shift=True)
+
+
+@pytest.mark.parametrize("P,q8", [(1, 256), (3, 224), (7, 0), (64, 128), (500, 255)])
+def test_paper_schedule(H, oracle, P, q8):
+    """HBP_FLAG_PAPER_SCHEDULE: Section 3.3 read literally (equal block counts per worker, a single
+    ticket counter over the rest).  Schedule arrays bit-equal to the oracle's, y within tolerance,
+    twice in a row (the ticket counter is re-armed)."""
+    m = random_csr(3000, 3000, 0.01, 21, empty_row_frac=0.1)
+    info = check_against_oracle(H, oracle, m, rows_per_block=64, cols_per_block=128, num_workers=P, fixed_fraction_q8=q8,
+                                paper_schedule=True)
+    assert info.first_ticket_block == P * ((info.blocks * q8) // (256 * P))
+    check_against_oracle(H, oracle, _mixed_matrix(seed=17), check_add_sign=False, rows_per_block=1024, cols_per_block=2048,
+                         num_workers=P, fixed_fraction_q8=q8, paper_schedule=True, threads_per_worker=512, rounds_per_batch=4)
 
 
 @pytest.mark.parametrize("q8", [256, 128])

@@ -425,3 +425,82 @@ def test_length_key_orders_rows_by_length(oracle):
     y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
     y, _ = by_len.spmv(m.x)
     assert np.all(np.abs(y - y_ref) <= 1e-12 * np.maximum(s_abs, 1e-300))
+
+
+# ---------------------------------------------------------------- keys, per-block shift, the paper's schedule
+
+def _hash_key_by_hand(n, a, R):
+    """The hash of Section 3.2 written out again (aggregation, dispersion, linear mapping, clamp)."""
+    b = max(1, R // 9)
+    return min(min(n >> a, 8) * b + (((n % (1 << a)) * b) >> a), R - 1)
+
+
+@pytest.mark.parametrize("mode", [-1, 2, -2, -3])
+def test_slot_keys_are_the_keys_of_the_lengths(oracle, mode):
+    """slot_key is what ordered the slots: the hash of the slot's own length with the matrix's shift
+    (0 without reorder, the length itself in the length-key mode), non-decreasing inside a block."""
+    m = make_config(5, 0.004)
+    o = build(oracle, m, R=64, C=512, W=8, hash_shift=mode)
+    key, n, sp = o.array("slot_key"), o.array("seg_len"), o.array("slot_ptr")
+    want = (np.zeros_like(key) if mode == -2 else n.astype(np.uint32) if mode == -3
+            else np.array([_hash_key_by_hand(int(v), o.a, 64) for v in n], dtype=np.uint32))
+    assert np.array_equal(key, want)
+    assert np.all(o.array("blk_shift") == o.a)
+    for b in range(o.B):
+        assert np.all(np.diff(key[sp[b]:sp[b + 1]].astype(np.int64)) >= 0)
+
+
+def test_per_block_shift_by_brute_force(oracle):
+    """hash_shift = -4: each block's shift is the smallest a with at least 15/16 of the block's own rows
+    below 9 * 2^a (recounted here from the CSR arrays), its slots are in (key with that shift, row) order,
+    and the nonzeros still round-trip."""
+    m = make_config(4, 2**-9)   # R-MAT: dense and sparse blocks side by side
+    R, C = 128, 256
+    o = build(oracle, m, R=R, C=C, W=16, hash_shift=-4)
+    rows = np.repeat(np.arange(m.n_rows), np.diff(m.ptr))
+    bm, bn = rows // R, m.col // C
+    shifts = o.array("blk_shift")
+    assert len(set(shifts.tolist())) > 1, "the test matrix should need different shifts in different blocks"
+    sp, rl, sl, key = o.array("slot_ptr"), o.array("row_local"), o.array("seg_len"), o.array("slot_key")
+    for b in range(o.B):
+        sel = (bm == o.array("blk_bm")[b]) & (bn == o.array("blk_bn")[b])
+        lens = np.bincount(rows[sel] % R, minlength=R)
+        lens_nz = lens[lens > 0]
+        a = next((a for a in range(13) if 16 * np.count_nonzero(lens_nz < 9 * 2**a) >= 15 * len(lens_nz)), 12)
+        assert shifts[b] == a
+        order = sorted((_hash_key_by_hand(int(lens[r]), a, R), r) for r in np.flatnonzero(lens))
+        assert [r for _, r in order] == rl[sp[b]:sp[b + 1]].tolist()
+        assert [k for k, _ in order] == key[sp[b]:sp[b + 1]].tolist()
+        assert [int(lens[r]) for _, r in order] == sl[sp[b]:sp[b + 1]].tolist()
+    r2, c2, v2 = o.to_coo()
+    assert coo_set(r2, c2, v2) == csr_coo(m)
+    y, _ = o.spmv(m.x)
+    y_ref, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
+    assert np.all(np.abs(y - y_ref) <= 1e-12 * s_abs)
+
+
+@pytest.mark.parametrize("P,q8", [(1, 256), (3, 224), (5, 100), (16, 256), (40, 0), (1000, 255)])
+def test_paper_schedule_by_definition(oracle, P, q8):
+    """Section 3.3 read literally: F = floor(B f / P) blocks per worker in list order (blocks of one
+    column stay together: the list is column-major), the blocks from P F on behind one ticket counter;
+    every block is walked exactly once."""
+    m = random_csr(900, 1400, 0.02, 5, empty_row_frac=0.2)
+    o = build(oracle, m, R=32, C=64, W=8, num_workers=P, fixed_q8=q8, paper_schedule=True)
+    F = (o.B * q8) // (256 * P)
+    assert o.first_ticket_block == P * F and P * F <= o.B
+    bgp, fs = o.array("blk_group_ptr"), o.array("fixed_start")
+    assert fs.tolist() == [int(bgp[w * F]) for w in range(P + 1)]
+    assert np.array_equal(o.array("comp_lo"), fs[1:])          # nothing inside a range is competitive
+    covered = []
+    for w in range(P):
+        covered += list(range(w * F, (w + 1) * F))
+        if F:
+            assert o.array("fixed_col")[w] == o.array("blk_bn")[w * F]
+            assert o.array("comp_col")[w] == o.array("blk_bn")[(w + 1) * F - 1]
+    covered += list(range(P * F, o.B))                          # claimed one by one
+    assert covered == list(range(o.B))
+    # the layout itself does not depend on the schedule
+    o0 = build(oracle, m, R=32, C=64, W=8, num_workers=P, fixed_q8=q8)
+    for name in ("row_local", "seg_len", "col_local", "data", "group_ptr", "slot_key"):
+        assert np.array_equal(o.array(name), o0.array(name))
+    assert o0.first_ticket_block == -1
