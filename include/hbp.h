@@ -113,30 +113,38 @@ typedef enum {
                                   ignored; ignored itself with HBP_FLAG_NO_REORDER or HBP_FLAG_KEY_LENGTH. */
 #define HBP_FLAG_KEEP_KEYS 32u /* keep the key every slot was placed by (4 bytes per slot) for hbp_export */
 
-/* Build parameters.  Block sizes follow Section 3.1 (the paper derives 4096 columns from
- * its 48 KB of shared memory and picks 512 rows); here the vector segment of a block is
- * staged in the 160 KB LDS of a gfx950 compute unit as fp32. */
+/* Build parameters.  Section 3.1 derives its block of 512 rows x 4096 columns from the 48 KB of
+ * shared memory of the paper's GPUs; here the vector segment of a block is staged in the 160 KB
+ * LDS of a gfx950 compute unit, and a value of 0 (or -1 where 0 is a valid choice) leaves the
+ * choice to the library, which makes it from the matrix (the sampling pass of Section 3.2 also
+ * measures the mean number of nonzeros a row has inside one column block). */
 typedef struct {
-    int32_t rows_per_block;    /* R, 1..8192 (fp64: 1..4096); 0 = default 512                   */
-    int32_t cols_per_block;    /* C, 1..32768 (fp64: 1..16384): 128 KB of x in LDS; 0 = default 4096 */
+    int32_t rows_per_block;    /* R, 1..8192 (fp64: 1..4096); 0 = chosen: 512 when the sampled rows average 6 or
+                                  more nonzeros per column block, else 2048 (the paper's value is 512)  */
+    int32_t cols_per_block;    /* C, 1..32768 (fp64: 1..16384): at most 128 KB of x in LDS; 0 = chosen: that
+                                  maximum, or n_cols if the whole vector is shorter (the paper's value is 4096) */
     int32_t group_width;       /* W, 1..64 lanes per group; 0 = default 64 (one wavefront)      */
     int32_t num_workers;       /* P, persistent workgroups the schedule is built for, up to 65536; 0 = as many as
                                   fit on the device at once, but no more than one per threads_per_worker / 64 groups */
-    int32_t fixed_fraction_q8; /* share of every worker's range that is pre-assigned, in 1/256; -1 = default 224 */
+    int32_t fixed_fraction_q8; /* share of every worker's range that is pre-assigned, in 1/256; -1 = default 240 */
     int32_t hash_shift;        /* a, 0..12; -1 = sample it from the matrix (Section 3.2)        */
     int32_t claim_chunk;       /* competitive part: groups per wavefront that a worker claims from a
                                   block column at a time, 1..1024; 0 = default (two draws per wavefront) */
     int32_t threads_per_worker;/* workgroup size of the SpMV-part kernel: 256, 512, 1024; 0 = default */
     int32_t rounds_per_batch;  /* rounds a wavefront loads per group before accumulating: 2, 4, 8, 9, 16
                                   (2 and 4 walk 8 and 4 groups at once; fp64 with 1024 threads: 4 and 2);
-                                  0 = default                                                       */
-    int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 0..64; -1 = default 4  */
-    int32_t group_weight;      /* schedule weight of a group as such, in nonzeros: 0..4096; -1 = default 0 */
+                                  0 = chosen with R: 8 for long row segments, 4 for short ones        */
+    int32_t slot_weight;       /* schedule weight of a slot, in nonzeros: 0..64; -1 = default 20 (2 when the groups
+                                  average 512 nonzeros or more: see group_weight)                      */
+    int32_t group_weight;      /* schedule weight of a group as such, in nonzeros: 0..4096; -1 = default 600: what a
+                                  group costs a wavefront of the SpMV-part kernel next to a nonzero while loads are
+                                  waited for anyway; 60 when the groups average 512 nonzeros or more and are
+                                  streamed at the memory bandwidth (all four default weights are a tenth then) */
     int32_t combine_unit_slots;/* slots one workgroup of the combine part should get at most: a row block
                                   with more is cut into several units; >= 64; 0 = default: twice the
                                   mean number of slots per row block, at least 16384                 */
     int32_t round_weight;      /* schedule weight of one round of a group (its rounds = the length of
-                                  its longest row), in nonzeros: 0..1024; -1 = default 8             */
+                                  its longest row), in nonzeros: 0..1024; -1 = default 100 (10)      */
     int32_t heavy_group_rounds;/* a group with a row of more nonzeros than this (inside the block) is walked
                                   by all wavefronts of its worker together, each taking an equal share of
                                   its nonzeros, instead of by one: >= 1; 0 = default 2048.  A group with a row of
@@ -145,7 +153,7 @@ typedef struct {
     uint32_t flags;            /* HBP_FLAG_*                                                    */
     int32_t column_weight;     /* schedule weight of entering a block column (the worker fetches its segment
                                   of x), in nonzeros, charged to the column's first group when the group list
-                                  is cut into the workers' ranges: 0..16777216; -1 = default C           */
+                                  is cut into the workers' ranges: 0..16777216; -1 = default 600000 (60000) */
 } hbp_params_t;
 
 typedef struct {
@@ -191,7 +199,7 @@ typedef enum {
     HBP_ARRAY_BLK_SHIFT = 26 /* int32 [B], the shift a each block's keys were taken with                  */
 } hbp_array_id;
 
-/* Fills *params with the defaults (R 512, C 4096, W 64, everything else "default"). */
+/* Fills *params with "chosen by the library" for everything (W = 64; validation on). */
 int hbp_default_params(hbp_params_t *params /* HOST */);
 
 /* Preprocessing: CSR -> HBP (Section 3.2: sampling of the shift a, data preparation of
@@ -249,8 +257,10 @@ int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int i
 int hbp_spmv_timed_f64(hbp_handle_t h, const double *x, double *y, void *stream, int iters,
                        float *ms_part, float *ms_combine, float *ms_total);
 
-/* In-repo CSR baselines (Algorithm 1).  kind 0: one thread per row; kind 1: one wavefront
- * per row with a cross-lane reduction.  All pointers DEVICE; y overwritten. */
+/* In-repo CSR baselines (Algorithm 1; the mapping of rows to lanes is free).  kind 0: one thread per
+ * row; kind 1: one wavefront (64 lanes) per row; kind 2, 4, 8, 16, 32: that many lanes per row, each
+ * with a cross-lane reduction (pick the power of two nearest the mean row length).  Any other kind is
+ * HBP_ERR_INVALID_ARGUMENT.  All pointers DEVICE; y overwritten. */
 int hbp_csr_spmv(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const float *csr_val,
                  const float *x, float *y, int64_t n_rows, void *stream);
 int hbp_csr_spmv_f64(int kind, const int32_t *csr_ptr, const int32_t *csr_col, const double *csr_val,

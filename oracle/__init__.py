@@ -73,7 +73,7 @@ def _load():
         lib.oracle_hbp_dims.restype = None
         lib.oracle_hbp_copy.argtypes = [vp, i32, vp]
         lib.oracle_hbp_copy.restype = i64
-        lib.oracle_hbp_spmv.argtypes = [vp, vp, vp, vp]
+        lib.oracle_hbp_spmv.argtypes = [vp, vp, vp, vp, vp]
         lib.oracle_hbp_spmv.restype = None
         lib.oracle_hbp_to_coo.argtypes = [vp, vp, vp, vp]
         lib.oracle_hbp_to_coo.restype = None
@@ -153,12 +153,16 @@ class OracleHbp:
             self._cache[name] = out
         return self._cache[name]
 
-    def spmv(self, x):
-        """(y, partial) through the layout (Algorithm 3 walk + combine), fp64."""
+    def spmv(self, x, with_abs=False):
+        """(y, partial) through the layout (Algorithm 3 walk + combine), fp64; with_abs adds the per-slot
+        sums of absolute products."""
         partial = np.zeros(max(self.S, 1), dtype=np.float64)
+        mag = np.zeros(max(self.S, 1), dtype=np.float64)
         y = np.zeros(self.n_rows, dtype=np.float64)
         assert x.dtype == self.value_dtype
-        _load().oracle_hbp_spmv(self._h, _p(x), _p(partial), _p(y))
+        _load().oracle_hbp_spmv(self._h, _p(x), _p(partial), _p(y), _p(mag) if with_abs else None)
+        if with_abs:
+            return y, partial[: self.S], mag[: self.S]
         return y, partial[: self.S]
 
     def to_coo(self):

@@ -393,23 +393,28 @@ int64_t oracle_hbp_copy(const oracle_hbp *h, int32_t which, void *dst)
  * group g starts at group_ptr[g] + (s - group_slot[g]) (no empty slots in compact mode,
  * so the zero_row correction is 0) and walks its row with add_sign, accumulating then
  * stopping once add_sign is negative.  partial[s] is the block's contribution to row
- * bm*R + row_local[s].  Combine part: partial sums of a row are added with bn ascending. */
-void oracle_hbp_spmv(const oracle_hbp *h, const void *x_any, double *partial, double *y)
+ * bm*R + row_local[s].  Combine part: partial sums of a row are added with bn ascending.
+ * partial_abs (may be NULL): the sum of the absolute products of each slot, the scale of a
+ * tolerance test on the partial sums. */
+void oracle_hbp_spmv(const oracle_hbp *h, const void *x_any, double *partial, double *y, double *partial_abs)
 {
     for (int64_t b = 0; b < h->B; b++) {
         const int64_t x0 = (int64_t)h->blk_bn[b] * h->C;   /* start of the block's vector segment */
         for (int64_t g = h->blk_group_ptr[b]; g < h->blk_group_ptr[b + 1]; g++) {
             for (int64_t s = h->group_slot[g]; s < h->group_slot[g + 1]; s++) {
                 int64_t j = h->group_ptr[g] + (s - h->group_slot[g]);
-                double sum = 0.0;
+                double sum = 0.0, mag = 0.0;
                 int32_t step;
                 do {
-                    sum += h->value_bytes == 4 ? (double)h->data[j] * (double)((const float *)x_any)[x0 + h->col_local[j]]
-                                               : h->data64[j] * ((const double *)x_any)[x0 + h->col_local[j]];
+                    double prod = h->value_bytes == 4 ? (double)h->data[j] * (double)((const float *)x_any)[x0 + h->col_local[j]]
+                                                      : h->data64[j] * ((const double *)x_any)[x0 + h->col_local[j]];
+                    sum += prod;
+                    mag += prod < 0 ? -prod : prod;
                     step = h->add_sign[j];
                     j += step;
                 } while (step > 0);
                 partial[s] = sum;
+                if (partial_abs) partial_abs[s] = mag;
             }
         }
     }

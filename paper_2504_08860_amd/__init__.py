@@ -249,7 +249,7 @@ def hbp_export(handle: int, name: str):
 
 
 def hbp_csr_spmv(kind: int, csr_ptr, csr_col, csr_val, x, y, stream=None) -> None:
-    """In-repo CSR baseline: kind 0 = thread per row, 1 = wavefront per row."""
+    """In-repo CSR baseline: kind 0 = thread per row, 1 = wavefront per row, 2/4/8/16/32 = that many lanes per row."""
     _check(lib().hbp_csr_spmv(int(kind), _dev_i32(csr_ptr, "csr_ptr"), _dev_i32(csr_col, "csr_col"),
                               _dev_f32(csr_val, "csr_val"), _dev_f32(x, "x"), _dev_f32(y, "y"),
                               csr_ptr.numel() - 1, _stream_ptr(stream)), "hbp_csr_spmv")

@@ -37,8 +37,8 @@ extern "C" {
 int hbp_default_params(hbp_params_t *p)
 {
     if (!p) return HBP_ERR_INVALID_ARGUMENT;
-    p->rows_per_block = 512;
-    p->cols_per_block = 4096;
+    p->rows_per_block = 0;
+    p->cols_per_block = 0;
     p->group_width = 64;
     p->num_workers = 0;
     p->fixed_fraction_q8 = -1;
@@ -66,16 +66,16 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
     hbp_params_t p;
     hbp_default_params(&p);
     if (params) p = *params;
-    if (p.rows_per_block == 0) p.rows_per_block = 512;
-    if (p.cols_per_block == 0) p.cols_per_block = 4096;
     if (p.group_width == 0) p.group_width = 64;
-    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 224;
-    if (p.slot_weight < 0) p.slot_weight = 4;
-    if (p.group_weight < 0) p.group_weight = 0;
-    if (p.round_weight < 0) p.round_weight = 8;
-    if (p.column_weight < 0) p.column_weight = p.cols_per_block;  // about what staging C values of x costs, in nonzeros
+    if (p.fixed_fraction_q8 < 0) p.fixed_fraction_q8 = 240;
     if (p.heavy_group_rounds == 0) p.heavy_group_rounds = 2048;
     const int32_t max_r = value_bytes == 8 ? hbp::kMaxR64 : hbp::kMaxR, max_c = value_bytes == 8 ? hbp::kMaxC64 : hbp::kMaxC;
+    if (p.rows_per_block < 0 || p.cols_per_block < 0 || p.rows_per_block > max_r || p.cols_per_block > max_c) return HBP_ERR_INVALID_ARGUMENT;
+    {
+        // whatever was left to the library is chosen from the matrix now (one sampling pass)
+        const int rc_choice = hbp::choose_block_parameters(csr_ptr, csr_col, n_rows, n_cols, value_bytes, p, (hipStream_t)stream);
+        if (rc_choice != HBP_OK) return rc_choice;
+    }
     if (p.rows_per_block < 1 || p.rows_per_block > max_r || p.cols_per_block < 1 || p.cols_per_block > max_c ||
         p.group_width < 1 || p.group_width > hbp::kWave || p.num_workers < 0 || p.num_workers > 65536 ||
         p.fixed_fraction_q8 > 256 || p.hash_shift > 12 || p.claim_chunk < 0 || p.claim_chunk > 1024 || p.slot_weight > 64 || p.group_weight > 4096 ||
@@ -109,11 +109,7 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
         h->threads = threads;
         h->unroll = p.rounds_per_batch ? p.rounds_per_batch : 8;
         h->fixed_q8 = p.fixed_fraction_q8;
-        h->slot_weight = p.slot_weight;
-        h->group_weight = p.group_weight;
         h->unit_slots = p.combine_unit_slots;
-        h->round_weight = p.round_weight;
-        h->column_weight = p.column_weight;
         h->heavy_rounds = p.heavy_group_rounds;
         h->P = p.num_workers > 0 ? p.num_workers : workers;
         rc = hbp::build_layout(h, csr_ptr, csr_col, csr_val, p, (hipStream_t)stream);
@@ -123,6 +119,20 @@ static int build_any(int32_t value_bytes, const int32_t *csr_ptr, const int32_t 
         free_arrays(h);
         delete h;
         return rc;
+    }
+    {
+        // Schedule weights, in units of one nonzero, where the caller left them open.  They are costs of
+        // the SpMV-part kernel on MI355X, not properties of a matrix: measured over workers with very
+        // different mixes, a group costs a wavefront 18 ns, a round 3 ns, a slot 0.6 ns and entering a
+        // block column costs the worker 19 us, next to 0.03 ns per nonzero while the wavefront waits for
+        // its loads anyway (groups of a few hundred nonzeros).  Groups of 512 nonzeros and more are
+        // streamed at the worker's share of the memory bandwidth instead (0.3 ns per nonzero): the same
+        // costs are a tenth as many nonzeros there.
+        const bool streamed = h->G > 0 && h->nnz >= 512 * h->G;
+        h->slot_weight = p.slot_weight >= 0 ? p.slot_weight : streamed ? 2 : 20;
+        h->group_weight = p.group_weight >= 0 ? p.group_weight : streamed ? 60 : 600;
+        h->round_weight = p.round_weight >= 0 ? p.round_weight : streamed ? 10 : 100;
+        h->column_weight = p.column_weight >= 0 ? p.column_weight : streamed ? 60000 : 600000;
     }
     if (p.num_workers == 0) {
         // device default: no more workers than the groups can keep busy, one group per wavefront
@@ -297,7 +307,7 @@ int hbp_export(hbp_handle_t h, int which, void *host_dst, size_t capacity, size_
 static int csr_any(int32_t value_bytes, int kind, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val, const void *x,
                    void *y, int64_t n_rows, void *stream)
 {
-    if ((kind != 0 && kind != 1) || !csr_ptr || !csr_col || !csr_val || !x || !y || n_rows < 1 ||
+    if (!csr_ptr || !csr_col || !csr_val || !x || !y || n_rows < 1 ||
         n_rows >= (int64_t(1) << 31) - 1)
         return HBP_ERR_INVALID_ARGUMENT;
     return hbp::launch_csr(kind, value_bytes, csr_ptr, csr_col, csr_val, x, y, n_rows, (hipStream_t)stream);

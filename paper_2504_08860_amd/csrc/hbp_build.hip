@@ -156,13 +156,15 @@ __device__ __forceinline__ uint32_t hash_key(uint32_t n, uint32_t a, uint32_t b,
 }
 
 // Sampling of the shift a: histogram, over the segments of up to 4096 evenly spaced rows, of
-// the smallest a in 0..12 with n < 9 * 2^a.  One wavefront walks one sampled row.
+// the smallest a in 0..12 with n < 9 * 2^a.  One wavefront walks one sampled row.  hist[14] also
+// counts the sampled segments with at least kLongSegment nonzeros (block sizes are chosen by it).
+constexpr int kLongSegment = 6;
 __global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
                                                      int64_t n_rows, int64_t nnz, int32_t C, int32_t S,
                                                      uint32_t *__restrict__ hist)
 {
-    __shared__ uint32_t sh_hist[14];
-    if (threadIdx.x < 14) sh_hist[threadIdx.x] = 0;
+    __shared__ uint32_t sh_hist[15];  // [14]: sampled segments with kLongSegment or more nonzeros
+    if (threadIdx.x < 15) sh_hist[threadIdx.x] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -170,6 +172,7 @@ __global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__
         int a = 0;
         while (a < 13 && n >= (9 << a)) a++;
         atomicAdd(&sh_hist[a], 1u);
+        if (n >= kLongSegment) atomicAdd(&sh_hist[14], 1u);
     };
     if (k < S) {
         const int64_t r = ((int64_t)k * n_rows) / S;
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(256) void k_sample_hist(const int32_t *__restrict__
         if (open >= 0 && lane == 0) tally((int)(j1 - open));
     }
     __syncthreads();
-    if (threadIdx.x < 14 && sh_hist[threadIdx.x]) atomicAdd(&hist[threadIdx.x], sh_hist[threadIdx.x]);
+    if (threadIdx.x < 15 && sh_hist[threadIdx.x]) atomicAdd(&hist[threadIdx.x], sh_hist[threadIdx.x]);
 }
 
 // a = smallest shift for which at least 15/16 of the sampled segments aggregate into 0..8.
@@ -1075,6 +1078,61 @@ inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + pe
 #define HBP_TRY(expr) do { int rc_ = (expr); if (rc_ != HBP_OK) return rc_; } while (0)
 
 }  // namespace
+
+// Parameters left at "choose for me" (Section 3.1 derives its 512 x 4096 from the shared memory of
+// the paper's GPUs; here they follow the matrix and the 160 KB of LDS of a gfx950 compute unit):
+//   C     the widest segment of x that fits the LDS budget of a worker (32768 fp32 / 16384 fp64
+//         values), or the whole vector when it is shorter: every column block less means one
+//         partial sum less per row, and the partial sums are the traffic the method adds;
+//   R, rounds per batch
+//         from the nonzeros the sampled rows have inside one column block (the sampling pass of
+//         Section 3.2, which also yields the shift a): when at least half of the sampled segments
+//         hold 6 or more nonzeros, the paper's R = 512 and deep batches (8 rounds, one group at a
+//         time); otherwise R = 2048 (four times fewer, fuller blocks for the same slots) and 4
+//         rounds with four groups in flight.  Both thresholds are measured on MI355X.
+// The sampled shift is written back into p.hash_shift, so that the build does not sample again.
+int choose_block_parameters(const int32_t *csr_ptr, const int32_t *csr_col, int64_t n_rows, int64_t n_cols, int32_t value_bytes,
+                            hbp_params_t &p, hipStream_t st)
+{
+    const int32_t max_c = value_bytes == 8 ? kMaxC64 : kMaxC;
+    if (p.cols_per_block == 0) p.cols_per_block = (int32_t)std::min<int64_t>(max_c, n_cols);
+    const bool need_stats = p.rows_per_block == 0 || p.rounds_per_batch == 0;
+    if (!need_stats) return HBP_OK;
+    if (p.cols_per_block < 1 || p.cols_per_block > max_c) return HBP_ERR_INVALID_ARGUMENT;
+    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
+    int device = 0;
+    HBP_HIP(hipGetDevice(&device));
+    int32_t ends[2] = {0, 0};
+    HBP_HIP(hipMemcpyAsync(&ends[0], csr_ptr, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipMemcpyAsync(&ends[1], csr_ptr + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HBP_HIP(hipStreamSynchronize(st));
+    if (ends[0] != 0 || ends[1] < 0) return HBP_ERR_BAD_CSR_PTR;
+    const int64_t nnz = ends[1];
+    uint32_t host[16] = {0};
+    int32_t a = 0;
+    if (nnz > 0) {
+        void *buf = nullptr;
+        const int rc = workspace_get(device, 1, 256, &buf);
+        if (rc != HBP_OK) return rc;
+        uint32_t *hist = static_cast<uint32_t *>(buf);
+        int32_t *d_a = reinterpret_cast<int32_t *>(hist + 16);
+        HBP_HIP(hipMemsetAsync(hist, 0, 17 * sizeof(uint32_t), st));
+        const int32_t S_rows = (int32_t)std::min<int64_t>(n_rows, 4096);
+        k_sample_hist<<<blocks_for(S_rows, 4), 256, 0, st>>>(csr_ptr, csr_col, n_rows, nnz, p.cols_per_block, S_rows, hist);
+        k_pick_shift<<<1, 64, 0, st>>>(hist, d_a);
+        HBP_HIP(hipGetLastError());
+        HBP_HIP(hipMemcpyAsync(host, hist, sizeof host, hipMemcpyDeviceToHost, st));
+        HBP_HIP(hipMemcpyAsync(&a, d_a, sizeof a, hipMemcpyDeviceToHost, st));
+        HBP_HIP(hipStreamSynchronize(st));
+    }
+    uint64_t segments = 0;
+    for (int i = 0; i < 14; i++) segments += host[i];
+    const bool long_segments = segments > 0 && 2 * (uint64_t)host[14] >= segments;
+    if (p.rows_per_block == 0) p.rows_per_block = long_segments ? 512 : 2048;
+    if (p.rounds_per_batch == 0) p.rounds_per_batch = long_segments ? 8 : 4;
+    if (p.hash_shift < 0 && nnz > 0) p.hash_shift = a;
+    return HBP_OK;
+}
 
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t st)

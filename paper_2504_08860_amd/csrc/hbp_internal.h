@@ -93,6 +93,8 @@ void set_last_hip_error(hipError_t e);
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t stream);
 int build_schedule(hbp_handle_s *h, hipStream_t stream);
+int choose_block_parameters(const int32_t *csr_ptr, const int32_t *csr_col, int64_t n_rows, int64_t n_cols, int32_t value_bytes,
+                            hbp_params_t &p, hipStream_t stream);
 int derive_add_sign(const hbp_handle_s *h, int32_t *d_out, hipStream_t stream);
 int hash_keys(const uint32_t *n, int64_t count, int32_t a, int32_t R, uint32_t *keys, hipStream_t stream);
 int release_workspace();

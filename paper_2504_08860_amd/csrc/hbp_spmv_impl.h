@@ -940,6 +940,24 @@ __global__ __launch_bounds__(256) void k_csr_scalar(const int32_t *__restrict__ 
     y[i] = sum;
 }
 
+// LPR lanes per row (a power of two below 64): the mapping between one thread and one wavefront per
+// row, for matrices whose rows hold a few to a few dozen nonzeros.
+template <int LPR, typename T>
+__global__ __launch_bounds__(256) void k_csr_sub(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
+                                                 const T *__restrict__ val, const T *__restrict__ x,
+                                                 T *__restrict__ y, int64_t n_rows)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = t / LPR;
+    const int sub = (int)(t % LPR);
+    T sum = T(0);
+    if (i < n_rows)
+        for (int32_t j = ptr[i] + sub; j < ptr[i + 1]; j += LPR) sum += val[j] * x[col[j]];
+#pragma unroll
+    for (int d = LPR / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d);  // stays inside the row's LPR lanes
+    if (i < n_rows && sub == 0) y[i] = sum;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_csr_vector(const int32_t *__restrict__ ptr, const int32_t *__restrict__ col,
                                                     const T *__restrict__ val, const T *__restrict__ x,
@@ -1033,10 +1051,20 @@ template <typename T>
 static int launch_csr_t(int kind, const int32_t *ptr, const int32_t *col, const T *val, const T *x, T *y, int64_t n_rows,
                         hipStream_t st)
 {
-    if (kind == 0)
-        k_csr_scalar<T><<<dim3((unsigned)((n_rows + 255) / 256)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
-    else
-        k_csr_vector<T><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
+    auto sub = [&](auto lanes) {
+        constexpr int LPR = decltype(lanes)::value;
+        k_csr_sub<LPR, T><<<dim3((unsigned)((n_rows * LPR + 255) / 256)), 256, 0, st>>>(ptr, col, val, x, y, n_rows);
+    };
+    switch (kind) {
+    case 0: k_csr_scalar<T><<<dim3((unsigned)((n_rows + 255) / 256)), 256, 0, st>>>(ptr, col, val, x, y, n_rows); break;
+    case 1: k_csr_vector<T><<<dim3((unsigned)((n_rows + 3) / 4)), 256, 0, st>>>(ptr, col, val, x, y, n_rows); break;
+    case 2: sub(std::integral_constant<int, 2>{}); break;
+    case 4: sub(std::integral_constant<int, 4>{}); break;
+    case 8: sub(std::integral_constant<int, 8>{}); break;
+    case 16: sub(std::integral_constant<int, 16>{}); break;
+    case 32: sub(std::integral_constant<int, 32>{}); break;
+    default: return HBP_ERR_INVALID_ARGUMENT;
+    }
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }

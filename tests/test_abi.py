@@ -41,7 +41,7 @@ def test_header_symbols_are_exported():
 def test_host_only_calls():
     import paper_2504_08860_amd as H
     p = H.hbp_default_params()
-    assert (p.rows_per_block, p.cols_per_block, p.group_width) == (512, 4096, 64)   # Section 3.1 sizes, wave64
+    assert (p.rows_per_block, p.cols_per_block, p.group_width) == (0, 0, 64)   # block sizes chosen from the matrix, wave64
     assert H.hbp_status_string(0) == "ok" and "column" in H.hbp_status_string(-3)
     assert H.lib().hbp_free(None) == 0
     assert H.lib().hbp_get_info(None, None) == -1
