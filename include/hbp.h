@@ -237,6 +237,18 @@ int hbp_build_f64(const int32_t *csr_ptr, const int32_t *csr_col, const double *
                   int64_t n_rows, int64_t n_cols, const hbp_params_t *params, void *stream, hbp_handle_t *out);
 int hbp_spmv_f64(hbp_handle_t h, const double *x, double *y, void *stream);
 
+/* hbp_spmv for callers that cannot allocate device memory or must not touch memory the library
+ * allocated for the handle's intermediates: code under HIP graph capture that replays on several
+ * handles, tight serving loops, harnesses that forbid hipMalloc.  Same result as hbp_spmv (fp32
+ * handles), but the per-slot partial sums and the claim counters of the call live in a fixed array
+ * of the library (32 MiB per device, held until the process ends) instead of the handle's buffers:
+ * 256 KiB of claim counters and at most 8,323,072 slots (S * 4 bytes <= 32 MiB - 256 KiB).  A handle
+ * with more slots or more than 65536 workers is refused with HBP_ERR_TOO_LARGE.  The call allocates
+ * nothing, launches three kernels (the first clears the counters), and is asynchronous on `stream`.
+ * All calls on one device share the one array: calls that overlap in time on one device (different
+ * streams, different handles) race and must be ordered by the caller. */
+int hbp_spmv_static_scratch(hbp_handle_t h, const float *x, float *y, void *stream);
+
 /* Frees the handle and its device arrays (synchronises the device first). NULL is allowed. */
 int hbp_free(hbp_handle_t h);
 

@@ -41,6 +41,7 @@ EXPORTED_SYMBOLS = (
     "hbp_default_params", "hbp_build", "hbp_spmv", "hbp_free", "hbp_get_info", "hbp_export", "hbp_spmv_timed",
     "hbp_csr_spmv", "hbp_status_string", "hbp_last_hip_error",
     "hbp_build_f64", "hbp_spmv_f64", "hbp_spmv_timed_f64", "hbp_csr_spmv_f64", "hbp_release_workspace", "hbp_hash_keys",
+    "hbp_spmv_static_scratch",
 )
 
 
@@ -100,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.hbp_csr_spmv.argtypes = [ctypes.c_int, vp, vp, vp, vp, vp, i64, vp]
         L.hbp_build_f64.argtypes = L.hbp_build.argtypes
         L.hbp_spmv_f64.argtypes = L.hbp_spmv.argtypes
+        L.hbp_spmv_static_scratch.argtypes = L.hbp_spmv.argtypes
         L.hbp_spmv_timed_f64.argtypes = L.hbp_spmv_timed.argtypes
         L.hbp_csr_spmv_f64.argtypes = L.hbp_csr_spmv.argtypes
         L.hbp_status_string.argtypes = [ctypes.c_int]
@@ -200,6 +202,13 @@ def hbp_spmv(handle: int, x, y, stream=None) -> None:
     info = hbp_get_info(handle)
     assert x.numel() == info.n_cols and y.numel() == info.n_rows
     _check(lib().hbp_spmv(handle, _dev_f32(x, "x"), _dev_f32(y, "y"), _stream_ptr(stream)), "hbp_spmv")
+
+
+def hbp_spmv_static_scratch(handle: int, x, y, stream=None) -> None:
+    """hbp_spmv with the call's intermediates in the library's fixed scratch array (no allocation anywhere)."""
+    info = hbp_get_info(handle)
+    assert x.numel() == info.n_cols and y.numel() == info.n_rows
+    _check(lib().hbp_spmv_static_scratch(handle, _dev_f32(x, "x"), _dev_f32(y, "y"), _stream_ptr(stream)), "hbp_spmv_static_scratch")
 
 
 def hbp_spmv_f64(handle: int, x, y, stream=None) -> None:

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 namespace hbp {
@@ -28,6 +29,42 @@ void free_arrays(hbp_handle_s *h)
 {
     for (void *p : h->arena)
         if (p) (void)hipFree(p);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// hbp_spmv_static_scratch: the per-slot partial sums and the claim counters of one SpMV in a
+// fixed array of the library instead of the handle's own buffers.
+constexpr size_t kStaticTicketBytes = 65536 * sizeof(uint32_t);     // the largest worker count
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;            // 32 MiB per device
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+__global__ __launch_bounds__(256) void k_clear_u32(uint32_t *p, int32_t n)
+{
+    const int32_t i = (int32_t)(blockIdx.x * 256 + threadIdx.x);
+    if (i < n) p[i] = 0u;
+}
+
+// Device address of `scratch` on each device, looked up once with that device current (every GPU
+// holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_static_scratch_mutex;
+void *g_static_scratch[kMaxDevices] = {};
+
+int static_scratch_address(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return HBP_ERR_INVALID_ARGUMENT;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[device]) {
+        void *p = nullptr;
+        HBP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));  // the caller has made `device` current
+        g_static_scratch[device] = p;
+    }
+    *out = g_static_scratch[device];
+    return HBP_OK;
 }
 
 }  // namespace
@@ -156,9 +193,10 @@ static int spmv_any(int32_t value_bytes, hbp_handle_t h, const void *x, void *y,
     if (!h || !x || !y || h->value_bytes != value_bytes) return HBP_ERR_INVALID_ARGUMENT;
     DeviceGuard guard(h->device);
     if (!guard.ok) return HBP_ERR_HIP;
-    int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream);
+    const hbp::SpmvScratch own{h->partial, h->ticket};
+    int rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream, own);
     if (rc != HBP_OK) return rc;
-    return hbp::launch_combine(h, y, (hipStream_t)stream);
+    return hbp::launch_combine(h, y, (hipStream_t)stream, own);
 }
 
 static int spmv_timed_any(int32_t value_bytes, hbp_handle_t h, const void *x, void *y, void *stream, int iters, float *ms_part,
@@ -174,13 +212,14 @@ static int spmv_timed_any(int32_t value_bytes, hbp_handle_t h, const void *x, vo
     hipError_t err = hipSuccess;
     auto check = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; return err == hipSuccess; };
     int rc = HBP_OK;
+    const hbp::SpmvScratch own{h->partial, h->ticket};
     for (auto &e : ev)
         if (!check(hipEventCreate(&e))) break;
     for (int i = 0; i < iters && rc == HBP_OK && err == hipSuccess; i++) {
         if (!check(hipEventRecord(ev[0], st))) break;
-        rc = hbp::launch_spmv_part(h, x, y, st);
+        rc = hbp::launch_spmv_part(h, x, y, st, own);
         if (!check(hipEventRecord(ev[1], st))) break;
-        if (rc == HBP_OK) rc = hbp::launch_combine(h, y, st);
+        if (rc == HBP_OK) rc = hbp::launch_combine(h, y, st, own);
         if (!check(hipEventRecord(ev[2], st))) break;
         if (!check(hipEventSynchronize(ev[2])) || rc != HBP_OK) break;
         float a = 0, b = 0, c = 0;
@@ -328,6 +367,28 @@ int hbp_build_f64(const int32_t *csr_ptr, const int32_t *csr_col, const double *
 int hbp_spmv(hbp_handle_t h, const float *x, float *y, void *stream) { return spmv_any(4, h, x, y, stream); }
 
 int hbp_spmv_f64(hbp_handle_t h, const double *x, double *y, void *stream) { return spmv_any(8, h, x, y, stream); }
+
+int hbp_spmv_static_scratch(hbp_handle_t h, const float *x, float *y, void *stream)
+{
+    if (!h || !x || !y || h->value_bytes != 4) return HBP_ERR_INVALID_ARGUMENT;
+    // the claim counters take the first 256 KiB, the partial sums (one fp32 value per slot) the rest
+    if ((size_t)h->P * sizeof(uint32_t) > kStaticTicketBytes ||
+        (size_t)h->S * sizeof(float) > kStaticScratchBytes - kStaticTicketBytes)
+        return HBP_ERR_TOO_LARGE;
+    DeviceGuard guard(h->device);
+    if (!guard.ok) return HBP_ERR_HIP;
+    void *base = nullptr;
+    int rc = static_scratch_address(h->device, &base);
+    if (rc != HBP_OK) return rc;
+    const hbp::SpmvScratch fixed{static_cast<unsigned char *>(base) + kStaticTicketBytes, static_cast<uint32_t *>(base)};
+    // whatever the last call on this device left in the counters goes (a fill kernel, not a memset
+    // node: the call may be recorded into a HIP graph)
+    k_clear_u32<<<dim3((unsigned)((h->P + 255) / 256)), 256, 0, (hipStream_t)stream>>>(fixed.ticket, h->P);
+    HBP_HIP(hipGetLastError());
+    rc = hbp::launch_spmv_part(h, x, y, (hipStream_t)stream, fixed);
+    if (rc != HBP_OK) return rc;
+    return hbp::launch_combine(h, y, (hipStream_t)stream, fixed);
+}
 
 int hbp_spmv_timed(hbp_handle_t h, const float *x, float *y, void *stream, int iters, float *ms_part, float *ms_combine,
                    float *ms_total)

@@ -103,8 +103,13 @@ int release_workspace();
 Layout hbp_view(const hbp_handle_s *h);
 int default_workers(int device, int32_t C, int32_t value_bytes, int32_t threads_wanted, int32_t *threads_out, int32_t *workers_out);
 // x, y (and val): arrays of the handle's value type (value_bytes for the CSR baselines)
-int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t stream);
-int launch_combine(const hbp_handle_s *h, void *y, hipStream_t stream);
+// where one SpMV keeps its per-slot partial sums (S values of the handle's type) and its claim counters (P)
+struct SpmvScratch {
+    void *partial;
+    uint32_t *ticket;
+};
+int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t stream, SpmvScratch scratch);
+int launch_combine(const hbp_handle_s *h, void *y, hipStream_t stream, SpmvScratch scratch);
 int launch_csr(int kind, int value_bytes, const int32_t *ptr, const int32_t *col, const void *val, const void *x, void *y,
                int64_t n_rows, hipStream_t stream);
 

@@ -62,21 +62,21 @@ int default_workers(int device, int32_t C, int32_t value_bytes, int32_t threads_
 }
 
 // fp64 instantiations live in a translation unit of their own (hbp_spmv_f64.hip)
-int launch_spmv_part_f64(const hbp_handle_s *h, const double *x, double *y, hipStream_t st);
-int launch_combine_f64(const hbp_handle_s *h, double *y, hipStream_t st);
+int launch_spmv_part_f64(const hbp_handle_s *h, const double *x, double *y, hipStream_t st, SpmvScratch sc);
+int launch_combine_f64(const hbp_handle_s *h, double *y, hipStream_t st, SpmvScratch sc);
 int launch_csr_f64(int kind, const int32_t *ptr, const int32_t *col, const double *val, const double *x, double *y, int64_t n_rows,
                    hipStream_t st);
 
-int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t st)
+int launch_spmv_part(const hbp_handle_s *h, const void *x, void *y, hipStream_t st, SpmvScratch sc)
 {
-    if (h->value_bytes == 8) return launch_spmv_part_f64(h, static_cast<const double *>(x), static_cast<double *>(y), st);
-    return launch_part_t<float>(h, static_cast<const float *>(x), static_cast<float *>(y), st);
+    if (h->value_bytes == 8) return launch_spmv_part_f64(h, static_cast<const double *>(x), static_cast<double *>(y), st, sc);
+    return launch_part_t<float>(h, static_cast<const float *>(x), static_cast<float *>(y), st, sc);
 }
 
-int launch_combine(const hbp_handle_s *h, void *y, hipStream_t st)
+int launch_combine(const hbp_handle_s *h, void *y, hipStream_t st, SpmvScratch sc)
 {
-    if (h->value_bytes == 8) return launch_combine_f64(h, static_cast<double *>(y), st);
-    return launch_combine_t<float>(h, static_cast<float *>(y), st);
+    if (h->value_bytes == 8) return launch_combine_f64(h, static_cast<double *>(y), st, sc);
+    return launch_combine_t<float>(h, static_cast<float *>(y), st, sc);
 }
 
 int launch_csr(int kind, int value_bytes, const int32_t *ptr, const int32_t *col, const void *val, const void *x, void *y,

@@ -4,12 +4,12 @@
 
 namespace hbp {
 
-int launch_spmv_part_f64(const hbp_handle_s *h, const double *x, double *y, hipStream_t st)
+int launch_spmv_part_f64(const hbp_handle_s *h, const double *x, double *y, hipStream_t st, SpmvScratch sc)
 {
-    return launch_part_t<double>(h, x, y, st);
+    return launch_part_t<double>(h, x, y, st, sc);
 }
 
-int launch_combine_f64(const hbp_handle_s *h, double *y, hipStream_t st) { return launch_combine_t<double>(h, y, st); }
+int launch_combine_f64(const hbp_handle_s *h, double *y, hipStream_t st, SpmvScratch sc) { return launch_combine_t<double>(h, y, st, sc); }
 
 int launch_csr_f64(int kind, const int32_t *ptr, const int32_t *col, const double *val, const double *x, double *y, int64_t n_rows,
                    hipStream_t st)

@@ -989,60 +989,60 @@ static int raise_lds_cap(std::atomic<uint64_t> &done, int device, K kernel, int 
 }
 
 template <int THREADS, int U, int GP, bool HEAVY, typename T>
-static int launch_part(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st)
+static int launch_part(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st, SpmvScratch sc)
 {
     const size_t lds = (size_t)h->C * sizeof(T);
     static std::atomic<uint64_t> configured{0};  // per instantiation
     const int rc = raise_lds_cap(configured, h->device, k_spmv_part<THREADS, U, GP, HEAVY, T>,
                                  kMaxC * (int)sizeof(float));  // 128 KB: kMaxC floats or kMaxC64 doubles
     if (rc != HBP_OK) return rc;
-    k_spmv_part<THREADS, U, GP, HEAVY, T><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, static_cast<T *>(h->partial), y, h->ticket);
+    k_spmv_part<THREADS, U, GP, HEAVY, T><<<dim3((unsigned)h->P), THREADS, lds, st>>>(L, x, static_cast<T *>(sc.partial), y, sc.ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
 
 template <int THREADS, bool HEAVY, typename T>
-static int launch_part_u(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st)
+static int launch_part_u(const hbp_handle_s *h, const Layout &L, const T *x, T *y, hipStream_t st, SpmvScratch sc)
 {
     // fp64 at 1024 threads (128 registers per lane): half as many groups at once, or the batches spill
     constexpr int kHalf = sizeof(T) == 8 && THREADS == 1024 ? 2 : 1;
     switch (h->unroll) {  // rounds per batch; short batches walk several groups at once
-    case 2: return launch_part<THREADS, 2, 8 / kHalf, HEAVY, T>(h, L, x, y, st);
-    case 4: return launch_part<THREADS, 4, 4 / kHalf, HEAVY, T>(h, L, x, y, st);
-    case 9: return launch_part<THREADS, 9, 1, HEAVY, T>(h, L, x, y, st);
-    case 16: return launch_part<THREADS, 16, 1, HEAVY, T>(h, L, x, y, st);
-    default: return launch_part<THREADS, 8, 1, HEAVY, T>(h, L, x, y, st);
+    case 2: return launch_part<THREADS, 2, 8 / kHalf, HEAVY, T>(h, L, x, y, st, sc);
+    case 4: return launch_part<THREADS, 4, 4 / kHalf, HEAVY, T>(h, L, x, y, st, sc);
+    case 9: return launch_part<THREADS, 9, 1, HEAVY, T>(h, L, x, y, st, sc);
+    case 16: return launch_part<THREADS, 16, 1, HEAVY, T>(h, L, x, y, st, sc);
+    default: return launch_part<THREADS, 8, 1, HEAVY, T>(h, L, x, y, st, sc);
     }
 }
 
 template <typename T>
-static int launch_part_t(const hbp_handle_s *h, const T *x, T *y, hipStream_t st)
+static int launch_part_t(const hbp_handle_s *h, const T *x, T *y, hipStream_t st, SpmvScratch sc)
 {
     const Layout L = hbp_view(h);
     // the kernel that can share heavy groups among a worker's wavefronts only where the matrix has one
     if (h->longest_segment > long_rounds_of(h->heavy_rounds)) {
-        if (h->threads == 1024) return launch_part_u<1024, true, T>(h, L, x, y, st);
-        if (h->threads == 512) return launch_part_u<512, true, T>(h, L, x, y, st);
-        return launch_part_u<256, true, T>(h, L, x, y, st);
+        if (h->threads == 1024) return launch_part_u<1024, true, T>(h, L, x, y, st, sc);
+        if (h->threads == 512) return launch_part_u<512, true, T>(h, L, x, y, st, sc);
+        return launch_part_u<256, true, T>(h, L, x, y, st, sc);
     }
-    if (h->threads == 1024) return launch_part_u<1024, false, T>(h, L, x, y, st);
-    if (h->threads == 512) return launch_part_u<512, false, T>(h, L, x, y, st);
-    return launch_part_u<256, false, T>(h, L, x, y, st);
+    if (h->threads == 1024) return launch_part_u<1024, false, T>(h, L, x, y, st, sc);
+    if (h->threads == 512) return launch_part_u<512, false, T>(h, L, x, y, st, sc);
+    return launch_part_u<256, false, T>(h, L, x, y, st, sc);
 }
 
 template <typename T>
-static int launch_combine_t(const hbp_handle_s *h, T *y, hipStream_t st)
+static int launch_combine_t(const hbp_handle_s *h, T *y, hipStream_t st, SpmvScratch sc)
 {
     const Layout L = hbp_view(h);
     static std::atomic<uint64_t> configured{0};
     const int rc = raise_lds_cap(configured, h->device, k_combine<256, true, T>,
                                  4 * kMaxR * (int)sizeof(float));  // 128 KB: kMaxR floats or kMaxR64 doubles, four copies
     if (rc != HBP_OK) return rc;
-    const T *partial = static_cast<const T *>(h->partial);
+    const T *partial = static_cast<const T *>(sc.partial);
     if (h->R <= 1024)
-        k_combine<128, false, T><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, h->ticket);
+        k_combine<128, false, T><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
     else
-        k_combine<256, true, T><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, h->ticket);
+        k_combine<256, true, T><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
