@@ -1134,10 +1134,23 @@ int choose_block_parameters(const int32_t *csr_ptr, const int32_t *csr_col, int6
     return HBP_OK;
 }
 
+static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
+                               const hbp_params_t &p, hipStream_t st);
+
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t st)
 {
     std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
+    const int rc = build_layout_locked(h, csr_ptr, csr_col, csr_val, p, st);
+    // A build that gives up may have kernels in flight that still use the shared workspace: they
+    // have to finish before the lock is released and the next build takes the workspace over.
+    if (rc != HBP_OK) (void)hipStreamSynchronize(st);
+    return rc;
+}
+
+static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
+                               const hbp_params_t &p, hipStream_t st)
+{
     const int64_t n_rows = h->n_rows, n_cols = h->n_cols;
     const int32_t R = h->R, C = h->C, W = h->W;
     const int64_t NBR = h->NBR, NBC = h->NBC, D = NBR * NBC;

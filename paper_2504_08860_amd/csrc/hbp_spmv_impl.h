@@ -326,13 +326,49 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             const uint64_t live = __ballot(k < n);
             if (!live) break;
             const int32_t m = __popcll(live);
-            if (m > 32 || __ballot(k + 2 * U < n) != live) {
-                // many rows still going, or one of them ends soon: a deep batch of rounds
-                constexpr int UL = 16;
+            constexpr int UL = 16;
+            // (The folded batches below are compiled into the variant for matrices with very long
+            // rows only: in the other variants, whose groups rarely get there, their code cost the
+            // main path 4-10 % through registers and instruction cache.)
+            const bool few = HEAVY ? m <= 32 : (m <= 32 && __ballot(k + 2 * U < n) == live);
+            if (!few) {
+                // many rows still going: a deep batch of rounds
                 Batch<UL, T> deep;
                 issue_batch<UL>(deep, L.col_local, data, base, n, k);
                 acc += consume_batch<UL, true>(deep, xs, n, k);
                 k += UL;
+                continue;
+            }
+            if (HEAVY && __ballot(k + 2 * U < n) != live) {
+                // Few rows left and one of them ends soon.  A batch would use m of 64 lanes, so the
+                // wavefront is folded: with mm the power of two that holds the m live rows and
+                // f = 64 / mm, lane j * mm + c serves the c-th live row in the rounds k + j, k + j + f,
+                // k + j + 2f, ...  In that lane order (round, then row) the elements of f consecutive
+                // rounds are exactly what one step of a batch reads, so the batch code runs
+                // unchanged on the folded lanes' own counts and covers UL * f rounds.
+                const int sh = m > 16 ? 5 : m > 8 ? 4 : m > 4 ? 3 : m > 2 ? 2 : m > 1 ? 1 : 0;  // mm = 2^sh
+                int32_t *left = reinterpret_cast<int32_t *>(sh_hand + wave * 64);
+                left[lane] = 0;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (k < n) left[lanes_below(live)] = n - k;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                const int32_t mine = left[lane & ((1 << sh) - 1)], j = lane >> sh;  // rounds left in the row this lane serves
+                const int32_t steps = mine > j ? (mine - j + (64 >> sh) - 1) >> (6 - sh) : 0;
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                Batch<UL, T> deep;
+                issue_batch<UL>(deep, L.col_local, data, base, steps, 0);
+                T *hand = sh_hand + wave * 64;
+                hand[lane] = consume_batch<UL, true>(deep, xs, steps, 0);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (k < n)
+                    for (int32_t t = lanes_below(live); t < 64; t += 1 << sh) acc += hand[t];
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                k += UL << (6 - sh);
                 continue;
             }
             // Few rows left, all of them with at least 2U more rounds.  Until the shortest of

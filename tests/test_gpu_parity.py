@@ -202,6 +202,17 @@ def test_csr_baselines(H, oracle, kind):
         assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= TOL * s_abs)
 
 
+def test_csr_baseline_rejects_unknown_kind(H):
+    import torch
+    m = make_config(1)
+    ptr, col, val, x = to_dev(m)
+    y = torch.zeros(m.n_rows, device="cuda")
+    for kind in (3, 64, -1):
+        with pytest.raises(H.HbpError) as e:
+            H.hbp_csr_spmv(kind, ptr, col, val, x, y)
+        assert e.value.status == -1
+
+
 def _mixed_matrix(seed=5):
     """Rows of equal length in bulk (full equal groups -> aligned wide loads), a band of short
     rows (packs of several groups), and a few very long rows (deep batches, whole-wavefront
