@@ -816,14 +816,17 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 // Combine part (Fig. 1): one workgroup per row block adds the partial sums of that row block's
 // blocks into LDS copies of its y slice and writes the slice out, zeros included.  The slot
 // ranges of up to kPass blocks are fetched in parallel first; then wavefronts take blocks
-// round-robin and lanes stride over a block's slots, four independent loads at a time.
+// round-robin and lanes stride over a block's slots.  With kRing > 0 a wavefront keeps a ring of
+// kRing chunks of 64 kChunk slots in flight across its blocks (the kernel is bound by the bytes
+// it has in flight); with kRing = 0 it walks block by block, four loads per lane at a time, and
+// loads the small blocks of a pass together.
 // Every wavefront accumulates into its own copy of the slice with plain LDS read-add-write:
 // a block holds a row at most once, so the lanes of one instruction never collide, and a
 // wavefront's LDS accesses complete in order.  (LDS float atomics would allow one shared copy
 // but run an order of magnitude slower on this hardware.)  The copies are summed on the way out.
 // Also re-arms the per-column ticket counters for the next call (the SpMV part of this call
 // has finished: same stream).
-template <int THREADS, bool DEEP, typename T>
+template <int THREADS, typename T, int kRing, int kChunk>
 __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restrict__ partial, T *__restrict__ y,
                                                      uint32_t *__restrict__ ticket)
 {
@@ -857,6 +860,54 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
             range[2 * t + 1] = end;
             small |= end - first <= 64 * kFirst;
         }
+        if constexpr (kRing > 0) {
+            __syncthreads();
+            // A ring of kRing chunks of up to 64 kChunk consecutive slots of one block is kept in
+            // flight per wavefront: the chunks of a wavefront's blocks follow each other whatever
+            // the blocks' sizes, and a chunk is added (read all, then write all: its slots are
+            // distinct rows) while the loads of the next kRing - 1 are on their way.
+            int32_t next_block = wave, cur = 0, cur_end = 0;
+            int32_t c0[kRing], c1[kRing];
+            uint32_t r[kRing][kChunk];
+            T p[kRing][kChunk];
+            auto issue = [&](int d) __attribute__((always_inline)) {
+                while (cur >= cur_end && next_block < nb) {
+                    cur = __builtin_amdgcn_readfirstlane(range[2 * next_block]);
+                    cur_end = __builtin_amdgcn_readfirstlane(range[2 * next_block + 1]);
+                    next_block += kWaves;
+                }
+                c0[d] = cur;
+                c1[d] = min(cur + 64 * kChunk, cur_end);
+                cur = c1[d];
+#pragma unroll
+                for (int u = 0; u < kChunk; u++) {
+                    r[d][u] = 0;
+                    p[d][u] = T(0);
+                    if (c0[d] + 64 * u < c1[d]) {  // wave-uniform; clamped: always a slot of this chunk
+                        const int32_t idx = min(c0[d] + lane + 64 * u, c1[d] - 1);
+                        r[d][u] = L.row_local[idx];
+                        p[d][u] = partial[idx];
+                    }
+                }
+            };
+#pragma unroll
+            for (int d = 0; d < kRing; d++) issue(d);
+            while (c1[0] > c0[0]) {  // chunks are issued in order: when this one is empty, all are
+#pragma unroll
+                for (int d = 0; d < kRing; d++) {
+                    if (c1[d] > c0[d]) {
+                        T o[kChunk];
+#pragma unroll
+                        for (int u = 0; u < kChunk; u++) o[u] = ys[r[d][u]];
+#pragma unroll
+                        for (int u = 0; u < kChunk; u++)
+                            if (c0[d] + lane + 64 * u < c1[d]) ys[r[d][u]] = o[u] + p[d][u];
+                    }
+                    issue(d);
+                }
+            }
+            continue;
+        }
         if (!__syncthreads_or(small)) {
             // only blocks with many slots: wavefronts take them one by one, KU slots per lane in
             // flight (the kernel is bound by the bytes it has in flight); the slots of a step are
@@ -881,9 +932,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
                             if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
                     }
                 };
-                if (DEEP && s1 - s0 > 512) add_block(std::integral_constant<int, 16>{});
-                else if (DEEP) add_block(std::integral_constant<int, 8>{});
-                else add_block(std::integral_constant<int, 4>{});
+                add_block(std::integral_constant<int, 4>{});
             }
             continue;
         }
@@ -946,9 +995,7 @@ __global__ __launch_bounds__(THREADS) void k_combine(Layout L, const T *__restri
                             if (s + 64 * u < s1) ys[r[u]] = o[u] + p[u];
                     }
                 };
-                if (DEEP && slots > 512) add_block(std::integral_constant<int, 16>{});
-                else if (DEEP) add_block(std::integral_constant<int, 8>{});
-                else add_block(std::integral_constant<int, 4>{});
+                add_block(std::integral_constant<int, 4>{});
             }
         }
     }
@@ -1070,15 +1117,25 @@ template <typename T>
 static int launch_combine_t(const hbp_handle_s *h, T *y, hipStream_t st, SpmvScratch sc)
 {
     const Layout L = hbp_view(h);
-    static std::atomic<uint64_t> configured{0};
-    const int rc = raise_lds_cap(configured, h->device, k_combine<256, true, T>,
-                                 4 * kMaxR * (int)sizeof(float));  // 128 KB: kMaxR floats or kMaxR64 doubles, four copies
-    if (rc != HBP_OK) return rc;
     const T *partial = static_cast<const T *>(sc.partial);
-    if (h->R <= 1024)
-        k_combine<128, false, T><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
-    else
-        k_combine<256, true, T><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
+    if (h->R <= 1024) {
+        // two copies of a short slice: enough workgroups per CU for the plain block-by-block walk
+        k_combine<128, T, 0, 0><<<dim3((unsigned)h->U), 128, 2 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
+    } else {
+        // four copies (up to 128 KB: kMaxR floats or kMaxR64 doubles); a ring of chunks in flight,
+        // shorter chunks and more of them where the blocks hold few slots on average
+        auto go = [&](auto kr, auto kc, std::atomic<uint64_t> &configured) {
+            constexpr int KR = decltype(kr)::value, KC = decltype(kc)::value;
+            const int rc = raise_lds_cap(configured, h->device, k_combine<256, T, KR, KC>, 4 * kMaxR * (int)sizeof(float));
+            if (rc != HBP_OK) return rc;
+            k_combine<256, T, KR, KC><<<dim3((unsigned)h->U), 256, 4 * (size_t)h->R * sizeof(T), st>>>(L, partial, y, sc.ticket);
+            return (int)HBP_OK;
+        };
+        static std::atomic<uint64_t> configured_long{0}, configured_short{0};
+        const int rc = h->S < 128 * h->B ? go(std::integral_constant<int, 8>{}, std::integral_constant<int, 2>{}, configured_short)
+                                         : go(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{}, configured_long);
+        if (rc != HBP_OK) return rc;
+    }
     HBP_HIP(hipGetLastError());
     return HBP_OK;
 }
