@@ -609,6 +609,33 @@ __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_
     }
 }
 
+// Which blocks a workgroup of k_fill takes.  The kernel gathers from arrays in CSR order (columns,
+// values), where the pieces that the blocks of one row block need lie side by side in the same
+// 128-byte lines.  Taken in the layout's column-major order every block fetches those lines anew
+// (16 times the bytes on a matrix with short row segments).  Here the blocks are taken row block
+// by row block (the order of stripe_blk), `parts` workgroups per row block, each taking every
+// parts-th block of it; and since consecutive workgroups are dealt round-robin to the 8 XCDs,
+// each with its own L2, the workgroups of a row block are numbered so that all of them land on
+// one XCD: an XCD runs a few dozen workgroups at a time, which then share the lines of one or a
+// few row blocks.
+struct StripeWalk {
+    int32_t k, k_end, step;  // entries k, k + step, ... below k_end of stripe_blk
+};
+
+__device__ __forceinline__ StripeWalk stripe_walk(const int32_t *__restrict__ stripe_ptr, int32_t NBR, int32_t parts)
+{
+    const int32_t q = (int32_t)(blockIdx.x >> 3), x = (int32_t)(blockIdx.x & 7u);
+    const int32_t octet = q / parts, p = q % parts;
+    // Which of the octet's eight row blocks goes to XCD x: x xor-ed with every 3-bit field of the
+    // octet's number, a bijection inside the octet.  (With bm mod 8 itself a matrix whose density
+    // follows the bits of the row index, as R-MAT's does, put 44 % of the work on one XCD.)
+    int32_t fold = 0;
+    for (int32_t t = octet; t; t >>= 3) fold ^= t & 7;
+    const int32_t bm = octet * 8 + (x ^ fold);
+    if (bm >= NBR) return {0, 0, 1};
+    return {stripe_ptr[bm] + p, stripe_ptr[bm + 1], parts};
+}
+
 // One workgroup per non-empty block: order its slots by (key, local row) with a bitonic
 // network in LDS, then write the slot arrays and the nonzero count of each group.
 __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict__ bucket_key, const uint32_t *__restrict__ bucket_seg,
@@ -701,20 +728,16 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
 
 // ------------------------------------------------------------------ step 7: fill
 
-// One wavefront per group.  Round k stores the k-th nonzero of every lane that still has
-// one, lanes in slot order; rows keep their CSR (ascending column) order.
+// One group, one wavefront.  Round k stores the k-th nonzero of every lane that still has one,
+// lanes in slot order; rows keep their CSR (ascending column) order.  col0 is the first column of
+// the group's block column.
 template <typename T>
-__global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_col, const T *__restrict__ csr_val,
-                                              const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
-                                              const int32_t *__restrict__ group_blk, const int32_t *__restrict__ blk_bn,
-                                              const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
-                                              int32_t G, int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
+__device__ __forceinline__ void fill_group(int32_t g, int32_t col0, int lane, const int32_t *__restrict__ csr_col,
+                                           const T *__restrict__ csr_val, const int32_t *__restrict__ group_ptr,
+                                           const int32_t *__restrict__ group_slot, const uint16_t *__restrict__ seg_len,
+                                           const int32_t *__restrict__ slot_j, uint16_t *__restrict__ col_local, T *__restrict__ data)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (g >= G) return;
     const int s0 = group_slot[g], cnt = group_slot[g + 1] - s0;
-    const int32_t col0 = blk_bn[group_blk[g]] * C;
     const int n = lane < cnt ? seg_len[s0 + lane] : 0;
     const int64_t j = lane < cnt ? slot_j[s0 + lane] : 0;
     int64_t base = group_ptr[g];
@@ -775,6 +798,41 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ csr_co
             base += __popcll(live);
         }
     }
+}
+
+// Workgroups take blocks as stripe_walk says, the wavefronts of one taking a block's groups in turn.
+template <typename T>
+__global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ stripe_ptr, const int32_t *__restrict__ stripe_blk,
+                                              int32_t NBR, int32_t B, int32_t parts,
+                                              const int32_t *__restrict__ csr_col, const T *__restrict__ csr_val,
+                                              const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
+                                              const int32_t *__restrict__ blk_group_ptr, const int32_t *__restrict__ blk_bn,
+                                              const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
+                                              int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
+{
+    const int lane = threadIdx.x & 63;
+    const StripeWalk walk = stripe_walk(stripe_ptr, NBR, parts);
+    for (int32_t entry = walk.k; entry < walk.k_end; entry += walk.step) {
+        const int32_t b = stripe_blk[entry];
+        const int32_t col0 = blk_bn[b] * C;
+        const int32_t g_end = blk_group_ptr[b + 1];
+        for (int32_t g = blk_group_ptr[b] + (int32_t)(threadIdx.x >> 6); g < g_end; g += 4)
+            fill_group<T>(g, col0, lane, csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j, col_local, data);
+    }
+}
+
+// The same with one wavefront per group, in the layout's own order.
+template <typename T>
+__global__ __launch_bounds__(256) void k_fill_flat(const int32_t *__restrict__ csr_col, const T *__restrict__ csr_val,
+                                                   const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
+                                                   const int32_t *__restrict__ group_blk, const int32_t *__restrict__ blk_bn,
+                                                   const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
+                                                   int32_t G, int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
+{
+    const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= G) return;
+    fill_group<T>((int32_t)g, blk_bn[group_blk[g]] * C, (int)(threadIdx.x & 63), csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j,
+                  col_local, data);
 }
 
 // add_sign derived from seg_len (Section 3.2: distance to the row's next nonzero = nonzeros
@@ -1336,6 +1394,16 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
     while (n2 < R) n2 <<= 1;
     const size_t order_lds = sizeof(uint64_t) * (size_t)n2;
     HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    // The order in which k_fill takes the blocks (see stripe_walk).  Row block by
+    // row block pays where a row segment is a small part of the 128-byte lines it is gathered from
+    // (fewer than 4 nonzeros on average) and the blocks are large enough to keep a workgroup busy
+    // (256 slots on average); measured: k_fill 2.30 -> 1.10 ms on the 4M x 1M matrix with 2 nonzeros
+    // per segment, 0.79 -> 0.37 ms on the 2^20 one with 1.6; with 13 nonzeros per segment (27-point
+    // stencil) or 86 slots per block (R-MAT, whose dense row blocks then also wait for a few
+    // workgroups) it is slower than the layout's own order with a wavefront per group.
+    const bool by_row_block = NBR >= 64 && nnz < 4 * S && S >= 256 * B;
+    const int32_t parts = !by_row_block ? 0 : (int32_t)std::min<int64_t>(32, std::max<int64_t>(1, (B + NBR - 1) / NBR));
+    const dim3 stripe_grid((unsigned)(8 * ((NBR + 7) / 8) * std::max(parts, 1)));
     k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
                                                             h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
                                                             group_blk, (uint32_t)long_rounds_of(h->heavy_rounds), longest_all,
@@ -1347,14 +1415,24 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
     // the padding behind the last group is read (and its products dropped) by lanes without an element
     HBP_HIP(hipMemsetAsync(h->col_local + nnz, 0, 256 * sizeof(uint16_t), st));
     HBP_HIP(hipMemsetAsync((char *)h->data + (size_t)nnz * h->value_bytes, 0, 256 * (size_t)h->value_bytes, st));
-    if (h->value_bytes == 8)
-        k_fill<double><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const double *>(csr_val), h->group_ptr, h->group_slot,
-                                                         group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
-                                                         static_cast<double *>(h->data));
-    else
-        k_fill<float><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const float *>(csr_val), h->group_ptr, h->group_slot,
-                                                        group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
-                                                        static_cast<float *>(h->data));
+    if (parts == 0) {
+        if (h->value_bytes == 8)
+            k_fill_flat<double><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const double *>(csr_val), h->group_ptr, h->group_slot,
+                                                                  group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                                  static_cast<double *>(h->data));
+        else
+            k_fill_flat<float><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const float *>(csr_val), h->group_ptr, h->group_slot,
+                                                                 group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                                 static_cast<float *>(h->data));
+    } else if (h->value_bytes == 8) {
+        k_fill<double><<<stripe_grid, 256, 0, st>>>(h->stripe_ptr, h->stripe_blk, (int32_t)NBR, (int32_t)B, parts, csr_col,
+                                                    static_cast<const double *>(csr_val), h->group_ptr, h->group_slot, h->blk_group_ptr,
+                                                    h->blk_bn, h->seg_len, slot_j, C, h->col_local, static_cast<double *>(h->data));
+    } else {
+        k_fill<float><<<stripe_grid, 256, 0, st>>>(h->stripe_ptr, h->stripe_blk, (int32_t)NBR, (int32_t)B, parts, csr_col,
+                                                   static_cast<const float *>(csr_val), h->group_ptr, h->group_slot, h->blk_group_ptr,
+                                                   h->blk_bn, h->seg_len, slot_j, C, h->col_local, static_cast<float *>(h->data));
+    }
     HBP_HIP(hipGetLastError());
     uint32_t n_units = 0, n_multi = 0, longest = 0;
     HBP_HIP(hipMemcpyAsync(&longest, longest_all, 4, hipMemcpyDeviceToHost, st));
