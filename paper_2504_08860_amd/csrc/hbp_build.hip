@@ -552,24 +552,20 @@ __global__ __launch_bounds__(256) void k_count_blocks(const int32_t *__restrict_
     }
 }
 
-// Bucketed scatter: (key << 16 | local row, segment id) into the block's slot range.  The order
-// in which the segments of a block arrive is arbitrary (k_order_block sorts them).
+// Bucketed scatter: (length << 16 | local row, first nonzero) of every segment into its block's
+// slot range.  The order in which the segments of a block arrive is arbitrary (k_order_block
+// computes the keys and sorts them).
 __global__ __launch_bounds__(256) void k_bucket(const int32_t *__restrict__ seg_j, const int32_t *__restrict__ seg_row,
                                                 const int32_t *__restrict__ seg_bn, int64_t S, int32_t R, int32_t NBR, int32_t NBC,
-                                                const int32_t *__restrict__ a_ptr, int32_t reorder, uint32_t *__restrict__ cursor,
-                                                uint32_t *__restrict__ bucket_key, uint32_t *__restrict__ bucket_seg)
+                                                uint32_t *__restrict__ cursor, uint32_t *__restrict__ bucket_len_row, int32_t *__restrict__ bucket_j)
 {
     __shared__ uint32_t cnt[kTileCounters];  // per counter of the tile: segments seen, then their first position
     const Tile t = tile_of(seg_row, S, R, NBC);
     if (t.base >= t.S) return;
-    const uint32_t R_u = (uint32_t)R, b = R_u / 9u ? R_u / 9u : 1u, a = (uint32_t)*a_ptr;
     auto emit = [&](int64_t s, int32_t row, uint32_t pos) {
-        const uint32_t n = (uint32_t)(seg_j[s + 1] - seg_j[s]);
-        // reorder 0: no key (plain 2D partition), 1: the hash, 2: the length itself (n <= C < 65536),
-        // 3: the length for now (k_order_block hashes it with the block's own shift)
-        const uint32_t key = reorder == 1 ? hash_key(n, a, b, R_u) : reorder >= 2 ? n : 0u;
-        bucket_key[pos] = (key << 16) | (uint32_t)(row % R);
-        bucket_seg[pos] = (uint32_t)s;
+        const int32_t j0 = seg_j[s];
+        bucket_len_row[pos] = ((uint32_t)(seg_j[s + 1] - j0) << 16) | (uint32_t)(row % R);  // length <= C <= 32768
+        bucket_j[pos] = j0;
     };
     if (t.span == 0) {
         for (int i = 0; i < kTileSegs / 256; i++) {
@@ -636,35 +632,79 @@ __device__ __forceinline__ StripeWalk stripe_walk(const int32_t *__restrict__ st
     return {stripe_ptr[bm] + p, stripe_ptr[bm + 1], parts};
 }
 
-// One workgroup per non-empty block: order its slots by (key, local row) with a bitonic
-// network in LDS, then write the slot arrays and the nonzero count of each group.
-__global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict__ bucket_key, const uint32_t *__restrict__ bucket_seg,
-                                                     const int32_t *__restrict__ seg_j, const int32_t *__restrict__ slot_ptr,
-                                                     const int32_t *__restrict__ blk_group_ptr, int32_t W,
-                                                     uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
+// Exclusive prefix sums of a[0 .. n) in LDS, in place, by the 256 threads of a workgroup.
+// sh_wave: four words of LDS.  Ends with a barrier.
+__device__ __forceinline__ void scan_in_lds(uint32_t *a, int n, uint32_t *sh_wave)
+{
+    const int chunk = (n + 255) / 256, lo = min(n, (int)threadIdx.x * chunk), hi = min(n, lo + chunk);
+    uint32_t sum = 0;
+    for (int i = lo; i < hi; i++) sum += a[i];
+    uint32_t incl = sum;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) sh_wave[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    uint32_t run = incl - sum;
+    for (int w = 0; w < (int)(threadIdx.x >> 6); w++) run += sh_wave[w];
+    for (int i = lo; i < hi; i++) {
+        const uint32_t t = a[i];
+        a[i] = run;
+        run += t;
+    }
+    __syncthreads();
+}
+
+// One workgroup per non-empty block: compute the keys of its segments, order its slots by (key,
+// local row), then write the slot arrays and the nonzero count of each group.
+// reorder 0: no key (plain 2D partition), 1: the hash with the matrix's shift, 2: the length
+// itself, 3: the hash with a shift of the block's own (Section 3.2: denser blocks call for a
+// larger a; a = smallest shift for which at least 15/16 of the block's rows aggregate into 0..8).
+// Blocks of more than kSmallBlock slots: the local rows of a block are distinct, so the order by
+// row costs nothing: entry (key << 16 | position in the block's bucket) is stored at index `row`
+// of an LDS array, which leaves holes for the rows without a segment.  Stable counting passes
+// over 4 bits of the key at a time, lowest first, then put the entries in key order and keep the
+// row order inside a key; the first pass also closes the holes.  In a pass a wavefront takes 64
+// consecutive entries at a time; the lanes that hold the same digit find each other with four
+// ballots, which gives an entry its rank among them and the tile its count per digit; a prefix
+// sum over (digit, tile) turns the counts into positions.  As many passes as the block's largest
+// key has hex digits.  Smaller blocks (the passes would still walk all R rows): a bitonic network
+// over (key, row, length, position) words.
+__global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict__ bucket_len_row, const int32_t *__restrict__ bucket_j,
+                                                     const int32_t *__restrict__ slot_ptr, const int32_t *__restrict__ blk_group_ptr,
+                                                     int32_t W, uint16_t *__restrict__ row_local, uint16_t *__restrict__ seg_len,
                                                      int32_t *__restrict__ slot_j, uint32_t *__restrict__ group_nnz, uint32_t *__restrict__ group_longest,
                                                      int32_t *__restrict__ group_slot, int32_t *__restrict__ group_blk, uint32_t heavy_rounds,
-                                                     uint32_t *__restrict__ longest_all, int32_t block_shift, uint32_t R,
+                                                     uint32_t *__restrict__ longest_all, int32_t reorder, uint32_t R,
                                                      const int32_t *__restrict__ a_ptr, int32_t *__restrict__ blk_shift,
                                                      uint32_t *__restrict__ slot_key)
 {
-    extern __shared__ uint64_t keys[];
+    extern __shared__ __align__(8) uint32_t order_lds[];  // two arrays of cap entries, then 16 counters per tile of 64
     __shared__ uint32_t sh_hist[14];
     __shared__ int32_t sh_shift;
+    __shared__ uint32_t sh_max_key, sh_wave[4];
+    constexpr uint32_t kHole = 0xffffffffu;
+    constexpr int kSmallBlock = 256;  // slots: one entry per thread
+    const int cap = (int)((R + 63u) & ~63u);
+    uint32_t *from = order_lds, *to = order_lds + cap, *cnt = order_lds + 2 * cap;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int b = blockIdx.x;
     const int s0 = slot_ptr[b], m = slot_ptr[b + 1] - s0;
-    int n2 = 1;
-    while (n2 < m) n2 <<= 1;
-    for (int i = threadIdx.x; i < n2; i += 256)
-        keys[i] = i < m ? ((uint64_t)bucket_key[s0 + i] << 32) | bucket_seg[s0 + i] : ~0ull;
-    if (block_shift) {
-        // One shift per block (Section 3.2: denser blocks call for a larger a): the entries carry the
-        // rows' lengths; a = smallest shift for which at least 15/16 of the block's rows aggregate
-        // into 0..8; then the lengths are replaced by their keys.
-        if (threadIdx.x < 14) sh_hist[threadIdx.x] = 0u;
-        __syncthreads();
+    const bool small = m <= kSmallBlock;
+    if (!small)
+        for (int i = threadIdx.x; i < cap; i += 256) from[i] = kHole;
+    if (threadIdx.x < 14) sh_hist[threadIdx.x] = 0u;
+    if (threadIdx.x == 0) {
+        sh_max_key = 0u;
+        sh_shift = *a_ptr;
+    }
+    __syncthreads();
+    if (reorder == 3) {
         for (int i = threadIdx.x; i < m; i += 256) {
-            const uint32_t n = (uint32_t)(keys[i] >> 48);
+            const uint32_t n = bucket_len_row[s0 + i] >> 16;
             int a = 0;
             while (a < 13 && n >= (9u << a)) a++;
             atomicAdd(&sh_hist[a], 1u);
@@ -680,34 +720,107 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
             sh_shift = a;
         }
         __syncthreads();
-        const uint32_t a = (uint32_t)sh_shift, band = R / 9u ? R / 9u : 1u;
-        for (int i = threadIdx.x; i < m; i += 256) {
-            const uint64_t e = keys[i];
-            keys[i] = ((uint64_t)hash_key((uint32_t)(e >> 48), a, band, R) << 48) | (e & 0xffffffffffffull);
-        }
     }
-    if (threadIdx.x == 0) blk_shift[b] = block_shift ? sh_shift : *a_ptr;
-    __syncthreads();
-    for (int k = 2; k <= n2; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < n2 / 2; t += 256) {  // pair t: i has bit j clear, its partner has it set
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), p = i | j;
-                const uint64_t x = keys[i], y = keys[p];
-                if ((x > y) == ((i & k) == 0)) { keys[i] = y; keys[p] = x; }
+    const uint32_t shift_a = (uint32_t)sh_shift, band = R / 9u ? R / 9u : 1u;
+    auto key_of = [&](uint32_t n) __attribute__((always_inline)) {
+        return reorder == 0 ? 0u : reorder == 2 ? n : hash_key(n, shift_a, band, R);
+    };
+    if (threadIdx.x == 0) blk_shift[b] = (int32_t)shift_a;
+    if (small) {
+        uint64_t *wide = reinterpret_cast<uint64_t *>(order_lds);  // 2 cap words: room for cap >= m entries
+        int n2 = 1;
+        while (n2 < m) n2 <<= 1;
+        for (int i = threadIdx.x; i < n2; i += 256) {
+            uint64_t e = ~0ull;
+            if (i < m) {
+                const uint32_t lr = bucket_len_row[s0 + i];
+                e = ((uint64_t)key_of(lr >> 16) << 48) | ((uint64_t)(lr & 0xffffu) << 32) | (lr & 0xffff0000u) | (uint32_t)i;
+            }
+            wide[i] = e;
+        }
+        __syncthreads();
+        for (int k = 2; k <= n2; k <<= 1)
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int t = threadIdx.x; t < n2 / 2; t += 256) {  // pair t: i has bit j clear, its partner has it set
+                    const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), p = i | j;
+                    const uint64_t x = wide[i], y = wide[p];
+                    if ((x > y) == ((i & k) == 0)) { wide[i] = y; wide[p] = x; }
+                }
+                __syncthreads();
+            }
+        const int i = threadIdx.x;  // m <= 256: one entry per thread
+        uint64_t e = 0;
+        if (i < m) e = wide[i];
+        __syncthreads();  // `to` may overlap `wide`
+        if (i < m) {
+            const uint32_t n = (uint32_t)(e >> 16) & 0xffffu;
+            row_local[s0 + i] = (uint16_t)((e >> 32) & 0xffffu);
+            seg_len[s0 + i] = (uint16_t)n;
+            if (slot_key) slot_key[s0 + i] = (uint32_t)(e >> 48);
+            slot_j[s0 + i] = bucket_j[s0 + (int32_t)(e & 0xffffu)];  // a gather inside the block's own range
+            to[i] = n;
+        }
+    } else {
+        uint32_t most = 0;
+        for (int i = threadIdx.x; i < m; i += 256) {
+            const uint32_t lr = bucket_len_row[s0 + i];
+            const uint32_t key = key_of(lr >> 16);
+            from[lr & 0xffffu] = (key << 16) | (uint32_t)i;
+            most = max(most, key);
+        }
+        if (most) atomicMax(&sh_max_key, most);
+        __syncthreads();
+        const uint32_t max_key = sh_max_key;
+        const int passes = max_key ? (35 - __clz(max_key)) / 4 : 1;  // hex digits of the largest key; one pass at least: it closes the holes
+        int len = cap;  // entries of `from` (with holes in the first pass)
+        for (int pass = 0; pass < passes; pass++) {
+            const int tiles = (len + 63) / 64, shift = 16 + 4 * pass;
+            for (int i = threadIdx.x; i < 16 * tiles; i += 256) cnt[i] = 0u;
+            __syncthreads();
+            // the lanes of a tile with the same digit as this lane (its rank among them: the lanes below it)
+            auto classify = [&](int tile, uint32_t &e, uint32_t &digit, uint64_t &same) __attribute__((always_inline)) {
+                const int i = tile * 64 + lane;
+                e = i < len ? from[i] : kHole;
+                const bool valid = e != kHole;
+                digit = (e >> shift) & 15u;
+                same = __ballot(valid);
+#pragma unroll
+                for (int bit = 0; bit < 4; bit++) {
+                    const bool set = (digit >> bit) & 1u;
+                    const uint64_t with = __ballot(valid && set);
+                    same &= set ? with : ~with;
+                }
+                return valid;
+            };
+            for (int tile = wave; tile < tiles; tile += 4) {
+                uint32_t e, digit;
+                uint64_t same;
+                const bool valid = classify(tile, e, digit, same);
+                if (valid && lanes_below(same) == 0) cnt[digit * tiles + tile] = (uint32_t)__popcll(same);
             }
             __syncthreads();
+            scan_in_lds(cnt, 16 * tiles, sh_wave);
+            for (int tile = wave; tile < tiles; tile += 4) {
+                uint32_t e, digit;
+                uint64_t same;
+                const bool valid = classify(tile, e, digit, same);
+                if (valid) to[cnt[digit * tiles + tile] + (uint32_t)lanes_below(same)] = e;
+            }
+            __syncthreads();
+            uint32_t *t = from; from = to; to = t;
+            len = m;
         }
-    for (int i = threadIdx.x; i < m; i += 256) {
-        const uint64_t e = keys[i];
-        const uint32_t seg = (uint32_t)e;
-        int32_t ends[2];  // seg_j[seg], seg_j[seg + 1] in one (unaligned) 8-byte load: a gather per slot
-        __builtin_memcpy(ends, seg_j + seg, sizeof ends);
-        const int32_t j0 = ends[0], n = ends[1] - j0;
-        row_local[s0 + i] = (uint16_t)((e >> 32) & 0xffffu);
-        seg_len[s0 + i] = (uint16_t)n;
-        if (slot_key) slot_key[s0 + i] = (uint32_t)(e >> 48);
-        slot_j[s0 + i] = j0;
-        keys[i] = (uint64_t)n;  // only this thread touches entry i in this phase
+        // `from` holds the m entries in (key, local row) order; `to` is free: the lengths go there
+        for (int i = threadIdx.x; i < m; i += 256) {
+            const uint32_t e = from[i];
+            const int32_t at = s0 + (int32_t)(e & 0xffffu);  // the segment's place in the block's bucket (gathers inside the block's own range)
+            const uint32_t lr = bucket_len_row[at];
+            row_local[s0 + i] = (uint16_t)(lr & 0xffffu);
+            seg_len[s0 + i] = (uint16_t)(lr >> 16);
+            if (slot_key) slot_key[s0 + i] = e >> 16;
+            slot_j[s0 + i] = bucket_j[at];
+            to[i] = lr >> 16;
+        }
     }
     __syncthreads();
     const int g0 = blk_group_ptr[b], ng = (m + W - 1) / W;
@@ -715,8 +828,8 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
         uint32_t sum = 0, longest = 0;
         const int e1 = min(m, (gi + 1) * W);
         for (int i = gi * W; i < e1; i++) {
-            sum += (uint32_t)keys[i];
-            longest = max(longest, (uint32_t)keys[i]);
+            sum += to[i];
+            longest = max(longest, to[i]);
         }
         group_nnz[g0 + gi] = sum;
         group_longest[g0 + gi] = longest;
@@ -1364,9 +1477,10 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
     Arena tmp2(false, h->device, 1);
     uint32_t *stripe_cum, *unit_cnt, *multi_idx;
     tmp2.reserve(&stripe_cum, B + 1); tmp2.reserve(&unit_cnt, NBR + 1); tmp2.reserve(&multi_idx, NBR + 1);
-    uint32_t *bucket_key, *bucket_seg, *group_nnz, *group_longest, *longest_all;
+    uint32_t *bucket_len_row, *group_nnz, *group_longest, *longest_all;
+    int32_t *bucket_j;
     int32_t *slot_j, *group_blk;
-    tmp2.reserve(&bucket_key, S); tmp2.reserve(&bucket_seg, S);
+    tmp2.reserve(&bucket_len_row, S); tmp2.reserve(&bucket_j, S);
     tmp2.reserve(&slot_j, S); tmp2.reserve(&group_nnz, G + 1); tmp2.reserve(&group_longest, G + 1); tmp2.reserve(&longest_all, 1); tmp2.reserve(&group_blk, G + 1);
     HBP_TRY(tmp2.commit());
     HBP_HIP(hipMemsetAsync(longest_all, 0, sizeof(uint32_t), st));
@@ -1387,13 +1501,8 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
                                                      h->unit_stripe, h->unit_k, h->multi_stripes);
     // steps 5-6 (slot_off doubles as the per-block cursor from here on)
     const int32_t reorder = (p.flags & HBP_FLAG_NO_REORDER) ? 0 : (p.flags & HBP_FLAG_KEY_LENGTH) ? 2 : (p.flags & HBP_FLAG_BLOCK_SHIFT) ? 3 : 1;
-    k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, d_a,
-                                                       reorder, slot_off,
-                                                       bucket_key, bucket_seg);
-    int n2 = 2;
-    while (n2 < R) n2 <<= 1;
-    const size_t order_lds = sizeof(uint64_t) * (size_t)n2;
-    HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    k_bucket<<<blocks_for(S, kTileSegs), 256, 0, st>>>(seg_j, seg_row, seg_bn, S, R, (int32_t)NBR, (int32_t)NBC, slot_off,
+                                                       bucket_len_row, bucket_j);
     // The order in which k_fill takes the blocks (see stripe_walk).  Row block by
     // row block pays where a row segment is a small part of the 128-byte lines it is gathered from
     // (fewer than 4 nonzeros on average) and the blocks are large enough to keep a workgroup busy
@@ -1404,10 +1513,16 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
     const bool by_row_block = NBR >= 64 && nnz < 4 * S && S >= 256 * B;
     const int32_t parts = !by_row_block ? 0 : (int32_t)std::min<int64_t>(32, std::max<int64_t>(1, (B + NBR - 1) / NBR));
     const dim3 stripe_grid((unsigned)(8 * ((NBR + 7) / 8) * std::max(parts, 1)));
-    k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_key, bucket_seg, seg_j, h->slot_ptr, h->blk_group_ptr, W,
+    const size_t order_cap = ((size_t)R + 63) & ~(size_t)63;
+    size_t small_n2 = 1;  // the bitonic network of a small block: 8-byte words, the next power of two above min(R, 256) slots
+    while (small_n2 < (size_t)std::min(R, 256)) small_n2 <<= 1;
+    const size_t order_lds = std::max(sizeof(uint32_t) * (2 * order_cap + 16 * (order_cap / 64)),  // two entry arrays, 16 counters per tile
+                                      sizeof(uint64_t) * small_n2);
+    HBP_HIP(hipFuncSetAttribute((const void *)k_order_block, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    k_order_block<<<dim3((unsigned)B), 256, order_lds, st>>>(bucket_len_row, bucket_j, h->slot_ptr, h->blk_group_ptr, W,
                                                             h->row_local, h->seg_len, slot_j, group_nnz, group_longest, h->group_slot,
                                                             group_blk, (uint32_t)long_rounds_of(h->heavy_rounds), longest_all,
-                                                            reorder == 3 ? 1 : 0, (uint32_t)R, d_a, h->blk_shift, h->slot_key);
+                                                            reorder, (uint32_t)R, d_a, h->blk_shift, h->slot_key);
     HBP_TRY(exclusive_scan<kOpIdentity>(group_nnz, (uint32_t *)h->group_ptr, G, 1, scan_tmp, st));
     HBP_TRY(exclusive_scan<kOpIdentity>(group_longest, (uint32_t *)h->group_rounds, G, 1, scan_tmp, st));
     k_set_i32<<<1, 64, 0, st>>>(h->group_slot + G, (int32_t)S);
