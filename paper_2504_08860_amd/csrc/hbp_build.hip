@@ -823,19 +823,23 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
         }
     }
     __syncthreads();
+    // a wavefront per group (W <= 64 slots): nonzeros and longest row by a reduction over the lanes
     const int g0 = blk_group_ptr[b], ng = (m + W - 1) / W;
-    for (int gi = threadIdx.x; gi < ng; gi += 256) {
-        uint32_t sum = 0, longest = 0;
-        const int e1 = min(m, (gi + 1) * W);
-        for (int i = gi * W; i < e1; i++) {
-            sum += to[i];
-            longest = max(longest, to[i]);
+    for (int gi = wave; gi < ng; gi += 4) {
+        const int i = gi * W + lane;
+        uint32_t sum = lane < W && i < m ? to[i] : 0u, longest = sum;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            sum += __shfl_xor(sum, d);
+            longest = max(longest, __shfl_xor(longest, d));
         }
-        group_nnz[g0 + gi] = sum;
-        group_longest[g0 + gi] = longest;
-        if (longest > heavy_rounds) atomicMax(longest_all, longest);  // only that long rows matter to the caller
-        group_slot[g0 + gi] = s0 + gi * W;
-        group_blk[g0 + gi] = b;
+        if (lane == 0) {
+            group_nnz[g0 + gi] = sum;
+            group_longest[g0 + gi] = longest;
+            if (longest > heavy_rounds) atomicMax(longest_all, longest);  // only that long rows matter to the caller
+            group_slot[g0 + gi] = s0 + gi * W;
+            group_blk[g0 + gi] = b;
+        }
     }
 }
 
