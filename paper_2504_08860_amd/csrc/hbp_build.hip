@@ -849,7 +849,7 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
 // lanes in slot order; rows keep their CSR (ascending column) order.  col0 is the first column of
 // the group's block column.
 template <typename T>
-__device__ __forceinline__ void fill_group(int32_t g, int32_t col0, int lane, const int32_t *__restrict__ csr_col,
+__device__ __forceinline__ void fill_group(int32_t g, int32_t col0, int lane, int64_t nnz, const int32_t *__restrict__ csr_col,
                                            const T *__restrict__ csr_val, const int32_t *__restrict__ group_ptr,
                                            const int32_t *__restrict__ group_slot, const uint16_t *__restrict__ seg_len,
                                            const int32_t *__restrict__ slot_j, uint16_t *__restrict__ col_local, T *__restrict__ data)
@@ -894,13 +894,28 @@ __device__ __forceinline__ void fill_group(int32_t g, int32_t col0, int lane, co
             __builtin_memcpy(c, csr_col + j + k, sizeof c);
             __builtin_memcpy(v, csr_val + j + k, sizeof v);
         } else {
+            // The end of a row: its elements are read four at a time all the same, as long as the
+            // four lie inside the arrays (what is read past the row's end is not stored).  Lanes
+            // read different rows: an instruction costs a line per lane whatever its width.
 #pragma unroll
             for (int u = 0; u < kRounds; u++) {
                 c[u] = 0;
                 v[u] = T(0);
-                if (k + u < n) {
-                    c[u] = csr_col[j + k + u];
-                    v[u] = csr_val[j + k + u];
+            }
+#pragma unroll
+            for (int q = 0; q < kRounds; q += 4) {
+                if (k + q < n) {
+                    if (j + k + q + 4 <= nnz) {
+                        __builtin_memcpy(c + q, csr_col + j + k + q, 4 * sizeof(int32_t));
+                        __builtin_memcpy(v + q, csr_val + j + k + q, 4 * sizeof(T));
+                    } else {
+#pragma unroll
+                        for (int u = q; u < q + 4; u++)
+                            if (k + u < n) {
+                                c[u] = csr_col[j + k + u];
+                                v[u] = csr_val[j + k + u];
+                            }
+                    }
                 }
             }
         }
@@ -925,7 +940,7 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ stripe
                                               const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
                                               const int32_t *__restrict__ blk_group_ptr, const int32_t *__restrict__ blk_bn,
                                               const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
-                                              int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
+                                              int32_t C, int64_t nnz, uint16_t *__restrict__ col_local, T *__restrict__ data)
 {
     const int lane = threadIdx.x & 63;
     const StripeWalk walk = stripe_walk(stripe_ptr, NBR, parts);
@@ -934,7 +949,7 @@ __global__ __launch_bounds__(256) void k_fill(const int32_t *__restrict__ stripe
         const int32_t col0 = blk_bn[b] * C;
         const int32_t g_end = blk_group_ptr[b + 1];
         for (int32_t g = blk_group_ptr[b] + (int32_t)(threadIdx.x >> 6); g < g_end; g += 4)
-            fill_group<T>(g, col0, lane, csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j, col_local, data);
+            fill_group<T>(g, col0, lane, nnz, csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j, col_local, data);
     }
 }
 
@@ -944,11 +959,11 @@ __global__ __launch_bounds__(256) void k_fill_flat(const int32_t *__restrict__ c
                                                    const int32_t *__restrict__ group_ptr, const int32_t *__restrict__ group_slot,
                                                    const int32_t *__restrict__ group_blk, const int32_t *__restrict__ blk_bn,
                                                    const uint16_t *__restrict__ seg_len, const int32_t *__restrict__ slot_j,
-                                                   int32_t G, int32_t C, uint16_t *__restrict__ col_local, T *__restrict__ data)
+                                                   int32_t G, int32_t C, int64_t nnz, uint16_t *__restrict__ col_local, T *__restrict__ data)
 {
     const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= G) return;
-    fill_group<T>((int32_t)g, blk_bn[group_blk[g]] * C, (int)(threadIdx.x & 63), csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j,
+    fill_group<T>((int32_t)g, blk_bn[group_blk[g]] * C, (int)(threadIdx.x & 63), nnz, csr_col, csr_val, group_ptr, group_slot, seg_len, slot_j,
                   col_local, data);
 }
 
@@ -1537,20 +1552,20 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
     if (parts == 0) {
         if (h->value_bytes == 8)
             k_fill_flat<double><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const double *>(csr_val), h->group_ptr, h->group_slot,
-                                                                  group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                                  group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, nnz, h->col_local,
                                                                   static_cast<double *>(h->data));
         else
             k_fill_flat<float><<<blocks_for(G, 4), 256, 0, st>>>(csr_col, static_cast<const float *>(csr_val), h->group_ptr, h->group_slot,
-                                                                 group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, h->col_local,
+                                                                 group_blk, h->blk_bn, h->seg_len, slot_j, (int32_t)G, C, nnz, h->col_local,
                                                                  static_cast<float *>(h->data));
     } else if (h->value_bytes == 8) {
         k_fill<double><<<stripe_grid, 256, 0, st>>>(h->stripe_ptr, h->stripe_blk, (int32_t)NBR, (int32_t)B, parts, csr_col,
                                                     static_cast<const double *>(csr_val), h->group_ptr, h->group_slot, h->blk_group_ptr,
-                                                    h->blk_bn, h->seg_len, slot_j, C, h->col_local, static_cast<double *>(h->data));
+                                                    h->blk_bn, h->seg_len, slot_j, C, nnz, h->col_local, static_cast<double *>(h->data));
     } else {
         k_fill<float><<<stripe_grid, 256, 0, st>>>(h->stripe_ptr, h->stripe_blk, (int32_t)NBR, (int32_t)B, parts, csr_col,
                                                    static_cast<const float *>(csr_val), h->group_ptr, h->group_slot, h->blk_group_ptr,
-                                                   h->blk_bn, h->seg_len, slot_j, C, h->col_local, static_cast<float *>(h->data));
+                                                   h->blk_bn, h->seg_len, slot_j, C, nnz, h->col_local, static_cast<float *>(h->data));
     }
     HBP_HIP(hipGetLastError());
     uint32_t n_units = 0, n_multi = 0, longest = 0;
