@@ -326,6 +326,31 @@ def _with_long_rows(m, rng):
     return CsrMatrix(m.name + "+long", m.n_rows, m.n_cols, ptr, col, rng.standard_normal(len(col)).astype(np.float32), m.x)
 
 
+@pytest.mark.parametrize("R", [65, 129, 130, 257, 300, 1000, 4097, 8192])
+@pytest.mark.parametrize("mode", ["hash", "no_reorder", "key_length", "block_shift"])
+def test_block_ordering_paths(H, oracle, R, mode):
+    """Both ways a block's slots are ordered (a bitonic network up to 256 slots, counting passes
+    through a row table above), with R off the multiples of 64 and of the powers of two, and
+    blocks from nearly empty to full: one dense and one sparse column block side by side."""
+    rng = np.random.default_rng(R)
+    n_rows, n_cols = 2 * R + 17, 600
+    lens = np.where(rng.random(n_rows) < 0.9, rng.integers(1, 40, n_rows), 0)
+    lens[rng.integers(0, n_rows, 5)] = 500
+    cols = []
+    for n in lens:
+        dense = np.sort(rng.choice(512, min(int(n), 512), replace=False))
+        extra = 512 + np.sort(rng.choice(88, 1, replace=False)) if rng.random() < 0.05 else np.empty(0, np.int64)
+        cols.append(np.r_[dense, extra])
+    ptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum([len(c) for c in cols], out=ptr[1:])
+    col = np.concatenate(cols).astype(np.int32)
+    from workloads import CsrMatrix
+    m = CsrMatrix(name=f"ordering_{R}", n_rows=n_rows, n_cols=n_cols, ptr=ptr, col=col,
+                  val=rng.standard_normal(len(col)).astype(np.float32), x=rng.uniform(-1, 1, n_cols).astype(np.float32))
+    kw = {} if mode == "hash" else {mode: True}
+    check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=512, **kw)
+
+
 @pytest.mark.parametrize("R,C", [(64, 128), (512, 4096)])
 def test_plain_2d_partition(H, oracle, R, C):
     """HBP_FLAG_NO_REORDER: the plain 2D-partitioning method of Section 4 (no hash reorder)."""
