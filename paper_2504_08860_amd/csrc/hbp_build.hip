@@ -1195,12 +1195,14 @@ __global__ __launch_bounds__(256) void k_hash_keys(const uint32_t *__restrict__ 
 // Scratch memory of the build, kept between builds: freeing a few hundred megabytes costs a
 // quarter of a millisecond per allocation, a good part of a build.  Two slots per device (a
 // build has two scratch arenas alive at a time), grown when a build needs more, given back by
-// hbp_release_workspace().  g_workspace_mutex is held for the whole of build_layout: builds on
-// one process are serialised.
+// hbp_release_workspace().  The device's lock is held for the whole of build_layout: the builds
+// of one process on one device are serialised; builds on different devices are not.
 constexpr int kWorkspaceDevices = 64, kWorkspaceSlots = 2;
 struct Workspace { void *base = nullptr; size_t bytes = 0; };
 Workspace g_workspace[kWorkspaceDevices][kWorkspaceSlots];
-std::mutex g_workspace_mutex;
+std::mutex g_workspace_mutex[kWorkspaceDevices];
+
+std::mutex &workspace_mutex(int device) { return g_workspace_mutex[device >= 0 && device < kWorkspaceDevices ? device : 0]; }
 
 int workspace_get(int device, int slot, size_t bytes, void **out)
 {
@@ -1289,9 +1291,9 @@ int choose_block_parameters(const int32_t *csr_ptr, const int32_t *csr_col, int6
     const bool need_stats = p.rows_per_block == 0 || p.rounds_per_batch == 0;
     if (!need_stats) return HBP_OK;
     if (p.cols_per_block < 1 || p.cols_per_block > max_c) return HBP_ERR_INVALID_ARGUMENT;
-    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
     int device = 0;
     HBP_HIP(hipGetDevice(&device));
+    std::lock_guard<std::mutex> workspace_lock(workspace_mutex(device));
     int32_t ends[2] = {0, 0};
     HBP_HIP(hipMemcpyAsync(&ends[0], csr_ptr, sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HBP_HIP(hipMemcpyAsync(&ends[1], csr_ptr + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -1330,7 +1332,7 @@ static int build_layout_locked(hbp_handle_s *h, const int32_t *csr_ptr, const in
 int build_layout(hbp_handle_s *h, const int32_t *csr_ptr, const int32_t *csr_col, const void *csr_val,
                  const hbp_params_t &p, hipStream_t st)
 {
-    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
+    std::lock_guard<std::mutex> workspace_lock(workspace_mutex(h->device));
     const int rc = build_layout_locked(h, csr_ptr, csr_col, csr_val, p, st);
     // A build that gives up may have kernels in flight that still use the shared workspace: they
     // have to finish before the lock is released and the next build takes the workspace over.
@@ -1607,14 +1609,15 @@ int build_schedule(hbp_handle_s *h, hipStream_t st)
 
 int release_workspace()
 {
-    std::lock_guard<std::mutex> workspace_lock(g_workspace_mutex);
     int rc = HBP_OK;
-    for (auto &dev : g_workspace)
-        for (auto &w : dev) {
+    for (int device = 0; device < kWorkspaceDevices; device++) {
+        std::lock_guard<std::mutex> workspace_lock(workspace_mutex(device));
+        for (auto &w : g_workspace[device]) {
             if (w.base && hipFree(w.base) != hipSuccess) rc = HBP_ERR_HIP;
             w.base = nullptr;
             w.bytes = 0;
         }
+    }
     return rc;
 }
 

@@ -28,6 +28,7 @@ def test_static_scratch_matches_hbp_spmv(oracle):
     # call finds the first one's partial sums and counters in the array
     cases = [(make_config(5, 0.02), dict(rows_per_block=512, cols_per_block=2048, fixed_fraction_q8=160, num_workers=48)),
              (random_csr(3000, 2500, 0.01, 5, empty_row_frac=0.2), dict(rows_per_block=64, cols_per_block=256, num_workers=7))]
+    first_call = True
     for m, params in cases:
         print(f"[no-alloc] {m.name} nnz={m.nnz} {params}", flush=True)
         ptr, col, val, x = _dev(m)
@@ -40,12 +41,18 @@ def test_static_scratch_matches_hbp_spmv(oracle):
             torch.cuda.synchronize()
             for rep in range(2):
                 y = torch.full((m.n_rows,), float("nan"), device="cuda")
-                before = torch.cuda.memory_allocated()
+                # free device memory as the driver sees it (tensors that Python drops meanwhile go back to
+                # torch's cache, not to the device, so only an allocation from the device would move it)
+                torch.cuda.synchronize()
+                free_before = torch.cuda.mem_get_info()[0]
                 rc = L.hbp_spmv_static_scratch(ctypes.c_void_p(h), ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(y.data_ptr()),
                                                ctypes.c_void_p(stream))
                 assert rc == 0, H.hbp_status_string(rc)
                 torch.cuda.synchronize()
-                assert torch.cuda.memory_allocated() == before
+                # (the process's very first call makes the runtime load the code object that holds the
+                # fixed array, which is when the device gives it its 32 MiB: not an allocation of the call)
+                assert first_call or torch.cuda.mem_get_info()[0] == free_before
+                first_call = False
                 assert torch.equal(y, y_ref), f"{m.name} rep {rep}"
             yo, s_abs = oracle.csr_spmv_f64(m.ptr, m.col, m.val, m.x)
             assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - yo) <= TOL * s_abs)
