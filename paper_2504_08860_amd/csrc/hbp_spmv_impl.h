@@ -429,7 +429,30 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
         int32_t e = 0, e1 = 0, e2 = 0;  // ends of the packs g, g1, g2: group g + q exists if it is below e
         int32_t g = draw_resolve(draw_issue(), e), g1 = draw_resolve(draw_issue(), e1), g2 = kNone;
         unsigned long long raw2 = draw_issue();
-        int32_t s0[GP], s1[GP], n[GP], s0n[GP], s1n[GP], done_slot[GP];
+        int32_t s0[GP], s1[GP], n[GP], done_slot[GP];
+        // The slot ranges and first positions of a pack's groups travel in one vector register per
+        // pack: lane l <= GP holds group_slot[first + l], lane 32 + l (l < GP) holds
+        // group_ptr[first + l], zero where the pack has no such group; they are read out into
+        // scalars where they are used.  (Loaded as scalars and carried three packs deep they did
+        // not fit the scalar registers: the spills cost some fifty instructions per pack and made
+        // the wavefront wait for each scalar load right where it was issued.)
+        auto load_meta = [&](int32_t first, int32_t end) __attribute__((always_inline)) {
+            uint32_t m = 0;
+            const int32_t l = lane & 31;
+            const bool position = lane >= 32;
+            if (first != kNone && l <= GP && l < end - first + (position ? 0 : 1))
+                m = (uint32_t)(position ? L.group_ptr : L.group_slot)[first + l];
+            return m;
+        };
+        auto meta_slots = [&](uint32_t m, int32_t first, int32_t end, int q, int32_t &from, int32_t &to) __attribute__((always_inline)) {
+            const bool there = in_pack(first, end, q);
+            from = there ? (int32_t)__builtin_amdgcn_readlane(m, q) : 0;
+            to = there ? (int32_t)__builtin_amdgcn_readlane(m, q + 1) : 0;
+        };
+        auto meta_base = [&](uint32_t m, int32_t first, int32_t end, int q) __attribute__((always_inline)) {
+            return in_pack(first, end, q) ? (uint32_t)__builtin_amdgcn_readlane(m, 32 + q) : 0u;
+        };
+        uint32_t meta = load_meta(g, e), meta_n = load_meta(g1, e1);  // of the packs g and g1
         // Packs of short rows have a path of their own in the fp64 kernels.  (In fp32 it measured
         // 2-3 % slower than the general path: the kernel is bound by the latency of a pack's
         // loads, not by its instructions, and the extra code costs registers.)
@@ -446,25 +469,14 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             }
             return most;
         };
-        uint32_t base[GP], basen[GP];  // positions stay 32-bit: nnz < 2^31
+        uint32_t base[GP];  // positions stay 32-bit: nnz < 2^31
         T done_acc[GP];
 #pragma unroll
         for (int q = 0; q < GP; q++) {
-            s0[q] = s1[q] = n[q] = s0n[q] = s1n[q] = 0;
-            base[q] = basen[q] = 0;
             done_slot[q] = -1;
             done_acc[q] = T(0);
-            if (in_pack(g, e, q)) {
-                s0[q] = uniform_load(L.group_slot, g + q);
-                s1[q] = uniform_load(L.group_slot, g + q + 1);
-                base[q] = (uint32_t)uniform_load(L.group_ptr, g + q);
-                n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
-            }
-            if (in_pack(g1, e1, q)) {
-                s0n[q] = uniform_load(L.group_slot, g1 + q);
-                s1n[q] = uniform_load(L.group_slot, g1 + q + 1);
-                basen[q] = (uint32_t)uniform_load(L.group_ptr, g1 + q);
-            }
+            meta_slots(meta, g, e, q, s0[q], s1[q]);
+            n[q] = s0[q] + lane < s1[q] ? L.seg_len[s0[q] + lane] : 0;
         }
         pack_longest = longest_in_pack(g, e);
         pack_longestn = longest_in_pack(g1, e1);
@@ -478,6 +490,11 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             g2 = draw_resolve(raw2, e2);  // drawn an iteration ago
             if (g == kNone && g1 == kNone && g2 == kNone) break;  // and this wavefront has stopped drawing
             raw2 = draw_issue();
+#pragma unroll
+            for (int q = 0; q < GP; q++) {
+                meta_slots(meta, g, e, q, s0[q], s1[q]);
+                base[q] = meta_base(meta, g, e, q);
+            }
             // A group with a row of more than heavy_rounds nonzeros would keep this wavefront busy
             // long after the rest of the worker has run dry: it goes on the worker's heavy list and
             // looks empty here (unless the list is full: then this wavefront walks it alone).  A
@@ -501,20 +518,16 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     }
                 }
             }
-            int32_t s0nn[GP], s1nn[GP], nn[GP], slot[GP];
+            int32_t nn[GP], slot[GP];
             const int32_t pack_longestnn = longest_in_pack(g2, e2);
-            uint32_t basenn[GP];
+            const uint32_t meta_nn = load_meta(g2, e2);
             T acc[GP];
-#pragma unroll
-            for (int q = 0; q < GP; q++) {
-                s0nn[q] = s1nn[q] = nn[q] = 0;
-                basenn[q] = 0;
-                if (in_pack(g2, e2, q)) {
-                    s0nn[q] = uniform_load(L.group_slot, g2 + q);
-                    s1nn[q] = uniform_load(L.group_slot, g2 + q + 1);
-                    basenn[q] = (uint32_t)uniform_load(L.group_ptr, g2 + q);
-                }
-            }
+            // lane lengths of group q of the pack g1
+            auto next_lengths = [&](int q) __attribute__((always_inline)) {
+                int32_t from, to;
+                meta_slots(meta_n, g1, e1, q, from, to);
+                return from + lane < to ? (int32_t)L.seg_len[from + lane] : 0;
+            };
             bool wide = false;
             if constexpr (GP == 1 && sizeof(T) == 4) {
                 const int32_t n0 = __builtin_amdgcn_readfirstlane(n[0]);
@@ -528,7 +541,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
                     WideBatch<CH, T> wb;
                     issue_wide<CH>(wb, L.col_local, data, chunk0, 0, base[0], run_end, lane);
                     if (done_slot[0] >= 0) partial[done_slot[0]] = done_acc[0];
-                    nn[0] = s0n[0] + lane < s1n[0] ? L.seg_len[s0n[0] + lane] : 0;
+                    nn[0] = next_lengths(0);
                     consume_wide<CH>(wb, xs, chunk0, 0, base[0], run_end, lane, a4);
                     for (uint32_t i0 = CH; i0 < n_chunks; i0 += CH) {
                         issue_wide<CH, false>(wb, L.col_local, data, chunk0, i0, base[0], run_end, lane);
@@ -570,7 +583,7 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 #pragma unroll
                 for (int q = 0; q < GP; q++) {
                     if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
-                    nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
+                    nn[q] = next_lengths(q);
                 }
                 if (pack_longest == 2) {
                     T x0[GP], x1[GP];
@@ -598,13 +611,15 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
 #pragma unroll
                 for (int q = 0; q < GP; q++) {
                     if (done_slot[q] >= 0) partial[done_slot[q]] = done_acc[q];
-                    nn[q] = s0n[q] + lane < s1n[q] ? L.seg_len[s0n[q] + lane] : 0;
+                    nn[q] = next_lengths(q);
                 }
 #pragma unroll
                 for (int q = 0; q < GP; q++) acc[q] = consume_batch<U>(bt[q], xs, n[q], 0);
 #pragma unroll
                 for (int q = 0; q < GP; q++) {  // rows longer than U, one group at a time
-                    walk_rounds(base[q], n[q], U, acc[q]);
+                    // (the test keeps what the compiler hoists out of the walk's loops, a dozen
+                    // values per group, off the path of the groups without such rows)
+                    if (__ballot(U < n[q])) walk_rounds(base[q], n[q], U, acc[q]);
                     slot[q] = s0[q] + lane < s1[q] ? s0[q] + lane : -1;
                 }
             }
@@ -612,10 +627,10 @@ __global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
             for (int q = 0; q < GP; q++) {
                 done_acc[q] = acc[q];
                 done_slot[q] = slot[q];
-                s0[q] = s0n[q]; s1[q] = s1n[q]; base[q] = basen[q]; n[q] = nn[q];
-                s0n[q] = s0nn[q]; s1n[q] = s1nn[q]; basen[q] = basenn[q];
-
+                n[q] = nn[q];
             }
+            meta = meta_n;
+            meta_n = meta_nn;
             g = g1; g1 = g2;
             e = e1; e1 = e2;
             pack_longest = pack_longestn; pack_longestn = pack_longestnn;
