@@ -39,6 +39,11 @@ struct Batch {
     int rounds;  // rounds of the batch in which some lane has a nonzero (they are the leading ones)
 };
 
+// a * b + c in one instruction (the value of a lane without an element in the round is zeroed
+// before it, one select instead of a select between a multiply and an add)
+__device__ __forceinline__ float fma_of(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fma_of(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
 // Issues the loads of rounds k .. k+U-1 and advances base past them.  No load is predicated: a
 // lane without an element in a round reads a neighbour's (or the position just behind the
 // round: inside the group, or inside the padding behind the last group) and drops the product.
@@ -53,10 +58,13 @@ __device__ __forceinline__ void issue_batch(Batch<U, T> &b, const uint16_t *__re
         b.c[u] = 0;
         b.v[u] = T(0);
         if (live) {  // wave-uniform: rounds past every row's end issue nothing
-            const uint32_t j = (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
-                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)live, base));
-            b.c[u] = __builtin_nontemporal_load(col_local + j);
-            b.v[u] = __builtin_nontemporal_load(data + j);
+            // the round's base stays in the scalar part of the address, the lane's rank among the
+            // live lanes is the 32-bit vector part: no 64-bit vector arithmetic per load
+            const uint32_t rank = (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)live, 0u));
+            const char *round_col = reinterpret_cast<const char *>(col_local) + ((uint64_t)base << 1);
+            const char *round_val = reinterpret_cast<const char *>(data) + (uint64_t)base * sizeof(T);
+            b.c[u] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(round_col + (rank << 1)));
+            b.v[u] = __builtin_nontemporal_load(reinterpret_cast<const T *>(round_val + rank * (uint32_t)sizeof(T)));
             base += (uint32_t)__popcll(live);
             b.rounds = u + 1;
         }
@@ -79,10 +87,7 @@ __device__ __forceinline__ T consume_batch(const Batch<U, T> &b, const T *xs, in
 #pragma unroll
                 for (int u = 0; u < Q; u++) xv[u] = xs[b.c[q0 + u]];
 #pragma unroll
-                for (int u = 0; u < Q; u++) {
-                    const T p = b.v[q0 + u] * xv[u];
-                    acc += k + q0 + u < n ? p : T(0);
-                }
+                for (int u = 0; u < Q; u++) acc = fma_of(k + q0 + u < n ? b.v[q0 + u] : T(0), xv[u], acc);
             }
         }
     } else {
@@ -90,10 +95,7 @@ __device__ __forceinline__ T consume_batch(const Batch<U, T> &b, const T *xs, in
 #pragma unroll
         for (int u = 0; u < U; u++) xv[u] = xs[b.c[u]];
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            const T p = b.v[u] * xv[u];
-            acc += k + u < n ? p : T(0);
-        }
+        for (int u = 0; u < U; u++) acc = fma_of(k + u < n ? b.v[u] : T(0), xv[u], acc);
     }
     return acc;
 }
