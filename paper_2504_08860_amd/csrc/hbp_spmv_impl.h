@@ -175,7 +175,9 @@ __device__ __forceinline__ void consume_wide(const WideBatch<CH, T> &b, const T 
 }
 
 template <int THREADS, int U, int GP, bool HEAVY, typename T>
-__global__ __launch_bounds__(THREADS) void k_spmv_part(Layout L,
+// (second launch bound: four wavefronts per SIMD, i.e. at most 128 vector registers per lane
+// whatever the workgroup size; with more, two 512-thread workers no longer fit a CU together)
+__global__ __launch_bounds__(THREADS, 4) void k_spmv_part(Layout L,
                                                        const T *__restrict__ x, T *__restrict__ partial,
                                                        T *__restrict__ y, uint32_t *__restrict__ col_ticket)
 {
