@@ -792,7 +792,25 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
                 }
                 return valid;
             };
-            for (int tile = wave; tile < tiles; tile += 4) {
+            // the first kKeep tiles of a wavefront (all of them up to R = 2048) keep their entry,
+            // counter and rank in registers for the scatter; tiles beyond are classified again
+            constexpr int kKeep = 8;
+            uint32_t kept_e[kKeep], kept_at[kKeep];  // kept_at: counter index << 6 | rank
+#pragma unroll
+            for (int t = 0; t < kKeep; t++) {
+                const int tile = wave + 4 * t;
+                kept_e[t] = kHole;
+                kept_at[t] = 0u;
+                if (tile < tiles) {
+                    uint32_t digit;
+                    uint64_t same;
+                    const bool valid = classify(tile, kept_e[t], digit, same);
+                    const uint32_t rank = (uint32_t)lanes_below(same);
+                    if (valid && rank == 0) cnt[digit * tiles + tile] = (uint32_t)__popcll(same);
+                    kept_at[t] = ((digit * (uint32_t)tiles + (uint32_t)tile) << 6) | rank;
+                }
+            }
+            for (int tile = wave + 4 * kKeep; tile < tiles; tile += 4) {
                 uint32_t e, digit;
                 uint64_t same;
                 const bool valid = classify(tile, e, digit, same);
@@ -800,7 +818,10 @@ __global__ __launch_bounds__(256) void k_order_block(const uint32_t *__restrict_
             }
             __syncthreads();
             scan_in_lds(cnt, 16 * tiles, sh_wave);
-            for (int tile = wave; tile < tiles; tile += 4) {
+#pragma unroll
+            for (int t = 0; t < kKeep; t++)
+                if (kept_e[t] != kHole) to[cnt[kept_at[t] >> 6] + (kept_at[t] & 63u)] = kept_e[t];
+            for (int tile = wave + 4 * kKeep; tile < tiles; tile += 4) {
                 uint32_t e, digit;
                 uint64_t same;
                 const bool valid = classify(tile, e, digit, same);
