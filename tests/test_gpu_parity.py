@@ -351,6 +351,31 @@ def test_block_ordering_paths(H, oracle, R, mode):
     check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=512, **kw)
 
 
+@pytest.mark.parametrize("f64", [False, True])
+@pytest.mark.parametrize("row_blocks,col_blocks", [(70, 5), (65, 40), (129, 2)])
+def test_fill_by_row_block(H, oracle, row_blocks, col_blocks, f64):
+    """Short row segments in large blocks over at least 64 row blocks: the build fills the blocks
+    row block by row block (several workgroups per row block, a number of row blocks that is no
+    multiple of 8, a ragged last one)."""
+    from workloads import CsrMatrix, widen_to_f64
+    rng = np.random.default_rng(row_blocks * 100 + col_blocks)
+    R, C = 512, 256
+    n_rows, n_cols = row_blocks * R - 499, col_blocks * C
+    per_block = rng.integers(1, 4, (n_rows, col_blocks))          # 1..3 nonzeros of every row in every column block
+    per_block[rng.random((n_rows, col_blocks)) < 0.05] = 0        # a few empty segments
+    starts = rng.integers(0, C - 3, (n_rows, col_blocks)) + np.arange(col_blocks)[None, :] * C
+    lens = per_block.sum(1)
+    ptr = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=ptr[1:])
+    col = np.concatenate([np.arange(s, s + k) for s, k in zip(starts.ravel(), per_block.ravel()) if k]).astype(np.int32)
+    m = CsrMatrix(name=f"fill_{row_blocks}x{col_blocks}", n_rows=n_rows, n_cols=n_cols, ptr=ptr, col=col,
+                  val=rng.standard_normal(len(col)).astype(np.float32), x=rng.uniform(-1, 1, n_cols).astype(np.float32))
+    if f64:
+        m = widen_to_f64(m)
+    info = check_against_oracle(H, oracle, m, rows_per_block=R, cols_per_block=C)
+    assert info.row_blocks == row_blocks and info.nnz < 4 * info.slots and info.slots >= 256 * info.blocks
+
+
 @pytest.mark.parametrize("R,C", [(64, 128), (512, 4096)])
 def test_plain_2d_partition(H, oracle, R, C):
     """HBP_FLAG_NO_REORDER: the plain 2D-partitioning method of Section 4 (no hash reorder)."""
